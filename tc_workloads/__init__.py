@@ -1,0 +1,165 @@
+"""Seeded synthetic inputs for the KV offload / upload path.
+
+This module serves both the CPU oracle and the HIP library with the *same* inputs
+and contains no part of the method: it only describes pool shapes, draws values and
+block ids, and scripts sequences of calls against whatever backend it is given.
+All randomness comes from ``numpy.random.Generator(PCG64(seed))`` (host side) or a
+seeded ``torch.Generator`` (device-side fills of pools too large to draw on the host).
+
+The pools stand in for the serving runs the paper measures on (Sec. 7.1, ShareGPT and
+AgentCode driven traffic on Qwen2.5 models): the path moves opaque bytes, so only the
+shapes matter.  Shapes follow Sec. 7.6 (16-token blocks, bf16, 64..320 blocks per
+request) scaled to the five benchmark configurations.
+"""
+from dataclasses import dataclass, replace
+
+import numpy as np
+
+BASE_SEED = 251018586
+
+
+def seed_for(config_index, salt=0):
+    return BASE_SEED + int(config_index) + 1000003 * int(salt)
+
+
+def rng_for(config_index, salt=0):
+    return np.random.Generator(np.random.PCG64(seed_for(config_index, salt)))
+
+
+@dataclass(frozen=True)
+class PoolShape:
+    name: str
+    num_layers: int
+    kv_heads: int
+    head_dim: int
+    block_size: int          # tokens per block
+    elem_bytes: int          # 2 = bf16, 1 = fp8
+    num_blocks: int          # NB
+    scales_per_block: int = 0  # 0, 1 or 2*num_layers fp32 words per block
+    dist: str = "normal"     # value distribution of the fill
+
+    @property
+    def planes(self):
+        return 2 * self.num_layers
+
+    @property
+    def page_bytes(self):
+        return self.block_size * self.kv_heads * self.head_dim * self.elem_bytes
+
+    @property
+    def pool_bytes(self):
+        return self.planes * self.num_blocks * self.page_bytes
+
+    def with_blocks(self, nb):
+        return replace(self, num_blocks=int(nb))
+
+
+# The five benchmark configurations (index = position in the list).
+CONFIGS = [
+    PoolShape("tiny", 2, 4, 64, 16, 2, 256, 0, "uniform"),
+    PoolShape("llama3-8b", 32, 8, 128, 16, 2, 16384, 0, "normal"),
+    PoolShape("llama3-8b-64agents", 32, 8, 128, 16, 2, 16384, 0, "normal"),
+    PoolShape("qwen-32b-trace", 64, 8, 128, 16, 2, 16384, 0, "normal"),
+    PoolShape("70b-fp8", 80, 8, 128, 32, 1, 32768, 160, "fp8"),
+]
+# The shape the paper's own measurement uses (Sec. 7.6: Qwen2.5-14B, 3 MiB per block).
+PAPER_14B = PoolShape("qwen2.5-14b", 48, 8, 128, 16, 2, 16384, 0, "normal")
+
+
+# --------------------------------------------------------------------------- values
+def _f32_to_bf16_bits(x):
+    """Round-to-nearest-even float32 -> bfloat16 bit patterns (uint16)."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    rounded = u + (np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1)))
+    return (rounded >> np.uint32(16)).astype(np.uint16)
+
+
+def make_pool_host(shape, rng):
+    """Pool bytes on the host (small pools only): uint8 array of shape.pool_bytes."""
+    n_elem = shape.pool_bytes // shape.elem_bytes
+    if shape.dist == "uniform":
+        vals = rng.uniform(-1.0, 1.0, size=n_elem).astype(np.float32)
+    elif shape.dist in ("normal", "fp8"):
+        vals = rng.standard_normal(size=n_elem, dtype=np.float32)
+    else:
+        raise ValueError(shape.dist)
+    if shape.elem_bytes == 2:
+        return _f32_to_bf16_bits(vals).view(np.uint8).copy()
+    if shape.elem_bytes == 1:
+        import torch
+        # OCP e4m3 ("fn") bytes, one scale per page: amax / 448
+        t = torch.from_numpy(vals).view(shape.planes * shape.num_blocks, -1)
+        amax = t.abs().amax(dim=1, keepdim=True).clamp_min(1e-12)
+        q = (t * (448.0 / amax)).to(torch.float8_e4m3fn)
+        return q.view(torch.uint8).numpy().reshape(-1).copy()
+    raise ValueError(shape.elem_bytes)
+
+
+def make_scales_host(shape, rng):
+    """Scale words [S][NB] as raw uint32 bit patterns of positive fp32 values."""
+    if not shape.scales_per_block:
+        return None
+    s = rng.uniform(1e-3, 4.0, size=shape.scales_per_block * shape.num_blocks).astype(np.float32)
+    return s.view(np.uint32).copy()
+
+
+def make_pool_device(shape, seed, device="cuda:0"):
+    """Fill a full-size pool on the device with a seeded torch generator; returns uint8 tensor."""
+    import torch
+    g = torch.Generator(device=device)
+    g.manual_seed(int(seed))
+    pool = torch.empty(shape.pool_bytes, dtype=torch.uint8, device=device)
+    plane_elems = shape.num_blocks * shape.page_bytes // shape.elem_bytes
+    view = pool.view(shape.planes, shape.num_blocks * shape.page_bytes)
+    for p in range(shape.planes):
+        if shape.elem_bytes == 2:
+            dst = view[p].view(torch.bfloat16)
+            if shape.dist == "uniform":
+                dst.uniform_(-1.0, 1.0, generator=g)
+            else:
+                dst.normal_(0.0, 1.0, generator=g)
+        else:
+            x = torch.empty(plane_elems, dtype=torch.bfloat16, device=device).normal_(0.0, 1.0, generator=g)
+            x = x.view(shape.num_blocks, -1).float()
+            amax = x.abs().amax(dim=1, keepdim=True).clamp_min(1e-12)
+            view[p].copy_((x * (448.0 / amax)).to(torch.float8_e4m3fn).view(torch.uint8).reshape(-1))
+            del x
+    return pool
+
+
+def make_scales_device(shape, seed, device="cuda:0"):
+    import torch
+    if not shape.scales_per_block:
+        return None
+    g = torch.Generator(device=device)
+    g.manual_seed(int(seed) + 77)
+    s = torch.empty(shape.scales_per_block * shape.num_blocks, dtype=torch.float32, device=device)
+    s.uniform_(1e-3, 4.0, generator=g)
+    return s
+
+
+# --------------------------------------------------------------------------- ids
+def pick_ids(rng, num_blocks, n, exclude=()):
+    """n distinct block ids, uniformly at random, none from `exclude`; int32."""
+    perm = rng.permutation(num_blocks)
+    if len(exclude):
+        mask = np.ones(num_blocks, dtype=bool)
+        mask[np.asarray(exclude, dtype=np.int64)] = False
+        perm = perm[mask[perm]]
+    if n > perm.size:
+        raise ValueError("not enough blocks")
+    return perm[:n].astype(np.int32)
+
+
+def lognormal_contexts(rng, n_agents, median=2048, sigma=0.8, cap=16384, floor=1):
+    """Context lengths in tokens: lognormal(median, sigma), capped."""
+    x = rng.lognormal(mean=np.log(median), sigma=sigma, size=n_agents)
+    return np.clip(np.rint(x), floor, cap).astype(np.int64)
+
+
+def uniform_contexts(rng, n_agents, lo=1024, hi=32768):
+    return rng.integers(lo, hi + 1, size=n_agents).astype(np.int64)
+
+
+def blocks_of(tokens, block_size):
+    return -(-np.asarray(tokens, dtype=np.int64) // block_size)
