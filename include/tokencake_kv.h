@@ -1,0 +1,172 @@
+/*
+ * tokencake_kv — paged KV-cache offload / upload for one AMD MI355X (gfx950).
+ *
+ * The library implements the data path of the paper's Temporal Scheduler
+ * (Sec. 4.1 runtime event loop; Sec. 6.3 "CPU Migration Infrastructure"):
+ * while an agent waits on a function call its idle KV blocks are copied to
+ * pinned CPU memory (offload), and before the call is predicted to finish they
+ * are copied back into newly reserved GPU blocks and the agent's block table is
+ * pointed at them (upload).  It also keeps the block bookkeeping that Sec. 6.3
+ * describes: a GPU free list with reference counts and the pending-free rule,
+ * and a CPU pool of fixed-size slots recycled through a free list.
+ *
+ * Layouts (the paper fixes none; sizes follow Sec. 7.6):
+ *   planes      P = 2 * num_layers, plane p = 2*layer + kv   (kv: 0 = K, 1 = V)
+ *   KV pool     DEVICE memory, pool[p][block][page_bytes]   (plane-major)
+ *   scales      DEVICE memory or NULL, scales[s][block], 32-bit words,
+ *               scales_per_block in {0, 1, P}
+ *   host record rec = roundup256(P*page_bytes + 4*scales_per_block) bytes per block:
+ *               [page 0 | ... | page P-1 | scale words | zero pad]
+ *   host buffer HOST pinned memory, n consecutive records, record j = block ids[j]
+ *
+ * Conventions
+ *   - every function returns TC_OK (0) or a negative TC_ERR_* code; nothing throws
+ *     or aborts.  All validation happens before anything is enqueued or any state
+ *     changes: an error return means the call had no effect.
+ *   - id arrays are HOST pointers (int32) and are copied before the call returns.
+ *   - tc_offload / tc_upload are asynchronous: they return after enqueueing on
+ *     `stream` (a hipStream_t passed as void*; NULL = the default stream).  Work
+ *     later enqueued on the same stream is ordered after them; the host buffer /
+ *     the pool may be read once the stream (or tc_sync) has completed.
+ *   - the caller owns the pool, the scales, block tables and any host buffer not
+ *     obtained from tc_host_alloc.  The context owns its staging ring and arena.
+ *   - one context serves one GPU (the device current at tc_create); calls on one
+ *     context are serialised by an internal mutex.
+ */
+#ifndef TOKENCAKE_KV_H
+#define TOKENCAKE_KV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TC_OK 0
+#define TC_ERR_INVAL (-1)      /* bad argument, unallocated block, over-release      */
+#define TC_ERR_RANGE (-2)      /* block id < 0 or >= num_blocks                      */
+#define TC_ERR_DUP (-3)        /* the same block id twice in one transfer            */
+#define TC_ERR_SHARED (-4)     /* block has more than one owner and must not move    */
+#define TC_ERR_NOMEM (-5)      /* not enough free GPU blocks (all-or-nothing)        */
+#define TC_ERR_HOST_NOMEM (-6) /* pinned arena has no run of slots that fits         */
+#define TC_ERR_NOT_PINNED (-7) /* host buffer is not pinned / device ptr is not device */
+#define TC_ERR_HIP (-8)        /* a HIP runtime call failed                          */
+
+typedef struct tc_ctx tc_ctx;
+
+typedef struct {
+    void *kv_base;              /* DEVICE, 256-B aligned, 2*num_layers*num_blocks*page_bytes bytes */
+    void *scales;               /* DEVICE or NULL, scales_per_block*num_blocks 32-bit words        */
+    uint32_t num_layers;
+    uint32_t num_blocks;
+    uint32_t page_bytes;        /* block_size * kv_heads * head_dim * elem bytes; multiple of 16   */
+    uint32_t block_size_tokens;
+    uint32_t scales_per_block;  /* 0, 1 or 2*num_layers                                            */
+} tc_pool_desc;
+
+typedef struct {
+    uint64_t host_arena_bytes;  /* pinned arena, allocated once; 0 = none (caller brings buffers)  */
+    uint64_t staging_bytes;     /* device staging ring in total; 0 = default                       */
+    uint32_t staging_slots;     /* ring depth, >= 2; 0 = default                                   */
+    uint32_t max_grid;          /* cap on workgroups per gather/scatter launch; 0 = one per tile   */
+    uint32_t ramp;              /* 1 = start an offload / end an upload with small chunks          */
+    uint32_t reserved;
+} tc_opts;
+
+typedef struct {
+    const int32_t *block_ids;   /* HOST, n ids: sources (offload) or destinations (upload)         */
+    uint32_t n;
+    void *host_buf;             /* HOST pinned, n records                                          */
+    int32_t *block_table;       /* DEVICE or NULL, upload only: first table entry to rewrite       */
+} tc_xfer_desc;
+
+typedef struct {
+    uint32_t gpu_blocks_total, gpu_blocks_free, gpu_blocks_used, gpu_blocks_pending_free, gpu_blocks_shared;
+    uint32_t ops_in_flight;
+    uint64_t host_slots_total, host_slots_used;
+    uint64_t n_offloads, n_uploads;           /* calls (a batch counts once)                       */
+    uint64_t blocks_offloaded, blocks_uploaded;
+    uint64_t bytes_offloaded, bytes_uploaded; /* host-record bytes                                 */
+    /* filled for retired transfers while profiling is on (tc_set_profiling) */
+    uint64_t gather_launches, scatter_launches;
+    uint64_t gather_bytes, scatter_bytes;     /* record bytes the timed launches moved one way     */
+    double gather_ms, scatter_ms;             /* sum of per-launch durations from HIP events       */
+} tc_stats_t;
+
+/* ---- life cycle ------------------------------------------------------------------------- */
+/* Binds a pool (Sec. 6.3: the block pool owns the GPU<->CPU mapping).  Allocates the staging
+ * ring, the pinned arena and a private copy stream; `opts` may be NULL for defaults. */
+int tc_create(const tc_pool_desc *pool, const tc_opts *opts, tc_ctx **out);
+/* Waits for every transfer in flight, then frees what the context owns. */
+int tc_destroy(tc_ctx *ctx);
+/* Host bytes per block (Sec. 7.6: 48 layers x K,V x 8 x 128 x 16 tokens x 2 B = 3 MiB). */
+uint64_t tc_record_bytes(const tc_ctx *ctx);
+const char *tc_strerror(int code);
+
+/* ---- GPU block bookkeeping (Sec. 6.3) --------------------------------------------------- */
+/* Pops n ids off the LIFO free list (first hand-out is 0,1,2,...); reference count := 1.
+ * TC_ERR_NOMEM and no change when fewer than n blocks are free. */
+int tc_alloc(tc_ctx *ctx, uint32_t n, int32_t *out_ids /* HOST, n */);
+/* Claims exactly these ids ("reuses the original GPU block when possible"); all must be free. */
+int tc_alloc_at(tc_ctx *ctx, const int32_t *ids, uint32_t n);
+/* One more owner for each id (shared prefix blocks). */
+int tc_ref(tc_ctx *ctx, const int32_t *ids, uint32_t n);
+/* Drops one owner per id.  At zero owners the block is free, unless a transfer touching it is
+ * still in flight: then it is pending-free and becomes free when tc_poll / tc_sync retire that
+ * transfer ("return to the free pool only after the transfer completes"). */
+int tc_free(tc_ctx *ctx, const int32_t *ids, uint32_t n);
+/* Copies the ids that have exactly one owner, order kept; *m = how many. */
+int tc_filter_private(tc_ctx *ctx, const int32_t *ids, uint32_t n, int32_t *out_ids, uint32_t *m);
+
+/* ---- CPU block pool (Sec. 6.3: fixed-size blocks recycled, never returned to the OS) ----- */
+/* n_blocks consecutive record slots from the pinned arena (first fit); n_blocks = 0 gives NULL. */
+int tc_host_alloc(tc_ctx *ctx, uint32_t n_blocks, void **host_buf);
+/* host_buf must be a pointer tc_host_alloc returned (NULL is a no-op).  If a transfer using it
+ * is in flight the slots are recycled when that transfer retires. */
+int tc_host_free(tc_ctx *ctx, void *host_buf);
+
+/* ---- transfers (Sec. 4.1, Sec. 6.3: issued asynchronously on a dedicated stream) --------- */
+/* Offload: record j of host_buf <- block block_ids[j] (all planes, then scale words, then zero
+ * pad).  Each block must be allocated and have exactly one owner (TC_ERR_INVAL / TC_ERR_SHARED);
+ * ids must be distinct.  The pool and the block table are not written.  n = 0 is a no-op. */
+int tc_offload(tc_ctx *ctx, const int32_t *block_ids, uint32_t n, void *host_buf, void *stream);
+/* Upload: block new_block_ids[i] <- record i of host_buf, then block_table[i] = new_block_ids[i]
+ * for i < n, written on `stream` after the data ("restores the GPU mapping").  block_table may
+ * be NULL.  Same id rules as tc_offload. */
+int tc_upload(tc_ctx *ctx, const void *host_buf, const int32_t *new_block_ids, uint32_t n,
+              int32_t *block_table, void *stream);
+/* Several agents in one call: their records share staging chunks and kernel launches.  Ids must
+ * be distinct across the whole batch. */
+int tc_offload_batch(tc_ctx *ctx, const tc_xfer_desc *descs, uint32_t n_descs, void *stream);
+int tc_upload_batch(tc_ctx *ctx, const tc_xfer_desc *descs, uint32_t n_descs, void *stream);
+
+/* Retires completed transfers in issue order (pending-free -> free); never blocks. */
+int tc_poll(tc_ctx *ctx);
+/* Waits for every transfer issued so far, then retires them all. */
+int tc_sync(tc_ctx *ctx);
+
+/* ---- observation ------------------------------------------------------------------------ */
+int tc_stats(tc_ctx *ctx, tc_stats_t *out);
+/* on != 0: bracket every gather / scatter launch with timing events on its stream. */
+int tc_set_profiling(tc_ctx *ctx, int on);
+/* The pinned arena (NULL / 0 without one). */
+void *tc_arena_base(const tc_ctx *ctx);
+
+/* ---- measurement helpers: not on the hot path ------------------------------------------- */
+/* dst[i] = src[i]: contiguous DEVICE->DEVICE copy with the gather kernel's access width; the
+ * "achievable HBM" reference and the calibration kernel for the traffic counters.
+ * bytes must be a multiple of 16. */
+int tc_copy_contiguous(void *dst, const void *src, uint64_t bytes, void *stream);
+/* `iters` passes of a[i] = b[i] + s*c[i] over n fp32 (DEVICE): the HBM-streaming kernel that the
+ * copy stream is overlapped with.  n must be a multiple of 4. */
+int tc_hbm_stream(float *a, const float *b, const float *c, uint64_t n, float s, uint32_t iters, void *stream);
+/* Comparators without a gather kernel: mode 0 = one hipMemcpyAsync per page, mode 1 = one
+ * hipMemcpy2DAsync per block.  direction 0 = offload, 1 = upload.  No bookkeeping. */
+int tc_naive_transfer(tc_ctx *ctx, const int32_t *block_ids, uint32_t n, void *host_buf, int mode,
+                      int direction, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TOKENCAKE_KV_H */

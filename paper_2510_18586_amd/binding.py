@@ -1,0 +1,293 @@
+"""ctypes binding of include/tokencake_kv.h: same names, argument marshalling only.
+
+Pointers may be given as ints, torch tensors (``data_ptr()``), numpy arrays or None; id arrays
+must be int32 numpy arrays (host); streams may be ``torch.cuda.Stream``, a raw handle or None.
+Functions return the library's status code unchanged unless noted; ``check(rc)`` raises.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+from . import build as _build
+
+__all__ = [
+    "TC_OK", "TC_ERR_INVAL", "TC_ERR_RANGE", "TC_ERR_DUP", "TC_ERR_SHARED", "TC_ERR_NOMEM",
+    "TC_ERR_HOST_NOMEM", "TC_ERR_NOT_PINNED", "TC_ERR_HIP",
+    "TcError", "check", "tc_pool_desc", "tc_opts", "tc_xfer_desc", "tc_stats_t", "library_path",
+    "tc_create", "tc_destroy", "tc_record_bytes", "tc_strerror", "tc_alloc", "tc_alloc_at", "tc_ref",
+    "tc_free", "tc_filter_private", "tc_host_alloc", "tc_host_free", "tc_offload", "tc_upload",
+    "tc_offload_batch", "tc_upload_batch", "tc_poll", "tc_sync", "tc_stats", "tc_set_profiling",
+    "tc_arena_base", "tc_copy_contiguous", "tc_hbm_stream", "tc_naive_transfer",
+]
+
+TC_OK = 0
+TC_ERR_INVAL, TC_ERR_RANGE, TC_ERR_DUP, TC_ERR_SHARED = -1, -2, -3, -4
+TC_ERR_NOMEM, TC_ERR_HOST_NOMEM, TC_ERR_NOT_PINNED, TC_ERR_HIP = -5, -6, -7, -8
+
+
+class tc_pool_desc(ctypes.Structure):
+    _fields_ = [
+        ("kv_base", ctypes.c_void_p), ("scales", ctypes.c_void_p),
+        ("num_layers", ctypes.c_uint32), ("num_blocks", ctypes.c_uint32),
+        ("page_bytes", ctypes.c_uint32), ("block_size_tokens", ctypes.c_uint32),
+        ("scales_per_block", ctypes.c_uint32),
+    ]
+
+
+class tc_opts(ctypes.Structure):
+    _fields_ = [
+        ("host_arena_bytes", ctypes.c_uint64), ("staging_bytes", ctypes.c_uint64),
+        ("staging_slots", ctypes.c_uint32), ("max_grid", ctypes.c_uint32),
+        ("ramp", ctypes.c_uint32), ("reserved", ctypes.c_uint32),
+    ]
+
+
+class tc_xfer_desc(ctypes.Structure):
+    _fields_ = [
+        ("block_ids", ctypes.c_void_p), ("n", ctypes.c_uint32),
+        ("host_buf", ctypes.c_void_p), ("block_table", ctypes.c_void_p),
+    ]
+
+
+class tc_stats_t(ctypes.Structure):
+    _fields_ = [
+        ("gpu_blocks_total", ctypes.c_uint32), ("gpu_blocks_free", ctypes.c_uint32),
+        ("gpu_blocks_used", ctypes.c_uint32), ("gpu_blocks_pending_free", ctypes.c_uint32),
+        ("gpu_blocks_shared", ctypes.c_uint32), ("ops_in_flight", ctypes.c_uint32),
+        ("host_slots_total", ctypes.c_uint64), ("host_slots_used", ctypes.c_uint64),
+        ("n_offloads", ctypes.c_uint64), ("n_uploads", ctypes.c_uint64),
+        ("blocks_offloaded", ctypes.c_uint64), ("blocks_uploaded", ctypes.c_uint64),
+        ("bytes_offloaded", ctypes.c_uint64), ("bytes_uploaded", ctypes.c_uint64),
+        ("gather_launches", ctypes.c_uint64), ("scatter_launches", ctypes.c_uint64),
+        ("gather_bytes", ctypes.c_uint64), ("scatter_bytes", ctypes.c_uint64),
+        ("gather_ms", ctypes.c_double), ("scatter_ms", ctypes.c_double),
+    ]
+
+    def as_dict(self):
+        return {k: getattr(self, k) for k, _ in self._fields_}
+
+
+class TcError(RuntimeError):
+    def __init__(self, code):
+        super().__init__(f"tokencake_kv error {code}: {tc_strerror(code)}")
+        self.code = code
+
+
+def check(rc):
+    if rc != TC_OK:
+        raise TcError(rc)
+    return rc
+
+
+_lib = None
+
+
+def library_path():
+    return _build.LIB
+
+
+def _load():
+    """Loads the built library; builds it first only when none exists.  Never falls back."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_build.LIB):
+        _build.build()
+    try:
+        import torch  # noqa: F401  the process must share torch's HIP runtime, so it is loaded first
+    except ImportError:
+        pass
+    lib = ctypes.CDLL(_build.LIB)
+    vp, u32, u64, ci = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint64, ctypes.c_int
+    sig = {
+        "tc_create": (ci, [ctypes.POINTER(tc_pool_desc), ctypes.POINTER(tc_opts), ctypes.POINTER(vp)]),
+        "tc_destroy": (ci, [vp]),
+        "tc_record_bytes": (u64, [vp]),
+        "tc_strerror": (ctypes.c_char_p, [ci]),
+        "tc_alloc": (ci, [vp, u32, vp]),
+        "tc_alloc_at": (ci, [vp, vp, u32]),
+        "tc_ref": (ci, [vp, vp, u32]),
+        "tc_free": (ci, [vp, vp, u32]),
+        "tc_filter_private": (ci, [vp, vp, u32, vp, ctypes.POINTER(u32)]),
+        "tc_host_alloc": (ci, [vp, u32, ctypes.POINTER(vp)]),
+        "tc_host_free": (ci, [vp, vp]),
+        "tc_offload": (ci, [vp, vp, u32, vp, vp]),
+        "tc_upload": (ci, [vp, vp, vp, u32, vp, vp]),
+        "tc_offload_batch": (ci, [vp, ctypes.POINTER(tc_xfer_desc), u32, vp]),
+        "tc_upload_batch": (ci, [vp, ctypes.POINTER(tc_xfer_desc), u32, vp]),
+        "tc_poll": (ci, [vp]),
+        "tc_sync": (ci, [vp]),
+        "tc_stats": (ci, [vp, ctypes.POINTER(tc_stats_t)]),
+        "tc_set_profiling": (ci, [vp, ci]),
+        "tc_arena_base": (vp, [vp]),
+        "tc_copy_contiguous": (ci, [vp, vp, u64, vp]),
+        "tc_hbm_stream": (ci, [vp, vp, vp, u64, ctypes.c_float, u32, vp]),
+        "tc_naive_transfer": (ci, [vp, vp, u32, vp, ci, ci, vp]),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(lib, name)
+        fn.restype, fn.argtypes = res, args
+    _lib = lib
+    return lib
+
+
+# ------------------------------------------------------------------ marshalling
+def _ptr(x):
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    if isinstance(x, np.ndarray):
+        return x.ctypes.data
+    if hasattr(x, "data_ptr"):
+        return x.data_ptr()
+    if isinstance(x, ctypes.c_void_p):
+        return x.value
+    raise TypeError(f"cannot take the address of {type(x).__name__}")
+
+
+def _ids(ids):
+    a = np.ascontiguousarray(ids, dtype=np.int32)
+    return a, (a.ctypes.data if a.size else None), int(a.size)
+
+
+def _stream(s):
+    if s is None:
+        return None
+    if isinstance(s, int):
+        return s
+    return s.cuda_stream
+
+
+# ------------------------------------------------------------------ the calls
+def tc_create(kv_base, scales, num_layers, num_blocks, page_bytes, block_size_tokens, scales_per_block=0,
+              host_arena_bytes=0, staging_bytes=0, staging_slots=0, max_grid=0, ramp=0):
+    """Returns (rc, ctx); ctx is an opaque handle (int) or None."""
+    desc = tc_pool_desc(_ptr(kv_base), _ptr(scales), num_layers, num_blocks, page_bytes, block_size_tokens,
+                        scales_per_block)
+    opts = tc_opts(host_arena_bytes, staging_bytes, staging_slots, max_grid, ramp, 0)
+    out = ctypes.c_void_p()
+    rc = _load().tc_create(ctypes.byref(desc), ctypes.byref(opts), ctypes.byref(out))
+    return rc, out.value
+
+
+def tc_destroy(ctx):
+    return _load().tc_destroy(ctx)
+
+
+def tc_record_bytes(ctx):
+    return int(_load().tc_record_bytes(ctx))
+
+
+def tc_strerror(code):
+    return _load().tc_strerror(code).decode()
+
+
+def tc_alloc(ctx, n):
+    """Returns (rc, ids) with ids an int32 numpy array (empty on failure)."""
+    out = np.empty(n, dtype=np.int32)
+    rc = _load().tc_alloc(ctx, n, out.ctypes.data if n else None)
+    return rc, (out if rc == TC_OK else out[:0])
+
+
+def tc_alloc_at(ctx, ids):
+    a, p, n = _ids(ids)
+    return _load().tc_alloc_at(ctx, p, n)
+
+
+def tc_ref(ctx, ids):
+    a, p, n = _ids(ids)
+    return _load().tc_ref(ctx, p, n)
+
+
+def tc_free(ctx, ids):
+    a, p, n = _ids(ids)
+    return _load().tc_free(ctx, p, n)
+
+
+def tc_filter_private(ctx, ids):
+    """Returns (rc, private_ids)."""
+    a, p, n = _ids(ids)
+    out = np.empty(n, dtype=np.int32)
+    m = ctypes.c_uint32(0)
+    rc = _load().tc_filter_private(ctx, p, n, out.ctypes.data if n else None, ctypes.byref(m))
+    return rc, out[: m.value].copy()
+
+
+def tc_host_alloc(ctx, n_blocks):
+    """Returns (rc, address) — address is an int, or None for n_blocks = 0 / failure."""
+    out = ctypes.c_void_p()
+    rc = _load().tc_host_alloc(ctx, n_blocks, ctypes.byref(out))
+    return rc, out.value
+
+
+def tc_host_free(ctx, host_buf):
+    return _load().tc_host_free(ctx, _ptr(host_buf))
+
+
+def tc_offload(ctx, block_ids, host_buf, stream=None):
+    a, p, n = _ids(block_ids)
+    return _load().tc_offload(ctx, p, n, _ptr(host_buf), _stream(stream))
+
+
+def tc_upload(ctx, host_buf, new_block_ids, block_table=None, stream=None):
+    a, p, n = _ids(new_block_ids)
+    return _load().tc_upload(ctx, _ptr(host_buf), p, n, _ptr(block_table), _stream(stream))
+
+
+def _descs(items):
+    """items: iterable of (ids, host_buf[, block_table])."""
+    keep = []
+    arr = (tc_xfer_desc * len(items))()
+    for i, it in enumerate(items):
+        a, p, n = _ids(it[0])
+        keep.append(a)
+        arr[i] = tc_xfer_desc(p, n, _ptr(it[1]), _ptr(it[2]) if len(it) > 2 else None)
+    return keep, arr
+
+
+def tc_offload_batch(ctx, items, stream=None):
+    keep, arr = _descs(items)
+    return _load().tc_offload_batch(ctx, arr, len(items), _stream(stream))
+
+
+def tc_upload_batch(ctx, items, stream=None):
+    keep, arr = _descs(items)
+    return _load().tc_upload_batch(ctx, arr, len(items), _stream(stream))
+
+
+def tc_poll(ctx):
+    return _load().tc_poll(ctx)
+
+
+def tc_sync(ctx):
+    return _load().tc_sync(ctx)
+
+
+def tc_stats(ctx):
+    """Returns (rc, tc_stats_t)."""
+    st = tc_stats_t()
+    rc = _load().tc_stats(ctx, ctypes.byref(st))
+    return rc, st
+
+
+def tc_set_profiling(ctx, on):
+    return _load().tc_set_profiling(ctx, int(bool(on)))
+
+
+def tc_arena_base(ctx):
+    return _load().tc_arena_base(ctx)
+
+
+def tc_copy_contiguous(dst, src, nbytes, stream=None):
+    return _load().tc_copy_contiguous(_ptr(dst), _ptr(src), nbytes, _stream(stream))
+
+
+def tc_hbm_stream(a, b, c, n, s=0.5, iters=1, stream=None):
+    return _load().tc_hbm_stream(_ptr(a), _ptr(b), _ptr(c), n, s, iters, _stream(stream))
+
+
+def tc_naive_transfer(ctx, block_ids, host_buf, mode, direction, stream=None):
+    a, p, n = _ids(block_ids)
+    return _load().tc_naive_transfer(ctx, p, n, _ptr(host_buf), mode, direction, _stream(stream))

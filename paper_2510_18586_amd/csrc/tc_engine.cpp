@@ -1,0 +1,733 @@
+// Transfer engine and C ABI of tokencake_kv (see include/tokencake_kv.h for the contract).
+//
+// Offload (paper Sec. 4.1 / 6.3: a stalled agent's KV is copied to CPU memory asynchronously on a
+// dedicated stream) runs as a two-stage pipeline over a ring of device staging chunks:
+//     gather_pages (caller's stream)  ->  one contiguous D2H DMA per agent segment (copy stream)
+// Upload is the mirror image:
+//     H2D DMA (copy stream)  ->  scatter_pages (caller's stream)  ->  rewrite_table
+// Events order the two streams per staging slot, so chunk c+1 is gathered while chunk c crosses
+// the host link.  The block bookkeeping (tc_blocks.h) is updated under one mutex; a transfer
+// holds its blocks "in flight" until tc_poll / tc_sync see its completion event.
+#include <cstdio>
+#include <cstring>
+#include <deque>
+#include <mutex>
+#include <new>
+#include <vector>
+
+#include <hip/hip_runtime_api.h>
+
+#include "tc_blocks.h"
+#include "tc_kernels.h"
+#include "tokencake_kv.h"
+
+namespace {
+
+constexpr uint64_t kDefaultSlotBytes = 128ull << 20;
+constexpr uint32_t kDefaultSlots = 3;
+
+struct Slot {
+    char *buf = nullptr;
+    hipEvent_t mid = nullptr;   // producer of the slot's content finished
+    hipEvent_t last = nullptr;  // last consumer finished: the slot may be overwritten
+    bool used = false;
+};
+
+struct Timed {
+    hipEvent_t t0, t1;
+    uint64_t bytes;
+    bool gather;
+};
+
+struct Op {
+    hipEvent_t done = nullptr;
+    hipEvent_t entry = nullptr;
+    std::vector<int32_t> ids;
+    std::vector<uint64_t> arena_starts;
+    uint64_t ring_consumed = 0;
+    std::vector<Timed> timed;
+};
+
+struct Segment {  // one agent's run of records inside the concatenated list
+    uint64_t first;  // index of its first record in the list
+    uint32_t n;
+    char *host;
+    int32_t *table;
+};
+
+}  // namespace
+
+struct tc_ctx {
+    std::mutex mu;
+    tc_pool_desc pool{};
+    tc_opts opts{};
+    tc::PageGeom geom{};
+    uint64_t rec = 0;
+    tc::BlockPool *blocks = nullptr;
+    tc::HostArena *arena = nullptr;
+    char *arena_base = nullptr;
+    uint64_t arena_bytes = 0;
+
+    char *staging = nullptr;
+    uint64_t slot_bytes = 0;
+    uint32_t slot_blocks = 0;
+    std::vector<Slot> slots;
+    uint32_t next_slot = 0;
+    hipStream_t dma = nullptr;
+
+    int32_t *ids_host = nullptr;  // pinned ring
+    int32_t *ids_dev = nullptr;   // device ring
+    uint64_t ring_cap = 0, ring_tail = 0, ring_used = 0;
+
+    std::deque<Op> ops;
+    std::vector<hipEvent_t> sync_events, time_events;  // recycled
+    bool profiling = false;
+    tc_stats_t st{};
+};
+
+namespace {
+
+#define HIP_TRY(expr)                                                                              \
+    do {                                                                                           \
+        hipError_t e_ = (expr);                                                                    \
+        if (e_ != hipSuccess) {                                                                    \
+            std::fprintf(stderr, "tokencake_kv: %s failed: %s (%s:%d)\n", #expr, hipGetErrorString(e_), \
+                         __FILE__, __LINE__);                                                      \
+            return TC_ERR_HIP;                                                                     \
+        }                                                                                          \
+    } while (0)
+
+int get_event(tc_ctx *c, bool timing, hipEvent_t *out)
+{
+    auto &poolv = timing ? c->time_events : c->sync_events;
+    if (!poolv.empty()) {
+        *out = poolv.back();
+        poolv.pop_back();
+        return TC_OK;
+    }
+    HIP_TRY(hipEventCreateWithFlags(out, timing ? hipEventDefault : hipEventDisableTiming));
+    return TC_OK;
+}
+
+void put_event(tc_ctx *c, bool timing, hipEvent_t e)
+{
+    if (e) (timing ? c->time_events : c->sync_events).push_back(e);
+}
+
+bool is_pinned_host(tc_ctx *c, const void *p, uint64_t bytes)
+{
+    const char *b = static_cast<const char *>(p);
+    if (c->arena_base && b >= c->arena_base && b + bytes <= c->arena_base + c->arena_bytes) return true;
+    for (const char *q : {b, b + (bytes ? bytes - 1 : 0)}) {
+        hipPointerAttribute_t a;
+        if (hipPointerGetAttributes(&a, q) != hipSuccess) {
+            (void)hipGetLastError();
+            return false;
+        }
+        if (a.type != hipMemoryTypeHost) return false;
+    }
+    return true;
+}
+
+bool is_device_ptr(const void *p)
+{
+    hipPointerAttribute_t a;
+    if (hipPointerGetAttributes(&a, p) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    return a.type == hipMemoryTypeDevice;
+}
+
+// The oldest transfer is known to be complete: release what it held.
+int retire_front(tc_ctx *c)
+{
+    Op &op = c->ops.front();
+    c->blocks->end_transfer(op.ids.data(), uint32_t(op.ids.size()));
+    for (uint64_t s : op.arena_starts) c->arena->end_transfer(s);
+    c->ring_used -= op.ring_consumed;
+    for (Timed &t : op.timed) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, t.t0, t.t1) == hipSuccess) {
+            if (t.gather) {
+                c->st.gather_launches++;
+                c->st.gather_bytes += t.bytes;
+                c->st.gather_ms += ms;
+            } else {
+                c->st.scatter_launches++;
+                c->st.scatter_bytes += t.bytes;
+                c->st.scatter_ms += ms;
+            }
+        } else {
+            (void)hipGetLastError();
+        }
+        put_event(c, true, t.t0);
+        put_event(c, true, t.t1);
+    }
+    put_event(c, false, op.done);
+    put_event(c, false, op.entry);
+    c->ops.pop_front();
+    return TC_OK;
+}
+
+int poll_locked(tc_ctx *c)
+{
+    while (!c->ops.empty()) {
+        hipError_t e = hipEventQuery(c->ops.front().done);
+        if (e == hipErrorNotReady) {
+            (void)hipGetLastError();
+            break;
+        }
+        if (e != hipSuccess) return TC_ERR_HIP;
+        retire_front(c);
+    }
+    return TC_OK;
+}
+
+int sync_locked(tc_ctx *c)
+{
+    while (!c->ops.empty()) {
+        HIP_TRY(hipEventSynchronize(c->ops.front().done));
+        retire_front(c);
+    }
+    return TC_OK;
+}
+
+// n consecutive entries of the id rings; waits for old transfers when the ring is full.
+int ring_alloc(tc_ctx *c, uint64_t n, uint64_t *start, uint64_t *consumed)
+{
+    if (n > c->ring_cap) return TC_ERR_INVAL;
+    for (;;) {
+        uint64_t waste = 0, at = c->ring_tail;
+        if (at + n > c->ring_cap) {
+            waste = c->ring_cap - at;
+            at = 0;
+        }
+        if (c->ring_used + waste + n <= c->ring_cap) {
+            c->ring_used += waste + n;
+            c->ring_tail = (at + n) % c->ring_cap;
+            *start = at;
+            *consumed = waste + n;
+            return TC_OK;
+        }
+        if (c->ops.empty()) return TC_ERR_INVAL;  // cannot happen: an empty ring fits n <= cap
+        HIP_TRY(hipEventSynchronize(c->ops.front().done));
+        retire_front(c);
+    }
+}
+
+// Chunk sizes (in blocks) for `total` records.  With ramp the sequence starts at 1/8 of a slot
+// and doubles, so the first DMA of an offload starts early; an upload uses the reversed sequence
+// so that little is left to scatter after its last DMA.
+std::vector<uint32_t> plan_chunks(uint64_t total, uint32_t slot_blocks, bool ramp, bool reversed)
+{
+    std::vector<uint32_t> out;
+    uint32_t cur = ramp ? std::max<uint32_t>(1, slot_blocks / 8) : slot_blocks;
+    while (total) {
+        uint32_t take = uint32_t(std::min<uint64_t>(cur, total));
+        out.push_back(take);
+        total -= take;
+        cur = std::min<uint64_t>(uint64_t(cur) * 2, slot_blocks);
+    }
+    if (reversed) std::reverse(out.begin(), out.end());
+    return out;
+}
+
+struct Plan {
+    std::vector<Segment> segs;
+    std::vector<int32_t> ids;
+    uint64_t total = 0;
+};
+
+// Validation of a whole batch; no state is changed.
+int validate(tc_ctx *c, const tc_xfer_desc *descs, uint32_t n_descs, Plan *plan)
+{
+    if (n_descs && !descs) return TC_ERR_INVAL;
+    uint64_t total = 0;
+    for (uint32_t d = 0; d < n_descs; ++d) {
+        if (descs[d].n == 0) continue;
+        if (!descs[d].block_ids || !descs[d].host_buf) return TC_ERR_INVAL;
+        total += descs[d].n;
+    }
+    if (total > c->blocks->total()) {
+        // more ids than blocks: there is a bad or repeated id among them; find out which
+        for (uint32_t d = 0; d < n_descs; ++d)
+            if (int rc = c->blocks->check_range(descs[d].block_ids, descs[d].n)) return rc;
+        return TC_ERR_DUP;
+    }
+    plan->ids.reserve(total);
+    for (uint32_t d = 0; d < n_descs; ++d) {
+        if (descs[d].n == 0) continue;
+        plan->segs.push_back(Segment{plan->ids.size(), descs[d].n, static_cast<char *>(descs[d].host_buf),
+                                     descs[d].block_table});
+        plan->ids.insert(plan->ids.end(), descs[d].block_ids, descs[d].block_ids + descs[d].n);
+    }
+    plan->total = total;
+    if (int rc = c->blocks->check_transfer(plan->ids.data(), uint32_t(total))) return rc;
+    for (const Segment &s : plan->segs) {
+        if (!is_pinned_host(c, s.host, uint64_t(s.n) * c->rec)) return TC_ERR_NOT_PINNED;
+        if (c->arena_base && s.host >= c->arena_base && s.host < c->arena_base + c->arena_bytes) {
+            uint64_t off = uint64_t(s.host - c->arena_base);
+            uint64_t start, room;
+            if (off % c->rec) return TC_ERR_INVAL;
+            if (!c->arena->locate(off / c->rec, &start, &room) || room < s.n) return TC_ERR_INVAL;
+        }
+    }
+    return TC_OK;
+}
+
+// Common start of a transfer: ids into the rings, blocks and arena runs marked in flight.
+int begin_op(tc_ctx *c, Plan &plan, hipStream_t stream, Op *op, uint64_t *ring_start)
+{
+    if (int rc = get_event(c, false, &op->done)) return rc;
+    if (int rc = ring_alloc(c, plan.total, ring_start, &op->ring_consumed)) return rc;
+    std::memcpy(c->ids_host + *ring_start, plan.ids.data(), plan.total * sizeof(int32_t));
+    HIP_TRY(hipMemcpyAsync(c->ids_dev + *ring_start, c->ids_host + *ring_start, plan.total * sizeof(int32_t),
+                           hipMemcpyHostToDevice, stream));
+    c->blocks->begin_transfer(plan.ids.data(), uint32_t(plan.total));
+    for (const Segment &s : plan.segs) {
+        if (c->arena_base && s.host >= c->arena_base && s.host < c->arena_base + c->arena_bytes) {
+            uint64_t start, room;
+            c->arena->locate(uint64_t(s.host - c->arena_base) / c->rec, &start, &room);
+            c->arena->begin_transfer(start);
+            op->arena_starts.push_back(start);
+        }
+    }
+    op->ids = std::move(plan.ids);
+    return TC_OK;
+}
+
+int time_begin(tc_ctx *c, Op *op, hipStream_t stream, uint64_t bytes, bool gather)
+{
+    if (!c->profiling) return TC_OK;
+    Timed t{nullptr, nullptr, bytes, gather};
+    if (int rc = get_event(c, true, &t.t0)) return rc;
+    if (int rc = get_event(c, true, &t.t1)) return rc;
+    HIP_TRY(hipEventRecord(t.t0, stream));
+    op->timed.push_back(t);
+    return TC_OK;
+}
+
+int time_end(tc_ctx *c, Op *op, hipStream_t stream)
+{
+    if (!c->profiling) return TC_OK;
+    HIP_TRY(hipEventRecord(op->timed.back().t1, stream));
+    return TC_OK;
+}
+
+// DMA of the parts of every segment that fall into records [c0, c1) of the list.
+int dma_chunk(tc_ctx *c, const Plan &plan, uint64_t c0, uint64_t c1, char *slot_buf, bool to_host)
+{
+    for (const Segment &s : plan.segs) {
+        uint64_t a = std::max<uint64_t>(s.first, c0), b = std::min<uint64_t>(s.first + s.n, c1);
+        if (a >= b) continue;
+        char *host = s.host + (a - s.first) * c->rec;
+        char *dev = slot_buf + (a - c0) * c->rec;
+        uint64_t bytes = (b - a) * c->rec;
+        if (to_host) HIP_TRY(hipMemcpyAsync(host, dev, bytes, hipMemcpyDeviceToHost, c->dma));
+        else HIP_TRY(hipMemcpyAsync(dev, host, bytes, hipMemcpyHostToDevice, c->dma));
+    }
+    return TC_OK;
+}
+
+int offload_locked(tc_ctx *c, const tc_xfer_desc *descs, uint32_t n_descs, hipStream_t stream)
+{
+    Plan plan;
+    if (int rc = validate(c, descs, n_descs, &plan)) return rc;
+    if (plan.total == 0) return TC_OK;
+    (void)poll_locked(c);
+
+    Op op;
+    uint64_t ring_start = 0;
+    if (int rc = begin_op(c, plan, stream, &op, &ring_start)) return rc;
+
+    uint64_t c0 = 0;
+    Slot *slot = nullptr;
+    for (uint32_t nblk : plan_chunks(plan.total, c->slot_blocks, c->opts.ramp != 0, false)) {
+        slot = &c->slots[c->next_slot];
+        c->next_slot = (c->next_slot + 1) % uint32_t(c->slots.size());
+        if (slot->used) HIP_TRY(hipStreamWaitEvent(stream, slot->last, 0));
+        if (int rc = time_begin(c, &op, stream, uint64_t(nblk) * c->rec, true)) return rc;
+        HIP_TRY(tc::launch_gather_pages(c->pool.kv_base, static_cast<const uint32_t *>(c->pool.scales), slot->buf,
+                                        c->ids_dev + ring_start + c0, nblk, c->geom, c->opts.max_grid, stream));
+        if (int rc = time_end(c, &op, stream)) return rc;
+        HIP_TRY(hipEventRecord(slot->mid, stream));
+        HIP_TRY(hipStreamWaitEvent(c->dma, slot->mid, 0));
+        if (int rc = dma_chunk(c, plan, c0, c0 + nblk, slot->buf, true)) return rc;
+        HIP_TRY(hipEventRecord(slot->last, c->dma));
+        slot->used = true;
+        c0 += nblk;
+    }
+    // the caller's stream completes only when the last DMA has landed in host memory
+    HIP_TRY(hipStreamWaitEvent(stream, slot->last, 0));
+    HIP_TRY(hipEventRecord(op.done, stream));
+
+    c->st.n_offloads++;
+    c->st.blocks_offloaded += plan.total;
+    c->st.bytes_offloaded += plan.total * c->rec;
+    c->ops.push_back(std::move(op));
+    return TC_OK;
+}
+
+int upload_locked(tc_ctx *c, const tc_xfer_desc *descs, uint32_t n_descs, hipStream_t stream)
+{
+    Plan plan;
+    if (int rc = validate(c, descs, n_descs, &plan)) return rc;
+    for (const Segment &s : plan.segs)
+        if (s.table && !is_device_ptr(s.table)) return TC_ERR_NOT_PINNED;
+    if (plan.total == 0) return TC_OK;
+    (void)poll_locked(c);
+
+    Op op;
+    uint64_t ring_start = 0;
+    if (int rc = get_event(c, false, &op.entry)) return rc;
+    if (int rc = begin_op(c, plan, stream, &op, &ring_start)) return rc;
+
+    // the DMAs start only after what the caller already queued on its stream
+    HIP_TRY(hipEventRecord(op.entry, stream));
+    HIP_TRY(hipStreamWaitEvent(c->dma, op.entry, 0));
+
+    uint64_t c0 = 0;
+    for (uint32_t nblk : plan_chunks(plan.total, c->slot_blocks, c->opts.ramp != 0, true)) {
+        Slot *slot = &c->slots[c->next_slot];
+        c->next_slot = (c->next_slot + 1) % uint32_t(c->slots.size());
+        if (slot->used) HIP_TRY(hipStreamWaitEvent(c->dma, slot->last, 0));
+        if (int rc = dma_chunk(c, plan, c0, c0 + nblk, slot->buf, false)) return rc;
+        HIP_TRY(hipEventRecord(slot->mid, c->dma));
+        HIP_TRY(hipStreamWaitEvent(stream, slot->mid, 0));
+        if (int rc = time_begin(c, &op, stream, uint64_t(nblk) * c->rec, false)) return rc;
+        HIP_TRY(tc::launch_scatter_pages(slot->buf, c->pool.kv_base, static_cast<uint32_t *>(c->pool.scales),
+                                         c->ids_dev + ring_start + c0, nblk, c->geom, c->opts.max_grid, stream));
+        if (int rc = time_end(c, &op, stream)) return rc;
+        HIP_TRY(hipEventRecord(slot->last, stream));
+        slot->used = true;
+        c0 += nblk;
+    }
+    // the mapping is restored only after the data it points to is in place
+    for (const Segment &s : plan.segs)
+        if (s.table) HIP_TRY(tc::launch_rewrite_table(s.table, c->ids_dev + ring_start + s.first, s.n, stream));
+    HIP_TRY(hipEventRecord(op.done, stream));
+
+    c->st.n_uploads++;
+    c->st.blocks_uploaded += plan.total;
+    c->st.bytes_uploaded += plan.total * c->rec;
+    c->ops.push_back(std::move(op));
+    return TC_OK;
+}
+
+void destroy_unlocked(tc_ctx *c)
+{
+    for (Slot &s : c->slots) {
+        if (s.mid) (void)hipEventDestroy(s.mid);
+        if (s.last) (void)hipEventDestroy(s.last);
+    }
+    for (hipEvent_t e : c->sync_events) (void)hipEventDestroy(e);
+    for (hipEvent_t e : c->time_events) (void)hipEventDestroy(e);
+    if (c->dma) (void)hipStreamDestroy(c->dma);
+    if (c->staging) (void)hipFree(c->staging);
+    if (c->ids_dev) (void)hipFree(c->ids_dev);
+    if (c->ids_host) (void)hipHostFree(c->ids_host);
+    if (c->arena_base) (void)hipHostFree(c->arena_base);
+    delete c->blocks;
+    delete c->arena;
+    delete c;
+}
+
+}  // namespace
+
+// ================================================================================= C ABI
+extern "C" {
+
+int tc_create(const tc_pool_desc *pool, const tc_opts *opts, tc_ctx **out)
+{
+    if (!pool || !out) return TC_ERR_INVAL;
+    *out = nullptr;
+    if (!pool->kv_base || pool->num_layers == 0 || pool->num_blocks == 0 || pool->page_bytes == 0) return TC_ERR_INVAL;
+    if (pool->page_bytes % 16 || (reinterpret_cast<uintptr_t>(pool->kv_base) % 256)) return TC_ERR_INVAL;
+    if (pool->num_blocks > 0x7fffffffu || pool->num_layers > (1u << 20)) return TC_ERR_INVAL;
+    const uint32_t P = 2 * pool->num_layers;
+    const uint32_t S = pool->scales_per_block;
+    if (S != 0 && S != 1 && S != P) return TC_ERR_INVAL;
+    if ((S != 0) != (pool->scales != nullptr)) return TC_ERR_INVAL;
+    if (S && (reinterpret_cast<uintptr_t>(pool->scales) % 4)) return TC_ERR_INVAL;
+    if (!is_device_ptr(pool->kv_base) || (S && !is_device_ptr(pool->scales))) return TC_ERR_NOT_PINNED;
+
+    tc_ctx *c = new (std::nothrow) tc_ctx;
+    if (!c) return TC_ERR_INVAL;
+    c->pool = *pool;
+    if (opts) c->opts = *opts;
+    const uint64_t raw = uint64_t(P) * pool->page_bytes + 4ull * S;
+    c->rec = (raw + 255) / 256 * 256;
+    c->geom.planes = P;
+    c->geom.page16 = pool->page_bytes / 16;
+    c->geom.num_blocks = pool->num_blocks;
+    c->geom.rec16 = c->rec / 16;
+    c->geom.scales = S;
+    c->geom.tail_words = uint32_t((c->rec - uint64_t(P) * pool->page_bytes) / 4);
+
+    uint32_t n_slots = c->opts.staging_slots ? c->opts.staging_slots : kDefaultSlots;
+    if (n_slots < 2) n_slots = 2;
+    uint64_t slot_bytes = c->opts.staging_bytes ? c->opts.staging_bytes / n_slots : kDefaultSlotBytes;
+    if (slot_bytes < c->rec) slot_bytes = c->rec;
+    uint64_t slot_blocks = slot_bytes / c->rec;
+    if (slot_blocks > pool->num_blocks) slot_blocks = pool->num_blocks;
+    c->slot_blocks = uint32_t(slot_blocks);
+    c->slot_bytes = slot_blocks * c->rec;
+
+    c->blocks = new (std::nothrow) tc::BlockPool(pool->num_blocks);
+    const uint64_t arena_slots = c->opts.host_arena_bytes / c->rec;
+    c->arena = new (std::nothrow) tc::HostArena(arena_slots);
+    c->arena_bytes = arena_slots * c->rec;
+    c->ring_cap = std::max<uint64_t>(4ull * pool->num_blocks, 1024);
+
+    auto fail = [&](int code) {
+        destroy_unlocked(c);
+        return code;
+    };
+    if (!c->blocks || !c->arena) return fail(TC_ERR_INVAL);
+#define HIP_OR_FAIL(expr)                                                                     \
+    do {                                                                                      \
+        hipError_t e_ = (expr);                                                               \
+        if (e_ != hipSuccess) {                                                               \
+            std::fprintf(stderr, "tokencake_kv: %s failed: %s\n", #expr, hipGetErrorString(e_)); \
+            return fail(e_ == hipErrorOutOfMemory && std::strstr(#expr, "Host") ? TC_ERR_HOST_NOMEM : TC_ERR_HIP); \
+        }                                                                                     \
+    } while (0)
+    HIP_OR_FAIL(hipMalloc(reinterpret_cast<void **>(&c->staging), c->slot_bytes * n_slots));
+    HIP_OR_FAIL(hipMalloc(reinterpret_cast<void **>(&c->ids_dev), c->ring_cap * sizeof(int32_t)));
+    HIP_OR_FAIL(hipHostMalloc(reinterpret_cast<void **>(&c->ids_host), c->ring_cap * sizeof(int32_t), hipHostMallocDefault));
+    if (c->arena_bytes)
+        HIP_OR_FAIL(hipHostMalloc(reinterpret_cast<void **>(&c->arena_base), c->arena_bytes, hipHostMallocDefault));
+    HIP_OR_FAIL(hipStreamCreateWithFlags(&c->dma, hipStreamNonBlocking));
+    c->slots.resize(n_slots);
+    for (uint32_t i = 0; i < n_slots; ++i) {
+        c->slots[i].buf = c->staging + uint64_t(i) * c->slot_bytes;
+        HIP_OR_FAIL(hipEventCreateWithFlags(&c->slots[i].mid, hipEventDisableTiming));
+        HIP_OR_FAIL(hipEventCreateWithFlags(&c->slots[i].last, hipEventDisableTiming));
+    }
+#undef HIP_OR_FAIL
+    *out = c;
+    return TC_OK;
+}
+
+int tc_destroy(tc_ctx *ctx)
+{
+    if (!ctx) return TC_OK;
+    int rc;
+    {
+        std::lock_guard<std::mutex> g(ctx->mu);
+        rc = sync_locked(ctx);
+        if (ctx->dma) (void)hipStreamSynchronize(ctx->dma);
+    }
+    destroy_unlocked(ctx);
+    return rc;
+}
+
+uint64_t tc_record_bytes(const tc_ctx *ctx) { return ctx ? ctx->rec : 0; }
+
+void *tc_arena_base(const tc_ctx *ctx) { return ctx ? ctx->arena_base : nullptr; }
+
+const char *tc_strerror(int code)
+{
+    switch (code) {
+    case TC_OK: return "ok";
+    case TC_ERR_INVAL: return "invalid argument, unallocated block or over-release";
+    case TC_ERR_RANGE: return "block id out of range";
+    case TC_ERR_DUP: return "duplicate block id in one transfer";
+    case TC_ERR_SHARED: return "block has more than one owner and must not move";
+    case TC_ERR_NOMEM: return "not enough free GPU blocks";
+    case TC_ERR_HOST_NOMEM: return "pinned host arena exhausted";
+    case TC_ERR_NOT_PINNED: return "host buffer is not pinned, or a device pointer is not device memory";
+    case TC_ERR_HIP: return "HIP runtime call failed";
+    default: return "unknown tokencake_kv error";
+    }
+}
+
+int tc_alloc(tc_ctx *ctx, uint32_t n, int32_t *out_ids)
+{
+    if (!ctx || (n && !out_ids)) return TC_ERR_INVAL;
+    std::lock_guard<std::mutex> g(ctx->mu);
+    return ctx->blocks->alloc(n, out_ids);
+}
+
+int tc_alloc_at(tc_ctx *ctx, const int32_t *ids, uint32_t n)
+{
+    if (!ctx || (n && !ids)) return TC_ERR_INVAL;
+    std::lock_guard<std::mutex> g(ctx->mu);
+    return ctx->blocks->alloc_at(ids, n);
+}
+
+int tc_ref(tc_ctx *ctx, const int32_t *ids, uint32_t n)
+{
+    if (!ctx || (n && !ids)) return TC_ERR_INVAL;
+    std::lock_guard<std::mutex> g(ctx->mu);
+    return ctx->blocks->ref(ids, n);
+}
+
+int tc_free(tc_ctx *ctx, const int32_t *ids, uint32_t n)
+{
+    if (!ctx || (n && !ids)) return TC_ERR_INVAL;
+    std::lock_guard<std::mutex> g(ctx->mu);
+    return ctx->blocks->free(ids, n);
+}
+
+int tc_filter_private(tc_ctx *ctx, const int32_t *ids, uint32_t n, int32_t *out_ids, uint32_t *m)
+{
+    if (!ctx || !m || (n && (!ids || !out_ids))) return TC_ERR_INVAL;
+    std::lock_guard<std::mutex> g(ctx->mu);
+    return ctx->blocks->filter_private(ids, n, out_ids, m);
+}
+
+int tc_host_alloc(tc_ctx *ctx, uint32_t n_blocks, void **host_buf)
+{
+    if (!ctx || !host_buf) return TC_ERR_INVAL;
+    *host_buf = nullptr;
+    if (n_blocks == 0) return TC_OK;
+    std::lock_guard<std::mutex> g(ctx->mu);
+    int64_t s = ctx->arena->alloc(n_blocks);
+    if (s < 0) {
+        // slots of finished transfers may be waiting for retirement
+        (void)poll_locked(ctx);
+        s = ctx->arena->alloc(n_blocks);
+    }
+    if (s < 0) return TC_ERR_HOST_NOMEM;
+    *host_buf = ctx->arena_base + uint64_t(s) * ctx->rec;
+    return TC_OK;
+}
+
+int tc_host_free(tc_ctx *ctx, void *host_buf)
+{
+    if (!ctx) return TC_ERR_INVAL;
+    if (!host_buf) return TC_OK;
+    std::lock_guard<std::mutex> g(ctx->mu);
+    char *p = static_cast<char *>(host_buf);
+    if (!ctx->arena_base || p < ctx->arena_base || p >= ctx->arena_base + ctx->arena_bytes) return TC_ERR_INVAL;
+    uint64_t off = uint64_t(p - ctx->arena_base);
+    if (off % ctx->rec) return TC_ERR_INVAL;
+    return ctx->arena->free(off / ctx->rec);
+}
+
+int tc_offload_batch(tc_ctx *ctx, const tc_xfer_desc *descs, uint32_t n_descs, void *stream)
+{
+    if (!ctx) return TC_ERR_INVAL;
+    std::lock_guard<std::mutex> g(ctx->mu);
+    return offload_locked(ctx, descs, n_descs, static_cast<hipStream_t>(stream));
+}
+
+int tc_upload_batch(tc_ctx *ctx, const tc_xfer_desc *descs, uint32_t n_descs, void *stream)
+{
+    if (!ctx) return TC_ERR_INVAL;
+    std::lock_guard<std::mutex> g(ctx->mu);
+    return upload_locked(ctx, descs, n_descs, static_cast<hipStream_t>(stream));
+}
+
+int tc_offload(tc_ctx *ctx, const int32_t *block_ids, uint32_t n, void *host_buf, void *stream)
+{
+    tc_xfer_desc d{block_ids, n, host_buf, nullptr};
+    return tc_offload_batch(ctx, &d, 1, stream);
+}
+
+int tc_upload(tc_ctx *ctx, const void *host_buf, const int32_t *new_block_ids, uint32_t n, int32_t *block_table,
+              void *stream)
+{
+    tc_xfer_desc d{new_block_ids, n, const_cast<void *>(host_buf), block_table};
+    return tc_upload_batch(ctx, &d, 1, stream);
+}
+
+int tc_poll(tc_ctx *ctx)
+{
+    if (!ctx) return TC_ERR_INVAL;
+    std::lock_guard<std::mutex> g(ctx->mu);
+    return poll_locked(ctx);
+}
+
+int tc_sync(tc_ctx *ctx)
+{
+    if (!ctx) return TC_ERR_INVAL;
+    std::lock_guard<std::mutex> g(ctx->mu);
+    return sync_locked(ctx);
+}
+
+int tc_stats(tc_ctx *ctx, tc_stats_t *out)
+{
+    if (!ctx || !out) return TC_ERR_INVAL;
+    std::lock_guard<std::mutex> g(ctx->mu);
+    tc_stats_t s = ctx->st;
+    s.gpu_blocks_total = ctx->blocks->total();
+    s.gpu_blocks_free = ctx->blocks->n_free();
+    s.gpu_blocks_used = ctx->blocks->n_used();
+    s.gpu_blocks_pending_free = ctx->blocks->n_pending();
+    s.gpu_blocks_shared = ctx->blocks->n_shared();
+    s.ops_in_flight = uint32_t(ctx->ops.size());
+    s.host_slots_total = ctx->arena->total();
+    s.host_slots_used = ctx->arena->used();
+    *out = s;
+    return TC_OK;
+}
+
+int tc_set_profiling(tc_ctx *ctx, int on)
+{
+    if (!ctx) return TC_ERR_INVAL;
+    std::lock_guard<std::mutex> g(ctx->mu);
+    ctx->profiling = on != 0;
+    return TC_OK;
+}
+
+int tc_copy_contiguous(void *dst, const void *src, uint64_t bytes, void *stream)
+{
+    if ((bytes && (!dst || !src)) || bytes % 16) return TC_ERR_INVAL;
+    if ((reinterpret_cast<uintptr_t>(dst) | reinterpret_cast<uintptr_t>(src)) % 16) return TC_ERR_INVAL;
+    HIP_TRY(tc::launch_copy_contiguous(dst, src, bytes, static_cast<hipStream_t>(stream)));
+    return TC_OK;
+}
+
+int tc_hbm_stream(float *a, const float *b, const float *c, uint64_t n, float s, uint32_t iters, void *stream)
+{
+    if ((n && (!a || !b || !c)) || n % 4) return TC_ERR_INVAL;
+    if ((reinterpret_cast<uintptr_t>(a) | reinterpret_cast<uintptr_t>(b) | reinterpret_cast<uintptr_t>(c)) % 16)
+        return TC_ERR_INVAL;
+    HIP_TRY(tc::launch_hbm_stream(a, b, c, n, s, iters, static_cast<hipStream_t>(stream)));
+    return TC_OK;
+}
+
+int tc_naive_transfer(tc_ctx *ctx, const int32_t *block_ids, uint32_t n, void *host_buf, int mode, int direction,
+                      void *stream)
+{
+    if (!ctx || (n && (!block_ids || !host_buf)) || mode < 0 || mode > 1 || direction < 0 || direction > 1)
+        return TC_ERR_INVAL;
+    if (ctx->pool.scales_per_block) return TC_ERR_INVAL;
+    std::lock_guard<std::mutex> g(ctx->mu);
+    if (int rc = ctx->blocks->check_range(block_ids, n)) return rc;
+    if (n && !is_pinned_host(ctx, host_buf, uint64_t(n) * ctx->rec)) return TC_ERR_NOT_PINNED;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const uint64_t pb = ctx->pool.page_bytes, NB = ctx->pool.num_blocks, P = ctx->geom.planes;
+    char *pool = static_cast<char *>(ctx->pool.kv_base);
+    char *host = static_cast<char *>(host_buf);
+    for (uint32_t j = 0; j < n; ++j) {
+        char *rec = host + uint64_t(j) * ctx->rec;
+        char *blk = pool + uint64_t(block_ids[j]) * pb;
+        if (mode == 1) {
+            if (direction == 0)
+                HIP_TRY(hipMemcpy2DAsync(rec, pb, blk, NB * pb, pb, P, hipMemcpyDeviceToHost, st));
+            else
+                HIP_TRY(hipMemcpy2DAsync(blk, NB * pb, rec, pb, pb, P, hipMemcpyHostToDevice, st));
+        } else {
+            for (uint64_t p = 0; p < P; ++p) {
+                if (direction == 0)
+                    HIP_TRY(hipMemcpyAsync(rec + p * pb, blk + p * NB * pb, pb, hipMemcpyDeviceToHost, st));
+                else
+                    HIP_TRY(hipMemcpyAsync(blk + p * NB * pb, rec + p * pb, pb, hipMemcpyHostToDevice, st));
+            }
+        }
+    }
+    return TC_OK;
+}
+
+/* tuning knob for kernel experiments; not part of the documented interface */
+int tc_debug_kernel_variant(int v)
+{
+    tc::set_kernel_variant(v);
+    return TC_OK;
+}
+
+}  // extern "C"

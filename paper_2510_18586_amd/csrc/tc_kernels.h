@@ -1,0 +1,36 @@
+// Launchers of the gfx950 kernels behind tc_offload / tc_upload.  Internal to the library.
+#pragma once
+
+#include <cstdint>
+#include <hip/hip_runtime_api.h>
+
+namespace tc {
+
+// Geometry shared by gather and scatter; all "16" fields count 16-byte units.
+struct PageGeom {
+    uint32_t planes;       // P = 2 * layers
+    uint32_t page16;       // page_bytes / 16
+    uint64_t num_blocks;   // NB
+    uint64_t rec16;        // host-record bytes / 16
+    uint32_t scales;       // S: scale words per block (0, 1 or P)
+    uint32_t tail_words;   // 32-bit words from the end of the pages to the end of the record
+};
+
+// staging[k] <- record of block ids[k] for k < n (pages, scale words, zero pad).
+hipError_t launch_gather_pages(const void *pool, const uint32_t *scales, void *staging, const int32_t *ids_dev,
+                               uint32_t n, const PageGeom &g, uint32_t max_grid, hipStream_t stream);
+// block ids[k] <- record k of staging.
+hipError_t launch_scatter_pages(const void *staging, void *pool, uint32_t *scales, const int32_t *ids_dev,
+                                uint32_t n, const PageGeom &g, uint32_t max_grid, hipStream_t stream);
+// table[i] = ids[i], i < n.
+hipError_t launch_rewrite_table(int32_t *table, const int32_t *ids_dev, uint32_t n, hipStream_t stream);
+
+hipError_t launch_copy_contiguous(void *dst, const void *src, uint64_t bytes, hipStream_t stream);
+hipError_t launch_hbm_stream(float *a, const float *b, const float *c, uint64_t n, float s, uint32_t iters,
+                             hipStream_t stream);
+
+// Tuning knob for kernel experiments: bit 0 = non-temporal accesses, bit 1 = at most 4 and
+// bit 2 = at most 2 loads in flight per lane.  0 is the production setting.
+void set_kernel_variant(int v);
+
+}  // namespace tc

@@ -1,0 +1,223 @@
+// gfx950 kernels of the KV offload / upload path (paper Sec. 6.3: KV blocks migrate between GPU
+// blocks and CPU blocks; Sec. 7.6: a block is block_size tokens of every layer's K and V).
+//
+// gather_pages   pool (plane-major, pages of one block strided by NB*page_bytes) -> staging
+//                chunk (block-major records, the host layout), so that one contiguous DMA can
+//                carry many blocks over the host link.
+// scatter_pages  the inverse, into the destination blocks of an upload.
+// rewrite_table  block_table[i] = new_ids[i] once the data is in place.
+//
+// Both copy kernels are pure HBM streaming: a workgroup of four wave64 moves one tile of a page,
+// every lane with U independent 16-byte loads in flight before the first store (a wave
+// instruction covers 1 KiB of consecutive addresses).  There is no arithmetic on the payload and
+// no reuse, so neither LDS nor MFMA has anything to add; bytes are never reinterpreted.
+#include <hip/hip_runtime.h>
+
+#include "tc_kernels.h"
+
+namespace tc {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr uint32_t kThreads = 256;
+
+template <bool NT>
+__device__ __forceinline__ u32x4 ld16(const u32x4 *p)
+{
+    if constexpr (NT) return __builtin_nontemporal_load(p);
+    else return *p;
+}
+template <bool NT>
+__device__ __forceinline__ void st16(u32x4 *p, u32x4 v)
+{
+    if constexpr (NT) __builtin_nontemporal_store(v, p);
+    else *p = v;
+}
+
+// One work item = (block k of the chunk, plane p, tile t of the page).  Items are ordered with
+// the tile fastest, then the plane: consecutive workgroups write (gather) or read (scatter)
+// consecutive staging addresses.
+template <int U, bool NT, bool GATHER>
+__global__ __launch_bounds__(kThreads) void page_copy_kernel(
+    u32x4 *__restrict__ pool, uint32_t *__restrict__ scales, u32x4 *__restrict__ staging,
+    const int32_t *__restrict__ ids, uint32_t n_items, uint32_t tiles, PageGeom g)
+{
+    constexpr uint32_t kTile = kThreads * U;  // 16-byte units per tile
+    for (uint32_t item = blockIdx.x; item < n_items; item += gridDim.x) {
+        const uint32_t t = item % tiles;
+        const uint32_t kp = item / tiles;
+        const uint32_t p = kp % g.planes;
+        const uint32_t k = kp / g.planes;
+        const uint64_t blk = uint64_t(uint32_t(ids[k]));
+
+        // wave-uniform bases; the lane offset stays 32-bit so loads use scalar-base addressing
+        u32x4 *in_pool = pool + (uint64_t(p) * g.num_blocks + blk) * g.page16 + t * kTile;
+        u32x4 *in_stag = staging + uint64_t(k) * g.rec16 + uint64_t(p) * g.page16 + t * kTile;
+        const u32x4 *src = GATHER ? in_pool : in_stag;
+        u32x4 *dst = GATHER ? in_stag : in_pool;
+        const uint32_t lane = threadIdx.x;
+        const uint32_t left = g.page16 - t * kTile;  // 16-byte units from the tile start to the page end
+
+        u32x4 v[U];
+        if (left >= kTile) {  // full tile: U loads in flight, then U stores, no predicates
+#pragma unroll
+            for (int u = 0; u < U; ++u) v[u] = ld16<NT>(src + lane + u * kThreads);
+#pragma unroll
+            for (int u = 0; u < U; ++u) st16<NT>(dst + lane + u * kThreads, v[u]);
+        } else {              // ragged last tile of a page
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (lane + u * kThreads < left) st16<NT>(dst + lane + u * kThreads, ld16<NT>(src + lane + u * kThreads));
+        }
+
+        // the record's tail: S scale words gathered from their planes, then zero pad
+        if (g.tail_words && p == 0 && t == 0) {
+            uint32_t *tail = reinterpret_cast<uint32_t *>(staging + uint64_t(k) * g.rec16 + uint64_t(g.planes) * g.page16);
+            for (uint32_t w = threadIdx.x; w < g.tail_words; w += kThreads) {
+                if (GATHER) tail[w] = (w < g.scales) ? scales[uint64_t(w) * g.num_blocks + blk] : 0u;
+                else if (w < g.scales) scales[uint64_t(w) * g.num_blocks + blk] = tail[w];
+            }
+        }
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void rewrite_table_kernel(int32_t *__restrict__ table,
+                                                                  const int32_t *__restrict__ ids, uint32_t n)
+{
+    const uint32_t i = blockIdx.x * kThreads + threadIdx.x;
+    if (i < n) table[i] = ids[i];
+}
+
+template <int U, bool NT>
+__global__ __launch_bounds__(kThreads) void copy_contiguous_kernel(u32x4 *__restrict__ dst,
+                                                                    const u32x4 *__restrict__ src, uint64_t n16)
+{
+    const uint64_t tile = uint64_t(blockIdx.x) * (kThreads * U);
+    const u32x4 *s = src + tile;
+    u32x4 *d = dst + tile;
+    const uint32_t lane = threadIdx.x;
+    const uint64_t left = n16 - tile;
+    if (left >= kThreads * U) {
+        u32x4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) v[u] = ld16<NT>(s + lane + u * kThreads);
+#pragma unroll
+        for (int u = 0; u < U; ++u) st16<NT>(d + lane + u * kThreads, v[u]);
+    } else {
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (lane + u * kThreads < left) st16<NT>(d + lane + u * kThreads, ld16<NT>(s + lane + u * kThreads));
+    }
+}
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__global__ __launch_bounds__(kThreads) void hbm_stream_kernel(f32x4 *__restrict__ a, const f32x4 *__restrict__ b,
+                                                               const f32x4 *__restrict__ c, uint64_t n4, float s,
+                                                               uint32_t iters)
+{
+    const uint64_t stride = uint64_t(gridDim.x) * kThreads;
+    for (uint32_t it = 0; it < iters; ++it)
+        for (uint64_t i = uint64_t(blockIdx.x) * kThreads + threadIdx.x; i < n4; i += stride) {
+            f32x4 x = b[i], y = c[i];
+            a[i] = x + s * y;
+        }
+}
+
+// ---------------------------------------------------------------------------------------------
+static int g_variant = 0;  // tuning knob, see set_kernel_variant
+void set_kernel_variant(int v) { g_variant = v; }
+
+template <bool GATHER>
+static hipError_t launch_page_copy(void *pool, uint32_t *scales, void *staging, const int32_t *ids_dev, uint32_t n,
+                                   const PageGeom &g, uint32_t max_grid, hipStream_t stream)
+{
+    if (n == 0) return hipSuccess;
+    // widest tile that a page still fills
+    int U = 8;
+    while (U > 1 && uint64_t(kThreads) * U > g.page16) U >>= 1;
+    bool nt = false;
+    if (g_variant & 1) nt = true;
+    if ((g_variant & 2) && U > 4) U = 4;
+    if ((g_variant & 4) && U > 2) U = 2;
+    const uint32_t tile16 = kThreads * U;
+    const uint32_t tiles = (g.page16 + tile16 - 1) / tile16;
+    const uint64_t items64 = uint64_t(n) * g.planes * tiles;
+    if (items64 > 0x7fffffffull) return hipErrorInvalidValue;
+    const uint32_t n_items = uint32_t(items64);
+    uint32_t grid = n_items;
+    if (max_grid && grid > max_grid) grid = max_grid;
+
+#define TC_LAUNCH(UU, NTT)                                                                                   \
+    hipLaunchKernelGGL((page_copy_kernel<UU, NTT, GATHER>), dim3(grid), dim3(kThreads), 0, stream,           \
+                       static_cast<u32x4 *>(pool), scales, static_cast<u32x4 *>(staging), ids_dev, n_items, \
+                       tiles, g)
+    if (nt) {
+        switch (U) {
+        case 8: TC_LAUNCH(8, true); break;
+        case 4: TC_LAUNCH(4, true); break;
+        case 2: TC_LAUNCH(2, true); break;
+        default: TC_LAUNCH(1, true); break;
+        }
+    } else {
+        switch (U) {
+        case 8: TC_LAUNCH(8, false); break;
+        case 4: TC_LAUNCH(4, false); break;
+        case 2: TC_LAUNCH(2, false); break;
+        default: TC_LAUNCH(1, false); break;
+        }
+    }
+#undef TC_LAUNCH
+    return hipGetLastError();
+}
+
+hipError_t launch_gather_pages(const void *pool, const uint32_t *scales, void *staging, const int32_t *ids_dev,
+                               uint32_t n, const PageGeom &g, uint32_t max_grid, hipStream_t stream)
+{
+    return launch_page_copy<true>(const_cast<void *>(pool), const_cast<uint32_t *>(scales), staging, ids_dev, n, g,
+                                  max_grid, stream);
+}
+
+hipError_t launch_scatter_pages(const void *staging, void *pool, uint32_t *scales, const int32_t *ids_dev,
+                                uint32_t n, const PageGeom &g, uint32_t max_grid, hipStream_t stream)
+{
+    return launch_page_copy<false>(pool, scales, const_cast<void *>(staging), ids_dev, n, g, max_grid, stream);
+}
+
+hipError_t launch_rewrite_table(int32_t *table, const int32_t *ids_dev, uint32_t n, hipStream_t stream)
+{
+    if (n == 0 || table == nullptr) return hipSuccess;
+    hipLaunchKernelGGL(rewrite_table_kernel, dim3((n + kThreads - 1) / kThreads), dim3(kThreads), 0, stream, table,
+                       ids_dev, n);
+    return hipGetLastError();
+}
+
+hipError_t launch_copy_contiguous(void *dst, const void *src, uint64_t bytes, hipStream_t stream)
+{
+    if (bytes == 0) return hipSuccess;
+    const uint64_t n16 = bytes / 16;
+    const uint64_t grid = (n16 + kThreads * 8 - 1) / (kThreads * 8);
+    if (grid > 0x7fffffffull) return hipErrorInvalidValue;
+    if (g_variant & 1)
+        hipLaunchKernelGGL((copy_contiguous_kernel<8, true>), dim3(uint32_t(grid)), dim3(kThreads), 0, stream,
+                           static_cast<u32x4 *>(dst), static_cast<const u32x4 *>(src), n16);
+    else
+        hipLaunchKernelGGL((copy_contiguous_kernel<8, false>), dim3(uint32_t(grid)), dim3(kThreads), 0, stream,
+                           static_cast<u32x4 *>(dst), static_cast<const u32x4 *>(src), n16);
+    return hipGetLastError();
+}
+
+hipError_t launch_hbm_stream(float *a, const float *b, const float *c, uint64_t n, float s, uint32_t iters,
+                             hipStream_t stream)
+{
+    if (n == 0 || iters == 0) return hipSuccess;
+    const uint64_t n4 = n / 4;
+    uint64_t grid = (n4 + kThreads - 1) / kThreads;
+    if (grid > 256 * 32) grid = 256 * 32;  // 32 workgroups per CU, grid-stride over the rest
+    hipLaunchKernelGGL(hbm_stream_kernel, dim3(uint32_t(grid)), dim3(kThreads), 0, stream,
+                       reinterpret_cast<f32x4 *>(a), reinterpret_cast<const f32x4 *>(b),
+                       reinterpret_cast<const f32x4 *>(c), n4, s, iters);
+    return hipGetLastError();
+}
+
+}  // namespace tc

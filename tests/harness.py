@@ -1,0 +1,90 @@
+"""Shared plumbing of the GPU parity tests: device memory via torch, calls via the C-ABI binding.
+
+Nothing here computes any part of the path; it allocates, copies inputs in and results out
+(torch copies), and drives the library and the oracle with the same seeded inputs.
+"""
+import numpy as np
+import torch
+
+import oracle
+import paper_2510_18586_amd as K
+import tc_workloads as W
+
+DEV = "cuda:0"
+
+
+class GpuPool:
+    """A KV pool (+ scales) in device memory bound to a library context."""
+
+    def __init__(self, shape, pool_host=None, scales_host=None, seed=None, **opts):
+        self.shape = shape
+        self.L, self.NB, self.pb = shape.num_layers, shape.num_blocks, shape.page_bytes
+        self.P, self.S = shape.planes, shape.scales_per_block
+        if pool_host is not None:
+            self.pool = torch.from_numpy(pool_host).to(DEV)
+            self.scales = torch.from_numpy(scales_host.view(np.int32)).to(DEV) if self.S else None
+        else:
+            self.pool = W.make_pool_device(shape, seed, DEV)
+            sc = W.make_scales_device(shape, seed, DEV)
+            self.scales = sc.view(torch.int32) if sc is not None else None
+        rc, self.ctx = K.tc_create(self.pool, self.scales, self.L, self.NB, self.pb, shape.block_size, self.S, **opts)
+        K.check(rc)
+        self.rec = K.tc_record_bytes(self.ctx)
+        assert self.rec == oracle.record_bytes(self.L, self.pb, self.S)
+
+    def close(self):
+        if self.ctx:
+            K.check(K.tc_destroy(self.ctx))
+            self.ctx = None
+
+    # ---- views / copies (torch only) --------------------------------------
+    def pool3(self):
+        return self.pool.view(self.P, self.NB, self.pb)
+
+    def blocks_to_host(self, ids):
+        """[P][len(ids)][pb] uint8 numpy copy of the given blocks."""
+        idx = torch.as_tensor(np.asarray(ids, dtype=np.int64), device=DEV)
+        return self.pool3()[:, idx].cpu().numpy()
+
+    def scales_to_host(self, ids):
+        idx = torch.as_tensor(np.asarray(ids, dtype=np.int64), device=DEV)
+        return self.scales.view(self.S, self.NB)[:, idx].cpu().numpy().view(np.uint32)
+
+    def pool_to_host(self):
+        return self.pool.cpu().numpy()
+
+    def scales_all_to_host(self):
+        return self.scales.cpu().numpy().view(np.uint32) if self.S else None
+
+    def page_checksums(self):
+        """One int64 per (plane, block): a torch reduction, independent of the library."""
+        return self.pool.view(torch.int32).view(self.P, self.NB, self.pb // 4).sum(dim=2, dtype=torch.int64)
+
+
+def pinned_bytes(n):
+    return torch.empty(max(int(n), 1), dtype=torch.uint8, pin_memory=True)
+
+
+class SparseMirror:
+    """Host mirror of a full-size pool holding only the blocks a test touches, at their true
+    offsets (untouched pages of the anonymous mapping are never materialised)."""
+
+    def __init__(self, gp, ids):
+        self.gp = gp
+        self.pool = np.empty(gp.P * gp.NB * gp.pb, dtype=np.uint8)
+        self.scales = np.empty(gp.S * gp.NB, dtype=np.uint32) if gp.S else None
+        self.load(ids)
+
+    def load(self, ids):
+        gp = self.gp
+        ids = np.asarray(ids, dtype=np.int64)
+        step = 64
+        v = self.pool.reshape(gp.P, gp.NB, gp.pb)
+        for a in range(0, ids.size, step):
+            sub = ids[a:a + step]
+            v[:, sub] = gp.blocks_to_host(sub)
+            if gp.S:
+                self.scales.reshape(gp.S, gp.NB)[:, sub] = gp.scales_to_host(sub)
+
+    def blocks(self, ids):
+        return self.pool.reshape(self.gp.P, self.gp.NB, self.gp.pb)[:, np.asarray(ids, dtype=np.int64)]

@@ -1,0 +1,160 @@
+"""GPU parity: tc_offload / tc_upload through the C ABI against the CPU oracle, bit for bit.
+
+Every case feeds the same seeded inputs to both sides.  Integer / byte work: the bar is
+exact equality of every host-record byte, every pool byte, every scale word and every
+block-table entry.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2510_18586_amd as K
+import tc_workloads as W
+from harness import DEV, GpuPool, SparseMirror, pinned_bytes
+
+pytestmark = pytest.mark.gpu
+
+
+def _round_trip_case(shape, seed_idx, n, salt=0, same_ids=False, **opts):
+    rng = W.rng_for(seed_idx, salt)
+    L, NB, pb, S, P = shape.num_layers, shape.num_blocks, shape.page_bytes, shape.scales_per_block, shape.planes
+    pool_h = W.make_pool_host(shape, rng)
+    scales_h = W.make_scales_host(shape, rng)
+    ids = W.pick_ids(rng, NB, n)
+    new_ids = ids.copy() if same_ids else W.pick_ids(rng, NB, n, exclude=ids)
+    rec = oracle.record_bytes(L, pb, S)
+
+    # ---- oracle
+    want_host = np.empty(max(n * rec, 1), dtype=np.uint8)
+    oracle.offload(pool_h, scales_h, L, NB, pb, S, ids, want_host)
+
+    # ---- GPU
+    gp = GpuPool(shape, pool_h, scales_h, **opts)
+    try:
+        stream = torch.cuda.Stream()
+        host = pinned_bytes(n * rec + 512)
+        host.fill_(0xA5)
+        K.check(K.tc_alloc_at(gp.ctx, ids))
+        K.check(K.tc_offload(gp.ctx, ids, host, stream))
+        K.check(K.tc_free(gp.ctx, ids))          # released right after the copy is issued
+        rc, st = K.tc_stats(gp.ctx)
+        assert st.gpu_blocks_free + st.gpu_blocks_used + st.gpu_blocks_pending_free == NB
+        K.check(K.tc_sync(gp.ctx))
+        got = host.numpy()
+        assert np.array_equal(got[: n * rec], want_host[: n * rec]), "offload records differ from the oracle"
+        assert (got[n * rec:] == 0xA5).all(), "bytes past the last record were written"
+        assert np.array_equal(gp.pool_to_host(), pool_h), "offload wrote the pool"
+        rc, st = K.tc_stats(gp.ctx)
+        assert st.gpu_blocks_pending_free == 0 and st.gpu_blocks_free == NB
+
+        # somebody else reuses the freed blocks: scramble them on both sides with the same bytes
+        junk = rng.integers(0, 256, size=(P, n, pb), dtype=np.uint8)
+        if n and not same_ids:
+            pool_h.reshape(P, NB, pb)[:, ids] = junk
+            gp.pool3()[:, torch.as_tensor(ids.astype(np.int64), device=DEV)] = torch.from_numpy(junk).to(DEV)
+
+        table_h = np.full(n + 4, -1, dtype=np.int32)
+        table_h[:n] = ids
+        table_d = torch.from_numpy(table_h.copy()).to(DEV)
+        oracle.upload(want_host, L, NB, pb, S, new_ids, pool_h, scales_h, table_h)
+
+        K.check(K.tc_alloc_at(gp.ctx, new_ids))
+        K.check(K.tc_upload(gp.ctx, host, new_ids, table_d, stream))
+        stream.synchronize()
+        assert np.array_equal(gp.pool_to_host(), pool_h), "pool after upload differs from the oracle"
+        if S:
+            assert np.array_equal(gp.scales_all_to_host(), scales_h), "scales after upload differ"
+        assert np.array_equal(table_d.cpu().numpy(), table_h), "block table differs"
+        K.check(K.tc_sync(gp.ctx))
+    finally:
+        gp.close()
+
+
+def test_config1_tiny():
+    # 2 layers, 4 KV heads, head_dim 64, 16-token blocks, bf16, 256 blocks, one agent with 8 blocks
+    _round_trip_case(W.CONFIGS[0], 0, 8)
+
+
+def test_config1_tiny_same_ids():
+    # the original blocks are claimed again on upload
+    _round_trip_case(W.CONFIGS[0], 0, 8, salt=1, same_ids=True)
+
+
+@pytest.mark.parametrize("ramp", [0, 1])
+def test_8b_pages_many_chunks_ragged_tail(ramp):
+    # 8B-shaped pages (32 KiB, 64 planes); staging of 3 slots x 5 records -> 8 chunks, last one ragged
+    shape = W.CONFIGS[1].with_blocks(96)
+    _round_trip_case(shape, 1, 37, salt=ramp, staging_bytes=3 * 5 * 2 * 1024 * 1024, staging_slots=3, ramp=ramp)
+
+
+def test_capped_grid_strides_over_items():
+    shape = W.CONFIGS[1].with_blocks(64)
+    _round_trip_case(shape, 1, 21, salt=7, max_grid=37)
+
+
+@pytest.mark.parametrize("shape,n", [
+    (W.PoolShape("odd-small", 3, 3, 24, 4, 1, 50, 6, "fp8"), 7),        # 288-B pages, one scale per plane
+    (W.PoolShape("odd-ragged", 2, 5, 128, 16, 1, 40, 1, "fp8"), 9),     # 10 KiB pages: ragged second tile; 1 scale
+    (W.PoolShape("fp8-70b-pages", 80, 8, 128, 32, 1, 24, 160, "fp8"), 10),  # config-5 record: 5 MiB + 640 B + pad
+    (W.PoolShape("min", 1, 1, 8, 1, 2, 10, 0, "normal"), 5),            # 16-B pages, every block is a source or a destination
+])
+def test_odd_shapes_and_scales(shape, n):
+    _round_trip_case(shape, 4, n, salt=n)
+
+
+def test_zero_blocks_is_a_no_op():
+    _round_trip_case(W.CONFIGS[0], 0, 0, salt=3)
+
+
+def test_config2_full_size_llama3_8b():
+    """32 layers x 8 heads x 128 x 16 tokens bf16 (2 MiB per block), 16 384 blocks (32 GiB), one agent
+    with a 4 096-token context = 256 blocks scattered uniformly; default launch configuration."""
+    shape = W.CONFIGS[1]
+    rng = W.rng_for(1)
+    n = oracle.blocks_for_tokens(4096, shape.block_size)
+    L, NB, pb, S, P = shape.num_layers, shape.num_blocks, shape.page_bytes, 0, shape.planes
+    ids = W.pick_ids(rng, NB, n)
+    new_ids = W.pick_ids(rng, NB, n, exclude=ids)
+    gp = GpuPool(shape, seed=W.seed_for(1))
+    try:
+        rec = gp.rec
+        before = gp.page_checksums()
+        mirror = SparseMirror(gp, np.concatenate([ids, new_ids]))
+        want_host = np.empty(n * rec, dtype=np.uint8)
+        oracle.offload(mirror.pool, None, L, NB, pb, S, ids, want_host)
+
+        stream = torch.cuda.Stream()
+        host = pinned_bytes(n * rec)
+        K.check(K.tc_alloc_at(gp.ctx, ids))
+        K.check(K.tc_offload(gp.ctx, ids, host, stream))
+        K.check(K.tc_free(gp.ctx, ids))
+        K.check(K.tc_sync(gp.ctx))
+        assert np.array_equal(host.numpy(), want_host)
+        assert torch.equal(gp.page_checksums(), before), "offload wrote the pool"
+
+        table_d = torch.full((n + 2,), -1, dtype=torch.int32, device=DEV)
+        table_h = np.full(n + 2, -1, dtype=np.int32)
+        oracle.upload(want_host, L, NB, pb, S, new_ids, mirror.pool, None, table_h)
+        K.check(K.tc_alloc_at(gp.ctx, new_ids))
+        K.check(K.tc_upload(gp.ctx, host, new_ids, table_d, stream))
+        stream.synchronize()
+        assert np.array_equal(gp.blocks_to_host(new_ids), mirror.blocks(new_ids)), "uploaded blocks differ"
+        assert np.array_equal(table_d.cpu().numpy(), table_h)
+        # every block outside new_ids: untouched (per-page checksums by torch, not by the library)
+        after = gp.page_checksums()
+        keep = torch.ones(NB, dtype=torch.bool, device=DEV)
+        keep[torch.as_tensor(new_ids.astype(np.int64), device=DEV)] = False
+        assert torch.equal(after[:, keep], before[:, keep])
+        # the remapped table addresses the same logical tokens (sampled)
+        t0 = np.full(n, -1, dtype=np.int32)
+        t0[:] = ids
+        src_blocks = mirror.blocks(ids)  # still the pre-offload bytes: sources were not scrambled here
+        for t in rng.integers(0, n * shape.block_size, size=64):
+            j, slot = divmod(int(t), shape.block_size)
+            tok = pb // shape.block_size
+            for layer, kv in ((0, 0), (17, 1), (31, 1)):
+                got = oracle.read_token(mirror.pool, L, NB, pb, shape.block_size, table_h, int(t), layer, kv)
+                assert np.array_equal(got, src_blocks[2 * layer + kv, j, slot * tok:(slot + 1) * tok])
+    finally:
+        gp.close()
