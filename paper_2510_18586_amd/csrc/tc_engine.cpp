@@ -23,7 +23,7 @@
 
 namespace {
 
-constexpr uint64_t kDefaultSlotBytes = 128ull << 20;
+constexpr uint64_t kDefaultSlotBytes = 512ull << 20;
 constexpr uint32_t kDefaultSlots = 3;
 
 struct Slot {
@@ -198,6 +198,7 @@ int ring_alloc(tc_ctx *c, uint64_t n, uint64_t *start, uint64_t *consumed)
 {
     if (n > c->ring_cap) return TC_ERR_INVAL;
     for (;;) {
+        if (c->ring_used == 0) c->ring_tail = 0;
         uint64_t waste = 0, at = c->ring_tail;
         if (at + n > c->ring_cap) {
             waste = c->ring_cap - at;
@@ -547,6 +548,8 @@ int tc_alloc(tc_ctx *ctx, uint32_t n, int32_t *out_ids)
 {
     if (!ctx || (n && !out_ids)) return TC_ERR_INVAL;
     std::lock_guard<std::mutex> g(ctx->mu);
+    // blocks of finished transfers may still be waiting for retirement
+    if (n > ctx->blocks->n_free()) (void)poll_locked(ctx);
     return ctx->blocks->alloc(n, out_ids);
 }
 
@@ -554,7 +557,12 @@ int tc_alloc_at(tc_ctx *ctx, const int32_t *ids, uint32_t n)
 {
     if (!ctx || (n && !ids)) return TC_ERR_INVAL;
     std::lock_guard<std::mutex> g(ctx->mu);
-    return ctx->blocks->alloc_at(ids, n);
+    int rc = ctx->blocks->alloc_at(ids, n);
+    if (rc == TC_ERR_NOMEM && ctx->blocks->n_pending()) {
+        (void)poll_locked(ctx);
+        rc = ctx->blocks->alloc_at(ids, n);
+    }
+    return rc;
 }
 
 int tc_ref(tc_ctx *ctx, const int32_t *ids, uint32_t n)
@@ -720,13 +728,6 @@ int tc_naive_transfer(tc_ctx *ctx, const int32_t *block_ids, uint32_t n, void *h
             }
         }
     }
-    return TC_OK;
-}
-
-/* tuning knob for kernel experiments; not part of the documented interface */
-int tc_debug_kernel_variant(int v)
-{
-    tc::set_kernel_variant(v);
     return TC_OK;
 }
 

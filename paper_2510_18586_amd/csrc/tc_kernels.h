@@ -29,8 +29,4 @@ hipError_t launch_copy_contiguous(void *dst, const void *src, uint64_t bytes, hi
 hipError_t launch_hbm_stream(float *a, const float *b, const float *c, uint64_t n, float s, uint32_t iters,
                              hipStream_t stream);
 
-// Tuning knob for kernel experiments: bit 0 = non-temporal accesses, bit 1 = at most 4 and
-// bit 2 = at most 2 loads in flight per lane.  0 is the production setting.
-void set_kernel_variant(int v);
-
 }  // namespace tc

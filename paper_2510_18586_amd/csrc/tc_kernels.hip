@@ -37,7 +37,7 @@ __device__ __forceinline__ void st16(u32x4 *p, u32x4 v)
 // One work item = (block k of the chunk, plane p, tile t of the page).  Items are ordered with
 // the tile fastest, then the plane: consecutive workgroups write (gather) or read (scatter)
 // consecutive staging addresses.
-template <int U, bool NT, bool GATHER>
+template <int U, bool NTL, bool NTS, bool GATHER>
 __global__ __launch_bounds__(kThreads) void page_copy_kernel(
     u32x4 *__restrict__ pool, uint32_t *__restrict__ scales, u32x4 *__restrict__ staging,
     const int32_t *__restrict__ ids, uint32_t n_items, uint32_t tiles, PageGeom g)
@@ -61,13 +61,13 @@ __global__ __launch_bounds__(kThreads) void page_copy_kernel(
         u32x4 v[U];
         if (left >= kTile) {  // full tile: U loads in flight, then U stores, no predicates
 #pragma unroll
-            for (int u = 0; u < U; ++u) v[u] = ld16<NT>(src + lane + u * kThreads);
+            for (int u = 0; u < U; ++u) v[u] = ld16<NTL>(src + lane + u * kThreads);
 #pragma unroll
-            for (int u = 0; u < U; ++u) st16<NT>(dst + lane + u * kThreads, v[u]);
+            for (int u = 0; u < U; ++u) st16<NTS>(dst + lane + u * kThreads, v[u]);
         } else {              // ragged last tile of a page
 #pragma unroll
             for (int u = 0; u < U; ++u)
-                if (lane + u * kThreads < left) st16<NT>(dst + lane + u * kThreads, ld16<NT>(src + lane + u * kThreads));
+                if (lane + u * kThreads < left) st16<NTS>(dst + lane + u * kThreads, ld16<NTL>(src + lane + u * kThreads));
         }
 
         // the record's tail: S scale words gathered from their planes, then zero pad
@@ -125,9 +125,6 @@ __global__ __launch_bounds__(kThreads) void hbm_stream_kernel(f32x4 *__restrict_
 }
 
 // ---------------------------------------------------------------------------------------------
-static int g_variant = 0;  // tuning knob, see set_kernel_variant
-void set_kernel_variant(int v) { g_variant = v; }
-
 template <bool GATHER>
 static hipError_t launch_page_copy(void *pool, uint32_t *scales, void *staging, const int32_t *ids_dev, uint32_t n,
                                    const PageGeom &g, uint32_t max_grid, hipStream_t stream)
@@ -136,10 +133,9 @@ static hipError_t launch_page_copy(void *pool, uint32_t *scales, void *staging, 
     // widest tile that a page still fills
     int U = 8;
     while (U > 1 && uint64_t(kThreads) * U > g.page16) U >>= 1;
-    bool nt = false;
-    if (g_variant & 1) nt = true;
-    if ((g_variant & 2) && U > 4) U = 4;
-    if ((g_variant & 4) && U > 2) U = 2;
+    // Measured on MI355X (512 MiB per launch): non-temporal loads help both directions; non-temporal
+    // stores help the contiguous staging writes of the gather (5.2 -> 6.0 TB/s) but hurt the scattered
+    // page writes of the scatter (6.6 -> 5.4 TB/s).
     const uint32_t tile16 = kThreads * U;
     const uint32_t tiles = (g.page16 + tile16 - 1) / tile16;
     const uint64_t items64 = uint64_t(n) * g.planes * tiles;
@@ -148,25 +144,20 @@ static hipError_t launch_page_copy(void *pool, uint32_t *scales, void *staging, 
     uint32_t grid = n_items;
     if (max_grid && grid > max_grid) grid = max_grid;
 
-#define TC_LAUNCH(UU, NTT)                                                                                   \
-    hipLaunchKernelGGL((page_copy_kernel<UU, NTT, GATHER>), dim3(grid), dim3(kThreads), 0, stream,           \
+#define TC_LAUNCH(UU, NL, NS)                                                                                \
+    hipLaunchKernelGGL((page_copy_kernel<UU, NL, NS, GATHER>), dim3(grid), dim3(kThreads), 0, stream,        \
                        static_cast<u32x4 *>(pool), scales, static_cast<u32x4 *>(staging), ids_dev, n_items, \
                        tiles, g)
-    if (nt) {
-        switch (U) {
-        case 8: TC_LAUNCH(8, true); break;
-        case 4: TC_LAUNCH(4, true); break;
-        case 2: TC_LAUNCH(2, true); break;
-        default: TC_LAUNCH(1, true); break;
-        }
-    } else {
-        switch (U) {
-        case 8: TC_LAUNCH(8, false); break;
-        case 4: TC_LAUNCH(4, false); break;
-        case 2: TC_LAUNCH(2, false); break;
-        default: TC_LAUNCH(1, false); break;
-        }
+#define TC_LAUNCH_U(NL, NS)                  \
+    switch (U) {                             \
+    case 8: TC_LAUNCH(8, NL, NS); break;     \
+    case 4: TC_LAUNCH(4, NL, NS); break;     \
+    case 2: TC_LAUNCH(2, NL, NS); break;     \
+    default: TC_LAUNCH(1, NL, NS); break;    \
     }
+    if (GATHER) { TC_LAUNCH_U(true, true) }
+    else { TC_LAUNCH_U(true, false) }
+#undef TC_LAUNCH_U
 #undef TC_LAUNCH
     return hipGetLastError();
 }
@@ -198,12 +189,8 @@ hipError_t launch_copy_contiguous(void *dst, const void *src, uint64_t bytes, hi
     const uint64_t n16 = bytes / 16;
     const uint64_t grid = (n16 + kThreads * 8 - 1) / (kThreads * 8);
     if (grid > 0x7fffffffull) return hipErrorInvalidValue;
-    if (g_variant & 1)
-        hipLaunchKernelGGL((copy_contiguous_kernel<8, true>), dim3(uint32_t(grid)), dim3(kThreads), 0, stream,
-                           static_cast<u32x4 *>(dst), static_cast<const u32x4 *>(src), n16);
-    else
-        hipLaunchKernelGGL((copy_contiguous_kernel<8, false>), dim3(uint32_t(grid)), dim3(kThreads), 0, stream,
-                           static_cast<u32x4 *>(dst), static_cast<const u32x4 *>(src), n16);
+    hipLaunchKernelGGL((copy_contiguous_kernel<8, true>), dim3(uint32_t(grid)), dim3(kThreads), 0, stream,
+                       static_cast<u32x4 *>(dst), static_cast<const u32x4 *>(src), n16);
     return hipGetLastError();
 }
 

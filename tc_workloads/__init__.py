@@ -163,3 +163,37 @@ def uniform_contexts(rng, n_agents, lo=1024, hi=32768):
 
 def blocks_of(tokens, block_size):
     return -(-np.asarray(tokens, dtype=np.int64) // block_size)
+
+
+# --------------------------------------------------------------------------- scripted call sequences
+def fragment_pool(backend, rng, n_ops=50000, median_blocks=128, sigma=0.8, need_free=0):
+    """Fragments a block pool with a seeded stream of alloc / free calls.
+
+    `backend` offers alloc(n) -> list of ids or None, free(ids) and n_free().  Each op: with
+    probability 1/2 (or when nothing is live) allocate k ~ lognormal(median_blocks, sigma) blocks
+    if they fit, otherwise release one live allocation chosen uniformly.  Afterwards live
+    allocations are released in seeded random order until at least `need_free` blocks are free.
+    Returns the list of (op, size) performed, so two backends can be compared.
+    """
+    live, log = [], []
+    for _ in range(n_ops):
+        want_alloc = rng.random() < 0.5 or not live
+        k = int(np.clip(np.rint(rng.lognormal(np.log(median_blocks), sigma)), 1, None))
+        victim = int(rng.integers(len(live))) if live else 0
+        if want_alloc and k <= backend.n_free():
+            ids = backend.alloc(k)
+            if ids is None:
+                raise RuntimeError("alloc failed although the blocks were free")
+            live.append(list(ids))
+            log.append(("a", k))
+        elif live:
+            backend.free(live.pop(victim))
+            log.append(("f", victim))
+    order = rng.permutation(len(live)) if live else []
+    for i in order:
+        if backend.n_free() >= need_free:
+            break
+        backend.free(live[int(i)])
+        live[int(i)] = None
+        log.append(("r", int(i)))
+    return log

@@ -1,0 +1,54 @@
+"""The C-ABI library loads without a GPU and exports every symbol the header declares."""
+import ctypes
+import os
+import re
+
+import paper_2510_18586_amd as K
+from paper_2510_18586_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "tokencake_kv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"\b(tc_[a-z_0-9]+)\s*\(", text)
+    return sorted(set(names))
+
+
+def test_header_declares_the_expected_calls():
+    names = _declared_functions()
+    for must in ("tc_create", "tc_destroy", "tc_alloc", "tc_free", "tc_offload", "tc_upload",
+                 "tc_offload_batch", "tc_upload_batch", "tc_poll", "tc_sync", "tc_stats"):
+        assert must in names
+
+
+def test_library_exports_every_declared_symbol():
+    lib = ctypes.CDLL(K.library_path()) if os.path.exists(K.library_path()) else binding._load()
+    for name in _declared_functions():
+        assert hasattr(lib, name), f"{name} is declared in the header but not exported"
+
+
+def test_binding_covers_every_declared_symbol():
+    for name in _declared_functions():
+        assert hasattr(K, name), f"the Python binding lacks {name}"
+
+
+def test_error_strings_and_struct_layout():
+    assert K.tc_strerror(K.TC_OK) == "ok"
+    for code in range(-8, 0):
+        assert K.tc_strerror(code) and "unknown" not in K.tc_strerror(code)
+    assert "unknown" in K.tc_strerror(-99)
+    # the ctypes mirrors must match the C layout (checked against sizes the compiler would give)
+    assert ctypes.sizeof(K.tc_pool_desc) == 40
+    assert ctypes.sizeof(K.tc_opts) == 32
+    assert ctypes.sizeof(K.tc_xfer_desc) == 32
+    assert ctypes.sizeof(K.tc_stats_t) == 24 + 16 + 48 + 32 + 16
+
+
+def test_null_arguments_are_rejected_without_a_gpu():
+    lib = binding._load()
+    assert lib.tc_create(None, None, None) == K.TC_ERR_INVAL
+    assert K.tc_sync(None) == K.TC_ERR_INVAL
+    assert K.tc_destroy(None) == K.TC_OK
+    assert K.tc_record_bytes(None) == 0

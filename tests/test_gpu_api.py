@@ -1,0 +1,238 @@
+"""GPU tests of the C ABI around the copies: validation, bookkeeping with real transfers in
+flight, batches, the pinned arena, partial uploads and shared prefix blocks.  Data is always
+compared with the oracle; ids and counters with the oracle's bookkeeping model."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2510_18586_amd as K
+import tc_workloads as W
+from harness import DEV, GpuPool, pinned_bytes
+
+pytestmark = pytest.mark.gpu
+
+SMALL = W.PoolShape("small", 4, 2, 64, 16, 2, 64, 0, "normal")      # 4 KiB pages, 32 KiB records
+
+
+def _stats(gp):
+    rc, st = K.tc_stats(gp.ctx)
+    assert rc == 0
+    return st
+
+
+def test_validation_errors_have_no_effect():
+    rng = W.rng_for(0, salt=11)
+    pool_h = W.make_pool_host(SMALL, rng)
+    gp = GpuPool(SMALL, pool_h, None)
+    try:
+        rec = gp.rec
+        host = pinned_bytes(8 * rec)
+        host.fill_(0x5A)
+        table = torch.full((8,), -9, dtype=torch.int32, device=DEV)
+        K.check(K.tc_alloc_at(gp.ctx, [3, 4, 5, 6]))
+        K.check(K.tc_ref(gp.ctx, [6]))
+        before = _stats(gp).as_dict()
+        cases = [
+            ([3, 64], K.TC_ERR_RANGE), ([-1, 3], K.TC_ERR_RANGE), ([3, 4, 3], K.TC_ERR_DUP),
+            ([3, 7], K.TC_ERR_INVAL), ([3, 6], K.TC_ERR_SHARED),
+        ]
+        for ids, code in cases:
+            assert K.tc_offload(gp.ctx, ids, host) == code
+            assert K.tc_upload(gp.ctx, host, ids, table) == code
+            assert K.tc_offload_batch(gp.ctx, [([5], host), (ids, host.data_ptr() + rec)]) == code
+        pageable = np.zeros(4 * rec, dtype=np.uint8)
+        assert K.tc_offload(gp.ctx, [3, 4], pageable) == K.TC_ERR_NOT_PINNED
+        assert K.tc_upload(gp.ctx, pageable, [3, 4], table) == K.TC_ERR_NOT_PINNED
+        assert K.tc_upload(gp.ctx, host, [3, 4], np.zeros(2, dtype=np.int32)) == K.TC_ERR_NOT_PINNED  # table not device
+        assert K.tc_offload(gp.ctx, [3], None) == K.TC_ERR_INVAL
+        assert K.tc_free(gp.ctx, [7]) == K.TC_ERR_INVAL
+        assert K.tc_free(gp.ctx, [64]) == K.TC_ERR_RANGE
+        assert K.tc_ref(gp.ctx, [7]) == K.TC_ERR_INVAL
+        assert K.tc_alloc(gp.ctx, 61)[0] == K.TC_ERR_NOMEM
+        assert K.tc_alloc_at(gp.ctx, [10, 3]) == K.TC_ERR_NOMEM
+        torch.cuda.synchronize()
+        assert _stats(gp).as_dict() == before
+        assert (host.numpy() == 0x5A).all()
+        assert np.array_equal(gp.pool_to_host(), pool_h)
+        assert (table.cpu().numpy() == -9).all()
+    finally:
+        gp.close()
+
+
+def test_create_rejects_bad_descriptions():
+    pool = torch.zeros(1 << 20, dtype=torch.uint8, device=DEV)
+    host = np.zeros(1 << 20, dtype=np.uint8)
+    assert K.tc_create(pool, None, 0, 8, 4096, 16)[0] == K.TC_ERR_INVAL           # no layers
+    assert K.tc_create(pool, None, 2, 8, 4100, 16)[0] == K.TC_ERR_INVAL           # page not a 16-B multiple
+    assert K.tc_create(pool, None, 2, 8, 4096, 16, 3)[0] == K.TC_ERR_INVAL        # scales_per_block not in {0,1,P}
+    assert K.tc_create(pool, None, 2, 8, 4096, 16, 4)[0] == K.TC_ERR_INVAL        # scales announced, none given
+    assert K.tc_create(pool.data_ptr() + 16, None, 2, 8, 4096, 16)[0] == K.TC_ERR_INVAL   # misaligned
+    assert K.tc_create(pinned_bytes(1 << 20), None, 2, 8, 4096, 16)[0] == K.TC_ERR_NOT_PINNED   # pool is host memory
+
+
+def test_pending_free_blocks_are_not_handed_out_while_the_copy_runs():
+    # 8B-shaped pages; 256 of 300 blocks move (512 MiB, ~10 ms on the link)
+    shape = W.CONFIGS[1].with_blocks(300)
+    gp = GpuPool(shape, seed=5)
+    model = oracle.OracleBlockPool(shape.num_blocks)
+    try:
+        n = 256
+        rc, ids = K.tc_alloc(gp.ctx, 300)
+        assert rc == 0 and list(ids) == model.alloc(300)
+        move = ids[:n]
+        host = pinned_bytes(n * gp.rec)
+        stream = torch.cuda.Stream()
+        K.check(K.tc_offload(gp.ctx, move, host, stream))
+        model.begin_op(list(move))
+        K.check(K.tc_free(gp.ctx, move))
+        model.free(list(move))
+        st = _stats(gp)
+        assert (st.gpu_blocks_pending_free, st.gpu_blocks_free, st.gpu_blocks_used) == (n, 0, 44)
+        assert (model.n_pending(), model.n_free(), model.n_used()) == (n, 0, 44)
+        # the copy was enqueued microseconds ago and takes milliseconds
+        assert K.tc_alloc(gp.ctx, 1)[0] == K.TC_ERR_NOMEM
+        assert K.tc_alloc_at(gp.ctx, move[:1]) == K.TC_ERR_NOMEM
+        stream.synchronize()
+        model.retire_all()
+        rc, again = K.tc_alloc(gp.ctx, n)      # retires the finished transfer itself
+        assert rc == 0 and list(again) == model.alloc(n)
+        assert _stats(gp).gpu_blocks_pending_free == 0
+    finally:
+        gp.close()
+
+
+def test_batch_of_agents_shares_chunks():
+    rng = W.rng_for(2, salt=3)
+    shape = W.CONFIGS[1].with_blocks(128)
+    L, NB, pb, P = shape.num_layers, shape.num_blocks, shape.page_bytes, shape.planes
+    pool_h = W.make_pool_host(shape, rng)
+    sizes = [5, 0, 17, 1, 9, 3]
+    perm = W.pick_ids(rng, NB, 2 * sum(sizes))
+    src = np.split(perm[: sum(sizes)], np.cumsum(sizes)[:-1])
+    dst = np.split(perm[sum(sizes):], np.cumsum(sizes)[:-1])
+    # staging: 3 slots of 4 records, so chunks straddle agents
+    gp = GpuPool(shape, pool_h, None, staging_bytes=3 * 4 * 2 * 1024 * 1024, staging_slots=3,
+                 host_arena_bytes=40 * 2 * 1024 * 1024)
+    try:
+        rec = gp.rec
+        bufs = []
+        for s in sizes:
+            rc, addr = K.tc_host_alloc(gp.ctx, s)
+            assert rc == 0 and (addr is None) == (s == 0)
+            bufs.append(addr)
+        assert _stats(gp).host_slots_used == sum(sizes)
+        assert K.tc_host_alloc(gp.ctx, 6)[0] == K.TC_ERR_HOST_NOMEM     # 40 slots, 35 taken
+        stream = torch.cuda.Stream()
+        K.check(K.tc_alloc_at(gp.ctx, perm[: sum(sizes)]))
+        K.check(K.tc_offload_batch(gp.ctx, list(zip(src, bufs)), stream))
+        K.check(K.tc_free(gp.ctx, perm[: sum(sizes)]))
+        K.check(K.tc_sync(gp.ctx))
+        wants = []
+        for ids, addr, s in zip(src, bufs, sizes):
+            want = np.empty(max(s * rec, 1), dtype=np.uint8)
+            oracle.offload(pool_h, None, L, NB, pb, 0, ids, want)
+            wants.append(want)
+            if s:
+                got = np.ctypeslib.as_array((np.ctypeslib.ctypes.c_uint8 * (s * rec)).from_address(addr))
+                assert np.array_equal(got, want[: s * rec])
+        # upload the whole batch into other blocks, one table row per agent
+        tables = torch.full((len(sizes), 20), -1, dtype=torch.int32, device=DEV)
+        tables_h = np.full((len(sizes), 20), -1, dtype=np.int32)
+        K.check(K.tc_alloc_at(gp.ctx, perm[sum(sizes):]))
+        K.check(K.tc_upload_batch(gp.ctx, [(dst[i], bufs[i], tables[i]) for i in range(len(sizes))], stream))
+        for i, s in enumerate(sizes):
+            oracle.upload(wants[i], L, NB, pb, 0, dst[i], pool_h, None, tables_h[i])
+            K.check(K.tc_host_free(gp.ctx, bufs[i]))      # while the upload may still be reading it
+        stream.synchronize()
+        assert np.array_equal(gp.pool_to_host(), pool_h)
+        assert np.array_equal(tables.cpu().numpy(), tables_h)
+        K.check(K.tc_sync(gp.ctx))
+        st = _stats(gp)
+        assert st.host_slots_used == 0 and st.n_offloads == 1 and st.n_uploads == 1
+        assert st.blocks_offloaded == sum(sizes) and st.bytes_uploaded == sum(sizes) * rec
+    finally:
+        gp.close()
+
+
+def test_partial_uploads_restore_an_agent_piecewise():
+    """Destination blocks arrive in pieces (gradual reservation): records [a, b) of the host buffer
+    are uploaded as they get their blocks; the result equals one whole upload."""
+    rng = W.rng_for(3, salt=4)
+    shape = SMALL
+    L, NB, pb = shape.num_layers, shape.num_blocks, shape.page_bytes
+    pool_h = W.make_pool_host(shape, rng)
+    n = 13
+    ids = W.pick_ids(rng, NB, n)
+    new_ids = W.pick_ids(rng, NB, n, exclude=ids)
+    gp = GpuPool(shape, pool_h, None)
+    try:
+        rec = gp.rec
+        host = pinned_bytes(n * rec)
+        K.check(K.tc_alloc_at(gp.ctx, ids))
+        K.check(K.tc_offload(gp.ctx, ids, host))
+        K.check(K.tc_free(gp.ctx, ids))
+        K.check(K.tc_sync(gp.ctx))
+        want = np.empty(n * rec, dtype=np.uint8)
+        oracle.offload(pool_h, None, L, NB, pb, 0, ids, want)
+        table = torch.full((n,), -1, dtype=torch.int32, device=DEV)
+        table_h = np.full(n, -1, dtype=np.int32)
+        oracle.upload(want, L, NB, pb, 0, new_ids, pool_h, None, table_h)
+        done = 0
+        for piece in (7, 3, 2, 1):      # ceil(deficit / 2) each step
+            part = new_ids[done: done + piece]
+            K.check(K.tc_alloc_at(gp.ctx, part))
+            K.check(K.tc_upload(gp.ctx, host.data_ptr() + done * rec, part, table.data_ptr() + 4 * done))
+            done += piece
+        torch.cuda.synchronize()
+        assert np.array_equal(gp.pool_to_host(), pool_h)
+        assert np.array_equal(table.cpu().numpy(), table_h)
+    finally:
+        gp.close()
+
+
+def test_shared_prefix_blocks_stay_put():
+    rng = W.rng_for(4, salt=5)
+    shape = W.PoolShape("fp8-small", 3, 2, 32, 8, 1, 80, 6, "fp8")
+    L, NB, pb, S = shape.num_layers, shape.num_blocks, shape.page_bytes, shape.scales_per_block
+    pool_h = W.make_pool_host(shape, rng)
+    scales_h = W.make_scales_host(shape, rng)
+    gp = GpuPool(shape, pool_h, scales_h)
+    model = oracle.OracleBlockPool(NB)
+    try:
+        rc, prefix = K.tc_alloc(gp.ctx, 4)
+        assert list(prefix) == model.alloc(4)
+        agents = []
+        for a in range(3):
+            if a:
+                K.check(K.tc_ref(gp.ctx, prefix))
+                model.ref(list(prefix))
+            rc, priv = K.tc_alloc(gp.ctx, 5 + a)
+            assert list(priv) == model.alloc(5 + a)
+            agents.append(np.concatenate([prefix, priv]))
+        assert _stats(gp).gpu_blocks_shared == 4
+        row = agents[1]
+        host = pinned_bytes(len(row) * gp.rec)
+        assert K.tc_offload(gp.ctx, row, host) == K.TC_ERR_SHARED
+        rc, private = K.tc_filter_private(gp.ctx, row)
+        assert rc == 0 and list(private) == model.filter_private(list(row)) == list(row[4:])
+        K.check(K.tc_offload(gp.ctx, private, host))
+        K.check(K.tc_free(gp.ctx, private))
+        K.check(K.tc_sync(gp.ctx))
+        want = np.empty(len(private) * gp.rec, dtype=np.uint8)
+        oracle.offload(pool_h, scales_h, L, NB, pb, S, private, want)
+        assert np.array_equal(host.numpy()[: want.size], want)
+        model.free(list(private))
+        # back into fresh blocks; the table's prefix entries are never written
+        rc, fresh = K.tc_alloc(gp.ctx, len(private))
+        assert list(fresh) == model.alloc(len(private))
+        table = torch.from_numpy(row.copy()).to(DEV)
+        table_h = row.copy()
+        oracle.upload(want, L, NB, pb, S, fresh, pool_h, scales_h, table_h[4:])
+        K.check(K.tc_upload(gp.ctx, host, fresh, table.data_ptr() + 4 * 4))
+        torch.cuda.synchronize()
+        assert np.array_equal(table.cpu().numpy(), table_h) and list(table_h[:4]) == list(prefix)
+        assert np.array_equal(gp.pool_to_host(), pool_h)
+        assert np.array_equal(gp.scales_all_to_host(), scales_h)
+    finally:
+        gp.close()

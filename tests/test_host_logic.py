@@ -1,0 +1,256 @@
+"""The library's host bookkeeping (csrc/tc_blocks.h) against the oracle's model, without a GPU.
+
+The C++ classes are compiled with g++ (address + undefined-behaviour sanitizers on) behind a
+test-only C shim and driven with the same seeded op streams as the oracle's OracleBlockPool /
+OracleHostArena; every returned id, status code and counter must agree.
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+import pytest
+
+import tc_workloads as W
+from oracle import OracleBlockPool, OracleHostArena, OracleError
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(HERE)
+CODE = {"INVAL": -1, "RANGE": -2, "DUP": -3, "SHARED": -4, "NOMEM": -5, "HOST_NOMEM": -6}
+
+
+@pytest.fixture(scope="module")
+def shim(tmp_path_factory):
+    out = str(tmp_path_factory.mktemp("shim") / "libblocks_shim.so")
+    subprocess.run(
+        ["g++", "-std=c++17", "-O1", "-g", "-fPIC", "-shared", "-Wall", "-Wextra", "-Werror",
+         "-fsanitize=undefined", "-fno-sanitize-recover=undefined",
+         "-I", os.path.join(ROOT, "include"), "-I", os.path.join(ROOT, "paper_2510_18586_amd", "csrc"),
+         os.path.join(HERE, "csrc", "blocks_shim.cpp"), "-o", out],
+        check=True)
+    lib = ctypes.CDLL(out)
+    vp, u32, u64 = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint64
+    lib.tcb_pool_new.restype, lib.tcb_pool_new.argtypes = vp, [u32]
+    lib.tcb_pool_del.argtypes = [vp]
+    for f in ("tcb_alloc_at", "tcb_ref", "tcb_free", "tcb_check_transfer", "tcb_begin", "tcb_end"):
+        getattr(lib, f).argtypes = [vp, vp, u32]
+    lib.tcb_alloc.argtypes = [vp, u32, vp]
+    lib.tcb_filter_private.argtypes = [vp, vp, u32, vp, ctypes.POINTER(u32)]
+    lib.tcb_counts.argtypes = [vp, vp]
+    lib.tcb_arena_new.restype, lib.tcb_arena_new.argtypes = vp, [u64]
+    lib.tcb_arena_del.argtypes = [vp]
+    lib.tcb_arena_alloc.restype, lib.tcb_arena_alloc.argtypes = ctypes.c_int64, [vp, u64]
+    lib.tcb_arena_free.argtypes = [vp, u64]
+    lib.tcb_arena_used.restype, lib.tcb_arena_used.argtypes = u64, [vp]
+    lib.tcb_arena_locate.argtypes = [vp, u64, ctypes.POINTER(u64), ctypes.POINTER(u64)]
+    lib.tcb_arena_begin.argtypes = [vp, u64]
+    lib.tcb_arena_end.argtypes = [vp, u64]
+    return lib
+
+
+class NativePool:
+    def __init__(self, lib, nb):
+        self.lib, self.p = lib, lib.tcb_pool_new(nb)
+
+    def __del__(self):
+        self.lib.tcb_pool_del(self.p)
+
+    @staticmethod
+    def _a(ids):
+        a = np.ascontiguousarray(ids, dtype=np.int32)
+        return a, (a.ctypes.data if a.size else None), int(a.size)
+
+    def call(self, name, ids):
+        a, p, n = self._a(ids)
+        return getattr(self.lib, name)(self.p, p, n)
+
+    def alloc(self, n):
+        out = np.empty(max(n, 1), dtype=np.int32)
+        rc = self.lib.tcb_alloc(self.p, n, out.ctypes.data)
+        return rc, list(out[:n]) if rc == 0 else []
+
+    def counts(self):
+        c = np.zeros(4, dtype=np.uint32)
+        self.lib.tcb_counts(self.p, c.ctypes.data)
+        return tuple(int(x) for x in c)
+
+    def filter_private(self, ids):
+        a, p, n = self._a(ids)
+        out = np.empty(max(n, 1), dtype=np.int32)
+        m = ctypes.c_uint32()
+        rc = self.lib.tcb_filter_private(self.p, p, n, out.ctypes.data, ctypes.byref(m))
+        return rc, list(out[:m.value])
+
+
+def _oracle_rc(fn, *a):
+    try:
+        return 0, fn(*a)
+    except OracleError as e:
+        return CODE[e.code], None
+
+
+def _same_counts(nat, orc):
+    assert nat.counts() == (orc.n_free(), orc.n_used(), orc.n_pending(), orc.n_shared())
+
+
+def test_hand_worked_sequence_matches_oracle(shim):
+    nat, orc = NativePool(shim, 8), OracleBlockPool(8)
+    assert nat.alloc(3) == (0, [0, 1, 2]) and orc.alloc(3) == [0, 1, 2]
+    assert nat.call("tcb_free", [1]) == 0
+    orc.free([1])
+    assert nat.alloc(2)[1] == orc.alloc(2) == [1, 3]
+    assert nat.call("tcb_free", [0, 2]) == 0
+    orc.free([0, 2])
+    assert nat.alloc(3)[1] == orc.alloc(3) == [2, 0, 4]
+    assert nat.alloc(4)[0] == CODE["NOMEM"]
+    _same_counts(nat, orc)
+
+
+def test_error_codes_and_no_side_effects(shim):
+    nat, orc = NativePool(shim, 8), OracleBlockPool(8)
+    nat.alloc(3), orc.alloc(3)
+    for ids in ([0, 8], [-1], [0, 1, 0], [0, 5], []):
+        assert nat.call("tcb_check_transfer", ids) == _oracle_rc(orc.check_transfer, ids)[0]
+    assert nat.call("tcb_free", [0, 0]) == _oracle_rc(orc.free, [0, 0])[0] == CODE["INVAL"]
+    assert nat.call("tcb_ref", [4]) == _oracle_rc(orc.ref, [4])[0] == CODE["INVAL"]
+    assert nat.call("tcb_ref", [0, 1]) == 0
+    orc.ref([0, 1])
+    assert nat.call("tcb_check_transfer", [2, 1]) == _oracle_rc(orc.check_transfer, [2, 1])[0] == CODE["SHARED"]
+    assert nat.filter_private([0, 1, 2]) == (0, orc.filter_private([0, 1, 2]))
+    assert nat.call("tcb_alloc_at", [4, 0]) == _oracle_rc(orc.alloc_at, [4, 0])[0] == CODE["NOMEM"]
+    assert nat.call("tcb_alloc_at", [4, 4]) == _oracle_rc(orc.alloc_at, [4, 4])[0] == CODE["DUP"]
+    _same_counts(nat, orc)
+    assert nat.call("tcb_free", [0, 0]) == 0   # two references now: both may be dropped at once
+    orc.free([0, 0])
+    _same_counts(nat, orc)
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_random_op_stream_id_for_id(shim, seed):
+    rng = np.random.default_rng(seed)
+    NB = 113
+    nat, orc = NativePool(shim, NB), OracleBlockPool(NB)
+    held, ops = [], []
+    for _ in range(8000):
+        r = rng.random()
+        if r < 0.30:
+            n = int(rng.integers(0, 14))
+            rc, got = nat.alloc(n)
+            rco, want = _oracle_rc(orc.alloc, n)
+            assert rc == rco and (rc != 0 or got == want)
+            if rc == 0 and got:
+                held.append(got)
+        elif r < 0.40 and orc.n_free():
+            k = int(rng.integers(1, 6))
+            ids = [int(x) for x in rng.choice(NB, size=k, replace=bool(rng.random() < 0.2))]
+            rc, rco = nat.call("tcb_alloc_at", ids), _oracle_rc(orc.alloc_at, ids)[0]
+            assert rc == rco
+            if rc == 0:
+                held.append(ids)
+        elif r < 0.50 and held:
+            ids = held[int(rng.integers(len(held)))]
+            assert nat.call("tcb_ref", ids) == 0
+            orc.ref(ids)
+            held.append(list(ids))
+        elif r < 0.75 and held:
+            ids = held.pop(int(rng.integers(len(held))))
+            if rng.random() < 0.5:
+                rc, rco = nat.call("tcb_check_transfer", ids), _oracle_rc(orc.check_transfer, ids)[0]
+                assert rc == rco
+                if rc == 0:
+                    nat.call("tcb_begin", ids)
+                    orc.begin_op(ids)
+                    ops.append(ids)
+            assert nat.call("tcb_free", ids) == 0
+            orc.free(ids)
+        elif r < 0.90 and ops:
+            ids = ops.pop(0)
+            nat.call("tcb_end", ids)
+            orc.retire_oldest()
+        _same_counts(nat, orc)
+        f, u, p, _ = nat.counts()
+        assert f + u + p == NB
+    while ops:
+        nat.call("tcb_end", ops.pop(0))
+        orc.retire_oldest()
+    # whatever is free now comes out in the same order on both sides
+    n = orc.n_free()
+    assert nat.alloc(n)[1] == orc.alloc(n)
+
+
+def test_fragmentation_script_same_ids_on_both_sides(shim):
+    """The config-3 fragmentation recipe (seeded alloc/free ops) run against both allocators."""
+    NB = 2048
+    nat, orc = NativePool(shim, NB), OracleBlockPool(NB)
+
+    class Nat:
+        def alloc(self, n):
+            rc, ids = nat.alloc(n)
+            return ids if rc == 0 else None
+
+        def free(self, ids):
+            assert nat.call("tcb_free", ids) == 0
+
+        def n_free(self):
+            return nat.counts()[0]
+
+    class Orc:
+        def alloc(self, n):
+            try:
+                return orc.alloc(n)
+            except OracleError:
+                return None
+
+        def free(self, ids):
+            orc.free(ids)
+
+        def n_free(self):
+            return orc.n_free()
+
+    a = W.fragment_pool(Nat(), W.rng_for(2, salt=9), n_ops=4000, median_blocks=16, need_free=900)
+    b = W.fragment_pool(Orc(), W.rng_for(2, salt=9), n_ops=4000, median_blocks=16, need_free=900)
+    assert a == b
+    _same_counts(nat, orc)
+    n = orc.n_free()
+    ids_n, ids_o = nat.alloc(n)[1], orc.alloc(n)
+    assert ids_n == ids_o
+    assert ids_n != sorted(ids_n), "the free list should be fragmented, not ascending"
+
+
+def test_host_arena_matches_oracle(shim):
+    rng = np.random.default_rng(5)
+    N = 300
+    a, o = shim.tcb_arena_new(N), OracleHostArena(N)
+    live, busy = [], []
+    try:
+        for _ in range(5000):
+            r = rng.random()
+            if r < 0.45:
+                n = int(rng.integers(1, 40))
+                got = shim.tcb_arena_alloc(a, n)
+                rco, want = _oracle_rc(o.alloc, n)
+                assert (got < 0) == (rco != 0)
+                if rco == 0:
+                    assert got == want
+                    live.append((got, n))
+            elif r < 0.60 and live:
+                s, n = live[int(rng.integers(len(live)))]
+                slot = s + int(rng.integers(n))
+                st, room = ctypes.c_uint64(), ctypes.c_uint64()
+                assert shim.tcb_arena_locate(a, slot, ctypes.byref(st), ctypes.byref(room)) == 1
+                assert st.value == o.owner_of(slot) == s and room.value == s + n - slot
+                shim.tcb_arena_begin(a, s)
+                o.begin_op(s)
+                busy.append(s)
+            elif r < 0.85 and live:
+                s, n = live.pop(int(rng.integers(len(live))))
+                assert shim.tcb_arena_free(a, s) == 0
+                o.free(s)
+                assert shim.tcb_arena_free(a, s) == CODE["INVAL"]     # second release is refused
+            elif busy:
+                s = busy.pop(0)
+                shim.tcb_arena_end(a, s)
+                o.end_op(s)
+            assert shim.tcb_arena_used(a) == o.used_slots()
+    finally:
+        shim.tcb_arena_del(a)
