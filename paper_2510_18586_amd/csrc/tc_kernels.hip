@@ -133,9 +133,12 @@ static hipError_t launch_page_copy(void *pool, uint32_t *scales, void *staging, 
     // widest tile that a page still fills
     int U = 8;
     while (U > 1 && uint64_t(kThreads) * U > g.page16) U >>= 1;
-    // Measured on MI355X (512 MiB per launch): non-temporal loads help both directions; non-temporal
-    // stores help the contiguous staging writes of the gather (5.2 -> 6.0 TB/s) but hurt the scattered
-    // page writes of the scatter (6.6 -> 5.4 TB/s).
+    // Cache policy, measured on MI355X with cold 512 MiB launches in the offload -> upload sequence:
+    // non-temporal loads help both directions.  The gather's staging writes stay ordinary
+    // write-back stores: they are absorbed by the memory-side cache and drain to HBM while the
+    // slow host-link DMA that follows reads them.  The scatter's page writes are non-temporal, so
+    // it leaves no dirty lines for the next kernel to evict (with ordinary stores the scatter looks
+    // faster and the following gather pays for it; the sum is worse).
     const uint32_t tile16 = kThreads * U;
     const uint32_t tiles = (g.page16 + tile16 - 1) / tile16;
     const uint64_t items64 = uint64_t(n) * g.planes * tiles;
@@ -155,8 +158,8 @@ static hipError_t launch_page_copy(void *pool, uint32_t *scales, void *staging, 
     case 2: TC_LAUNCH(2, NL, NS); break;     \
     default: TC_LAUNCH(1, NL, NS); break;    \
     }
-    if (GATHER) { TC_LAUNCH_U(true, true) }
-    else { TC_LAUNCH_U(true, false) }
+    if (GATHER) { TC_LAUNCH_U(true, false) }
+    else { TC_LAUNCH_U(true, true) }
 #undef TC_LAUNCH_U
 #undef TC_LAUNCH
     return hipGetLastError();
