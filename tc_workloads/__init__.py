@@ -197,3 +197,46 @@ def fragment_pool(backend, rng, n_ops=50000, median_blocks=128, sigma=0.8, need_
         live[int(i)] = None
         log.append(("r", int(i)))
     return log
+
+
+def dag_trace(rng, n_agents=200, depth=6, mean_call_s=2.0, predicted_s=2.0, lead_s=0.2,
+              median_tokens=2048, sigma=0.8, cap_tokens=16384, block_size=16):
+    """A seeded trace of agents in a random DAG, each making one function call.
+
+    Nodes are spread over `depth` levels (at least one per level, the rest uniformly); every node
+    below level 0 gets 1-3 parents drawn from the level above and starts when all of them have
+    finished.  An agent computes for c1 seconds, calls a tool for d ~ Exp(mean_call_s) seconds and
+    computes c2 seconds more.  The predictor is the constant `predicted_s`, so the upload is due
+    `lead_s` before the predicted finish, or at the real finish when the tool returns earlier.
+
+    Returns (agents, events): agents[i] = dict(blocks, level, parents, ...), events = list of
+    (time, order, kind, agent) sorted by virtual time; kind in start / call_start / upload_due /
+    call_finish / finish.  Virtual time orders the calls; nothing sleeps.
+    """
+    levels = np.concatenate([np.arange(depth), rng.integers(0, depth, size=n_agents - depth)])
+    levels.sort()
+    by_level = [np.flatnonzero(levels == l) for l in range(depth)]
+    tokens = lognormal_contexts(rng, n_agents, median_tokens, sigma, cap_tokens)
+    agents, finish = [], np.zeros(n_agents)
+    events = []
+    order = {"finish": 0, "call_finish": 1, "start": 2, "call_start": 3, "upload_due": 4}
+    for i in range(n_agents):
+        l = int(levels[i])
+        parents = []
+        if l > 0:
+            k = int(rng.integers(1, 4))
+            parents = sorted(int(x) for x in rng.choice(by_level[l - 1], size=min(k, len(by_level[l - 1])), replace=False))
+        c1, c2 = float(rng.uniform(0.05, 0.5)), float(rng.uniform(0.05, 0.3))
+        d = float(rng.exponential(mean_call_s))
+        t_start = max([finish[p] for p in parents], default=0.0)
+        t_call = t_start + c1
+        t_ret = t_call + d
+        t_up = min(t_call + max(0.0, predicted_s - lead_s), t_ret)
+        finish[i] = t_ret + c2
+        agents.append(dict(blocks=int(blocks_of(tokens[i], block_size)), tokens=int(tokens[i]), level=l,
+                           parents=parents, call_s=d, early=bool(d < predicted_s - lead_s)))
+        for t, kind in ((t_start, "start"), (t_call, "call_start"), (t_up, "upload_due"),
+                        (t_ret, "call_finish"), (finish[i], "finish")):
+            events.append((float(t), order[kind], kind, i))
+    events.sort(key=lambda e: (e[0], e[1], e[3]))
+    return agents, events

@@ -36,6 +36,16 @@ class GpuPool:
         if self.ctx:
             K.check(K.tc_destroy(self.ctx))
             self.ctx = None
+        self.pool = self.scales = None
+        torch.cuda.empty_cache()
+
+    def block_checksums(self, ids):
+        """[P][len(ids)] int64 page checksums (+ scale words as extra rows): torch only."""
+        idx = torch.as_tensor(np.asarray(ids, dtype=np.int64), device=DEV)
+        cs = self.pool.view(torch.int32).view(self.P, self.NB, self.pb // 4)[:, idx].sum(dim=2, dtype=torch.int64)
+        if self.S:
+            cs = torch.cat([cs, self.scales.view(self.S, self.NB)[:, idx].to(torch.int64)], dim=0)
+        return cs
 
     # ---- views / copies (torch only) --------------------------------------
     def pool3(self):
@@ -67,24 +77,50 @@ def pinned_bytes(n):
 
 class SparseMirror:
     """Host mirror of a full-size pool holding only the blocks a test touches, at their true
-    offsets (untouched pages of the anonymous mapping are never materialised)."""
+    offsets: an anonymous no-reserve mapping, so untouched pages are never materialised.
+    close() returns the memory."""
 
-    def __init__(self, gp, ids):
+    def __init__(self, gp, ids=()):
+        import mmap
         self.gp = gp
-        self.pool = np.empty(gp.P * gp.NB * gp.pb, dtype=np.uint8)
-        self.scales = np.empty(gp.S * gp.NB, dtype=np.uint32) if gp.S else None
-        self.load(ids)
+        flags = mmap.MAP_PRIVATE | mmap.MAP_ANONYMOUS | getattr(mmap, "MAP_NORESERVE", 0)
+        self._mm = [mmap.mmap(-1, gp.P * gp.NB * gp.pb, flags=flags)]
+        self.pool = np.frombuffer(self._mm[0], dtype=np.uint8)
+        self.scales = None
+        if gp.S:
+            self._mm.append(mmap.mmap(-1, 4 * gp.S * gp.NB, flags=flags))
+            self.scales = np.frombuffer(self._mm[1], dtype=np.uint32)
+        if len(ids):
+            self.load(ids)
 
     def load(self, ids):
+        """Copies the current device content of these blocks (and their scale words) into the mirror."""
         gp = self.gp
         ids = np.asarray(ids, dtype=np.int64)
-        step = 64
         v = self.pool.reshape(gp.P, gp.NB, gp.pb)
-        for a in range(0, ids.size, step):
-            sub = ids[a:a + step]
+        for a in range(0, ids.size, 64):
+            sub = ids[a:a + 64]
             v[:, sub] = gp.blocks_to_host(sub)
             if gp.S:
                 self.scales.reshape(gp.S, gp.NB)[:, sub] = gp.scales_to_host(sub)
 
     def blocks(self, ids):
         return self.pool.reshape(self.gp.P, self.gp.NB, self.gp.pb)[:, np.asarray(ids, dtype=np.int64)]
+
+    def scale_words(self, ids):
+        return self.scales.reshape(self.gp.S, self.gp.NB)[:, np.asarray(ids, dtype=np.int64)]
+
+    def close(self):
+        self.pool = self.scales = None
+        for m in self._mm:
+            try:
+                m.close()
+            except BufferError:
+                pass
+        self._mm = []
+
+
+def host_view(addr, nbytes):
+    """numpy view of pinned memory the library handed out (tc_host_alloc)."""
+    import ctypes
+    return np.ctypeslib.as_array((ctypes.c_uint8 * int(nbytes)).from_address(int(addr)))

@@ -1,0 +1,373 @@
+"""Benchmark configurations 3, 4 and 5 at full size on the GPU, through the C ABI.
+
+Ids, counters and error codes are compared with the oracle's bookkeeping model call by call.
+Data: every agent's round trip is checked through torch-computed page checksums (what its table
+addresses before the offload is what the rewritten table addresses after the upload, every page
+outside the destination set is unchanged); a sample of agents is compared byte for byte with the
+oracle's records and uploaded blocks on a sparse host mirror of the pool.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2510_18586_amd as K
+import tc_workloads as W
+from harness import DEV, GpuPool, SparseMirror, host_view
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(f"[configs] {msg}", flush=True)
+
+
+CODE = {"INVAL": -1, "RANGE": -2, "DUP": -3, "SHARED": -4, "NOMEM": -5, "HOST_NOMEM": -6}
+
+
+class LockStep:
+    """Runs every bookkeeping call on the library and on the model and insists they agree."""
+
+    def __init__(self, gp):
+        self.gp, self.ctx = gp, gp.ctx
+        self.model = oracle.OracleBlockPool(gp.NB)
+
+    def alloc(self, n):
+        rc, ids = K.tc_alloc(self.ctx, n)
+        try:
+            want = self.model.alloc(n)
+        except oracle.OracleError as e:
+            assert rc == CODE[e.code]
+            return None
+        assert rc == 0 and ids.tolist() == want
+        return ids
+
+    def free(self, ids):
+        assert K.tc_free(self.ctx, ids) == 0
+        self.model.free(list(ids))
+
+    def ref(self, ids):
+        assert K.tc_ref(self.ctx, ids) == 0
+        self.model.ref(list(ids))
+
+    def n_free(self):
+        return self.model.n_free()
+
+    def begin(self, ids):
+        self.model.begin_op(list(ids))
+
+    def sync(self):
+        K.check(K.tc_sync(self.ctx))
+        self.model.retire_all()
+
+    def check_counters(self):
+        rc, st = K.tc_stats(self.ctx)
+        assert rc == 0
+        m = self.model
+        assert (st.gpu_blocks_free, st.gpu_blocks_used, st.gpu_blocks_pending_free, st.gpu_blocks_shared) == \
+               (m.n_free(), m.n_used(), m.n_pending(), m.n_shared())
+        return st
+
+
+def _oracle_records(gp, mirror, ids):
+    want = np.empty(len(ids) * gp.rec, dtype=np.uint8)
+    oracle.offload(mirror.pool, mirror.scales, gp.L, gp.NB, gp.pb, gp.S, np.asarray(ids, dtype=np.int32), want)
+    return want
+
+
+# ------------------------------------------------------------------------------------ config 3
+def test_config3_64_agents_fragmented_pool_overlapped_with_hbm_stream():
+    """8B-shaped pool (32 GiB), 64 agents with lognormal contexts (median 2 048, sigma 0.8, cap 16 384
+    tokens), pool fragmented by 50 000 seeded alloc/free ops, all agents offloaded concurrently while
+    an HBM-streaming kernel runs on another stream; then uploaded into newly allocated blocks."""
+    shape = W.CONFIGS[2]
+    rng = W.rng_for(2)
+    tokens = W.lognormal_contexts(rng, 64)
+    nblk = W.blocks_of(tokens, shape.block_size).astype(int)
+    total = int(nblk.sum())
+    rec = 2 * shape.num_layers * shape.page_bytes
+    gp = GpuPool(shape, seed=W.seed_for(2), host_arena_bytes=(total + 8) * rec)
+    mirrors = []
+    try:
+        ls = LockStep(gp)
+        say(f"config 3: pool ready, {total} blocks to move; fragmenting")
+        W.fragment_pool(ls, rng, n_ops=50000, need_free=total)
+        ls.check_counters()
+        agents = [ls.alloc(int(n)) for n in nblk]
+        assert all(a is not None for a in agents)
+        spread = np.diff(np.sort(agents[int(np.argmax(nblk))]))
+        assert (spread > 1).any(), "fragmentation should scatter an agent's blocks"
+        bufs = [K.tc_host_alloc(gp.ctx, int(n)) for n in nblk]
+        assert all(rc == 0 for rc, _ in bufs)
+        bufs = [addr for _, addr in bufs]
+
+        before = gp.page_checksums()
+        sample = sorted({int(np.argmax(nblk)), int(np.argmin(nblk)), *[int(x) for x in rng.choice(64, 4, replace=False)]})
+        mirror = SparseMirror(gp)
+        mirrors.append(mirror)
+        for i in sample:
+            mirror.load(agents[i])
+        wants = {i: _oracle_records(gp, mirror, agents[i]) for i in sample}
+
+        # the neighbour on the compute stream: fp32 triad over 3 x 1 GiB, s = 0.5 keeps it exact
+        m = 1 << 28
+        b = torch.rand(m, device=DEV)
+        c = torch.rand(m, device=DEV)
+        a = torch.zeros(m, device=DEV)
+        compute, copy = torch.cuda.Stream(), torch.cuda.Stream()
+        torch.cuda.synchronize()
+        K.check(K.tc_hbm_stream(a, b, c, m, 0.5, 40, compute))
+        for i in range(32):                      # back-to-back single calls ...
+            K.check(K.tc_offload(gp.ctx, agents[i], bufs[i], copy))
+            ls.begin(agents[i])
+        K.check(K.tc_offload_batch(gp.ctx, [(agents[i], bufs[i]) for i in range(32, 64)], copy))   # ... and one batch
+        ls.begin(np.concatenate(agents[32:]))
+        for i in range(64):
+            ls.free(agents[i])
+        st = ls.check_counters()
+        assert st.gpu_blocks_pending_free == total
+        ls.sync()
+        torch.cuda.synchronize()
+        say("config 3: offloads done; checking records")
+        assert torch.equal(a, b + 0.5 * c), "the neighbour kernel's result was disturbed"
+        assert torch.equal(gp.page_checksums(), before), "offload wrote the pool"
+        del a, b, c
+
+        # every record page of every agent against the device checksums; sampled agents byte for byte
+        for i in range(64):
+            h = host_view(bufs[i], int(nblk[i]) * rec)
+            cs = h.view(np.int32).reshape(int(nblk[i]), gp.P, gp.pb // 4).sum(axis=2, dtype=np.int64)
+            want_cs = before[:, torch.as_tensor(agents[i].astype(np.int64), device=DEV)].cpu().numpy().T
+            assert np.array_equal(cs, want_cs), f"agent {i}: host records differ"
+            if i in wants:
+                assert np.array_equal(h, wants[i]), f"agent {i}: host records differ from the oracle"
+
+        # upload everything into newly allocated blocks, one table row per agent
+        say("config 3: uploading")
+        new = [ls.alloc(int(n)) for n in nblk]
+        tables = torch.full((64, int(nblk.max()) + 1), -1, dtype=torch.int32, device=DEV)
+        K.check(K.tc_upload_batch(gp.ctx, [(new[i], bufs[i], tables[i]) for i in range(64)], copy))
+        ls.begin(np.concatenate(new))
+        for i in range(64):
+            K.check(K.tc_host_free(gp.ctx, bufs[i]))
+        ls.sync()
+        after = gp.page_checksums()
+        touched = torch.zeros(gp.NB, dtype=torch.bool, device=DEV)
+        for i in range(64):
+            src = torch.as_tensor(agents[i].astype(np.int64), device=DEV)
+            dst = torch.as_tensor(new[i].astype(np.int64), device=DEV)
+            assert torch.equal(after[:, dst], before[:, src]), f"agent {i}: uploaded pages differ"
+            row = tables[i].cpu().numpy()
+            assert np.array_equal(row[: nblk[i]], new[i]) and (row[nblk[i]:] == -1).all()
+            touched[dst] = True
+        assert torch.equal(after[:, ~touched], before[:, ~touched]), "a block outside the destinations changed"
+        for i in sample:
+            t = np.full(int(nblk[i]), -1, dtype=np.int32)
+            oracle.upload(wants[i], gp.L, gp.NB, gp.pb, 0, new[i], mirror.pool, None, t)
+            assert np.array_equal(gp.blocks_to_host(new[i]), mirror.blocks(new[i])), f"agent {i}: blocks differ from the oracle"
+        rc, st = K.tc_stats(gp.ctx)
+        assert st.host_slots_used == 0 and st.blocks_offloaded == total and st.blocks_uploaded == total
+    finally:
+        for mr in mirrors:
+            mr.close()
+        gp.close()
+
+
+# ------------------------------------------------------------------------------------ config 4
+def test_config4_trace_replay_200_agents():
+    """32B-shaped pool (64 layers, 4 MiB per block, 64 GiB): replay of a seeded trace of 200 agents in
+    a random DAG of depth 6; every call offloads, the upload is issued 200 ms (virtual) before the
+    predicted finish or at the finish when the tool returns early; a 16 GiB arena forces some
+    'CPU capacity insufficient' rejections."""
+    shape = W.CONFIGS[3]
+    rng = W.rng_for(3)
+    agents, events = W.dag_trace(rng, block_size=shape.block_size)
+    rec = 2 * shape.num_layers * shape.page_bytes
+    gp = GpuPool(shape, seed=W.seed_for(3), host_arena_bytes=4096 * rec)
+    mirror = None
+    try:
+        ls = LockStep(gp)
+        arena = oracle.OracleHostArena(4096)
+        stream = torch.cuda.Stream()
+        tables = torch.full((len(agents), 1024 + 1), -1, dtype=torch.int32, device=DEV)
+        sample = set(int(x) for x in rng.choice(len(agents), 8, replace=False))
+        mirror = SparseMirror(gp)
+        st8 = [dict(state="new") for _ in agents]
+        counts = dict(offloads=0, rejected=0, predictive=0, immediate=0)
+
+        def upload(i):
+            s = st8[i]
+            ls.sync()                                   # retire: deterministic free list on both sides
+            new = ls.alloc(agents[i]["blocks"])
+            if new is None:
+                return False
+            if i in sample:                             # the offload has completed: compare its records
+                assert np.array_equal(host_view(s["buf"], len(new) * rec), s["want"]), f"agent {i}: records differ"
+            K.check(K.tc_upload(gp.ctx, s["buf"], new, tables[i], stream))
+            ls.begin(new)
+            K.check(K.tc_host_free(gp.ctx, s["buf"]))   # recycled when the upload retires
+            arena.begin_op(s["slot"])
+            arena.free(s["slot"])
+            arena.end_op(s["slot"])                     # the model has no clock: released at once
+            s.update(state="uploaded", ids=new)
+            return True
+
+        say("config 4: pool ready; replaying 1000 events")
+        for e_no, (t, _, kind, i) in enumerate(events):
+            if e_no % 100 == 0:
+                say(f"config 4: event {e_no}, virtual t = {t:.2f} s, {counts}")
+            s, n = st8[i], agents[i]["blocks"]
+            if kind == "start":
+                ids = ls.alloc(n)
+                assert ids is not None, "the pool is sized for the trace's peak"
+                tables[i, :n] = torch.from_numpy(ids).to(DEV)
+                s.update(state="running", ids=ids)
+            elif kind == "call_start":
+                ls.sync()                               # finished uploads hand their arena slots back
+                rc, buf = K.tc_host_alloc(gp.ctx, n)
+                try:
+                    slot = arena.alloc(n)
+                except oracle.OracleError:
+                    assert rc == K.TC_ERR_HOST_NOMEM
+                    counts["rejected"] += 1
+                    s["state"] = "kept"                 # CPU capacity insufficient: the KV stays on the GPU
+                    continue
+                assert rc == 0 and buf == K.tc_arena_base(gp.ctx) + slot * rec
+                s.update(sig=gp.block_checksums(s["ids"]), buf=buf, slot=slot, src=s["ids"])
+                if i in sample:
+                    mirror.load(s["ids"])
+                    s["want"] = _oracle_records(gp, mirror, s["ids"])
+                K.check(K.tc_offload(gp.ctx, s["ids"], buf, stream))
+                ls.begin(s["ids"])
+                ls.free(s["ids"])
+                s["state"] = "offloaded"
+                counts["offloads"] += 1
+            elif kind == "upload_due":
+                if s["state"] == "offloaded" and upload(i):
+                    counts["predictive" if not agents[i]["early"] else "immediate"] += 1
+            elif kind == "call_finish":
+                if s["state"] == "offloaded":           # the tool returned before the upload could be issued
+                    assert upload(i), "an immediate upload must find blocks"
+                    counts["immediate"] += 1
+                if s["state"] == "uploaded":
+                    stream.synchronize()
+                    row = tables[i].cpu().numpy()
+                    assert np.array_equal(row[:n], s["ids"]) and (row[n:] == -1).all()
+                    assert torch.equal(gp.block_checksums(s["ids"]), s["sig"]), f"agent {i}: KV changed in the round trip"
+                    if i in sample:
+                        tbl = np.full(n, -1, dtype=np.int32)
+                        oracle.upload(s["want"], gp.L, gp.NB, gp.pb, 0, s["ids"], mirror.pool, None, tbl)
+                        assert np.array_equal(gp.blocks_to_host(s["ids"]), mirror.blocks(s["ids"]))
+                        assert np.array_equal(tbl, s["ids"])
+                    s["state"] = "running"
+            elif kind == "finish":
+                assert s["state"] in ("running", "kept")
+                ls.free(s["ids"])
+                s["state"] = "done"
+        ls.sync()
+        st = ls.check_counters()
+        assert st.gpu_blocks_free == gp.NB and st.host_slots_used == 0 and arena.used_slots() == 0
+        assert counts["offloads"] + counts["rejected"] == len(agents)
+        assert counts["predictive"] + counts["immediate"] == counts["offloads"]
+        assert counts["rejected"] > 0 and counts["predictive"] > 0 and counts["immediate"] > 0
+        assert st.n_offloads == counts["offloads"] == st.n_uploads
+    finally:
+        if mirror:
+            mirror.close()
+        gp.close()
+
+
+# ------------------------------------------------------------------------------------ config 5
+def test_config5_fp8_shared_prefix_waves():
+    """70B-shaped fp8 pool (80 layers, 32-token blocks, one fp32 scale per page; 32 768 blocks, 160 GiB):
+    128 agents share 32 refcounted prefix blocks that must not move; only private suffix blocks travel;
+    contexts uniform 1k..32k tokens; agents run in waves that fit the pool and a 32 GiB arena."""
+    shape = W.CONFIGS[4]
+    rng = W.rng_for(4)
+    rec = oracle.record_bytes(shape.num_layers, shape.page_bytes, shape.scales_per_block)
+    arena_slots = (32 << 30) // rec
+    gp = GpuPool(shape, seed=W.seed_for(4), host_arena_bytes=arena_slots * rec)
+    try:
+        assert gp.rec == rec == 5 * 1024 * 1024 + 768
+        ls = LockStep(gp)
+        W.fragment_pool(ls, rng, n_ops=3000, median_blocks=256, need_free=gp.NB)   # scrambles the free list
+        ls.check_counters()
+        n_agents, n_prefix = 128, 1024 // shape.block_size
+        prefix = ls.alloc(n_prefix)
+        for _ in range(n_agents - 1):
+            ls.ref(prefix)
+        assert ls.check_counters().gpu_blocks_shared == n_prefix
+        tokens = W.uniform_contexts(rng, n_agents)
+        private = (W.blocks_of(tokens, shape.block_size) - n_prefix).astype(int)
+        assert private.min() >= 0 and private.max() <= 992
+        prefix_sig = gp.block_checksums(prefix)
+        stream = torch.cuda.Stream()
+        tables = torch.full((n_agents, 1024), -1, dtype=torch.int32, device=DEV)
+        tables[:, :n_prefix] = torch.from_numpy(prefix).to(DEV)
+        sampled = 0
+        i = 0
+        n_waves = 0
+        while i < n_agents:
+            wave, used = [], 0
+            while i < n_agents and used + private[i] <= min(arena_slots, ls.n_free()):
+                wave.append(i)
+                used += int(private[i])
+                i += 1
+            assert wave, "an agent does not fit an empty pool / arena"
+            n_waves += 1
+            say(f"config 5: wave {n_waves}: agents {wave[0]}..{wave[-1]}, {used} private blocks")
+            ids = {a: ls.alloc(int(private[a])) for a in wave}
+            bufs = {}
+            for a in wave:
+                rc, bufs[a] = K.tc_host_alloc(gp.ctx, int(private[a]))
+                assert rc == 0
+                tables[a, n_prefix:n_prefix + private[a]] = torch.from_numpy(ids[a]).to(DEV)
+            # the whole row must be refused, the private part is what moves
+            a0 = max(wave, key=lambda a: private[a])
+            row = np.concatenate([prefix, ids[a0]])
+            assert K.tc_offload(gp.ctx, row, bufs[a0], stream) == K.TC_ERR_SHARED
+            assert K.tc_offload(gp.ctx, prefix[:1], bufs[a0], stream) == K.TC_ERR_SHARED
+            rc, priv = K.tc_filter_private(gp.ctx, row)
+            assert rc == 0 and np.array_equal(priv, ids[a0])
+            sigs = {a: gp.block_checksums(ids[a]) for a in wave}
+            pick = min(wave, key=lambda a: abs(int(private[a]) - 200)) if sampled < 4 else None
+            mirror = want = None
+            if pick is not None and private[pick] > 0:
+                mirror = SparseMirror(gp, ids[pick])
+                want = _oracle_records(gp, mirror, ids[pick])
+                sampled += 1
+            K.check(K.tc_offload_batch(gp.ctx, [(ids[a], bufs[a]) for a in wave], stream))
+            ls.begin(np.concatenate([ids[a] for a in wave]))
+            for a in wave:
+                ls.free(ids[a])
+            ls.sync()
+            if want is not None:
+                assert np.array_equal(host_view(bufs[pick], private[pick] * rec), want), f"agent {pick}: records differ"
+            new = {a: ls.alloc(int(private[a])) for a in wave}
+            K.check(K.tc_upload_batch(
+                gp.ctx, [(new[a], bufs[a], tables[a].data_ptr() + 4 * n_prefix) for a in wave], stream))
+            ls.begin(np.concatenate([new[a] for a in wave]))
+            for a in wave:
+                K.check(K.tc_host_free(gp.ctx, bufs[a]))
+            ls.sync()
+            rows = tables[wave[0]: wave[-1] + 1].cpu().numpy()
+            for k, a in enumerate(wave):
+                assert np.array_equal(rows[k, :n_prefix], prefix), "prefix entries were written"
+                assert np.array_equal(rows[k, n_prefix:n_prefix + private[a]], new[a])
+                assert (rows[k, n_prefix + private[a]:] == -1).all()
+                assert torch.equal(gp.block_checksums(new[a]), sigs[a]), f"agent {a}: KV or scales changed"
+            if want is not None:
+                tbl = np.full(int(private[pick]), -1, dtype=np.int32)
+                oracle.upload(want, gp.L, gp.NB, gp.pb, gp.S, new[pick], mirror.pool, mirror.scales, tbl)
+                assert np.array_equal(gp.blocks_to_host(new[pick]), mirror.blocks(new[pick]))
+                assert np.array_equal(gp.scales_to_host(new[pick]), mirror.scale_words(new[pick]))
+                mirror.close()
+            assert torch.equal(gp.block_checksums(prefix), prefix_sig), "shared prefix blocks changed"
+            for a in wave:
+                ls.free(new[a])
+            ls.check_counters()
+        assert n_waves > 1 and sampled >= 2
+        rc, st = K.tc_stats(gp.ctx)
+        assert st.blocks_offloaded == st.blocks_uploaded == int(private.sum()) and st.host_slots_used == 0
+    finally:
+        gp.close()
