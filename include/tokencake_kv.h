@@ -68,10 +68,9 @@ typedef struct {
 typedef struct {
     uint64_t host_arena_bytes;  /* pinned arena, allocated once; 0 = none (caller brings buffers)  */
     uint64_t staging_bytes;     /* device staging ring in total; 0 = default                       */
-    uint32_t staging_slots;     /* ring depth, >= 2; 0 = default                                   */
+    uint32_t staging_slots;     /* ring depth, >= 1; 0 = default                                   */
     uint32_t max_grid;          /* cap on workgroups per gather/scatter launch; 0 = one per tile   */
-    uint32_t ramp;              /* 1 = start an offload / end an upload with small chunks          */
-    uint32_t reserved;
+    uint32_t reserved[2];       /* must be 0                                                       */
 } tc_opts;
 
 typedef struct {
@@ -92,11 +91,14 @@ typedef struct {
     uint64_t gather_launches, scatter_launches;
     uint64_t gather_bytes, scatter_bytes;     /* record bytes the timed launches moved one way     */
     double gather_ms, scatter_ms;             /* sum of per-launch durations from HIP events       */
+    uint64_t d2h_copies, h2d_copies;          /* timed DMA chunks (all copies of one chunk together) */
+    uint64_t d2h_bytes, h2d_bytes;
+    double d2h_ms, h2d_ms;                    /* event pairs on the stream around each chunk's DMAs */
 } tc_stats_t;
 
 /* ---- life cycle ------------------------------------------------------------------------- */
 /* Binds a pool (Sec. 6.3: the block pool owns the GPU<->CPU mapping).  Allocates the staging
- * ring, the pinned arena and a private copy stream; `opts` may be NULL for defaults. */
+ * ring and the pinned arena; `opts` may be NULL for defaults. */
 int tc_create(const tc_pool_desc *pool, const tc_opts *opts, tc_ctx **out);
 /* Waits for every transfer in flight, then frees what the context owns. */
 int tc_destroy(tc_ctx *ctx);

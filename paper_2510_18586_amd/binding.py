@@ -39,7 +39,7 @@ class tc_opts(ctypes.Structure):
     _fields_ = [
         ("host_arena_bytes", ctypes.c_uint64), ("staging_bytes", ctypes.c_uint64),
         ("staging_slots", ctypes.c_uint32), ("max_grid", ctypes.c_uint32),
-        ("ramp", ctypes.c_uint32), ("reserved", ctypes.c_uint32),
+        ("reserved", ctypes.c_uint32 * 2),
     ]
 
 
@@ -62,6 +62,9 @@ class tc_stats_t(ctypes.Structure):
         ("gather_launches", ctypes.c_uint64), ("scatter_launches", ctypes.c_uint64),
         ("gather_bytes", ctypes.c_uint64), ("scatter_bytes", ctypes.c_uint64),
         ("gather_ms", ctypes.c_double), ("scatter_ms", ctypes.c_double),
+        ("d2h_copies", ctypes.c_uint64), ("h2d_copies", ctypes.c_uint64),
+        ("d2h_bytes", ctypes.c_uint64), ("h2d_bytes", ctypes.c_uint64),
+        ("d2h_ms", ctypes.c_double), ("h2d_ms", ctypes.c_double),
     ]
 
     def as_dict(self):
@@ -162,11 +165,11 @@ def _stream(s):
 
 # ------------------------------------------------------------------ the calls
 def tc_create(kv_base, scales, num_layers, num_blocks, page_bytes, block_size_tokens, scales_per_block=0,
-              host_arena_bytes=0, staging_bytes=0, staging_slots=0, max_grid=0, ramp=0):
+              host_arena_bytes=0, staging_bytes=0, staging_slots=0, max_grid=0):
     """Returns (rc, ctx); ctx is an opaque handle (int) or None."""
     desc = tc_pool_desc(_ptr(kv_base), _ptr(scales), num_layers, num_blocks, page_bytes, block_size_tokens,
                         scales_per_block)
-    opts = tc_opts(host_arena_bytes, staging_bytes, staging_slots, max_grid, ramp, 0)
+    opts = tc_opts(host_arena_bytes, staging_bytes, staging_slots, max_grid)
     out = ctypes.c_void_p()
     rc = _load().tc_create(ctypes.byref(desc), ctypes.byref(opts), ctypes.byref(out))
     return rc, out.value

@@ -1,13 +1,17 @@
 // Transfer engine and C ABI of tokencake_kv (see include/tokencake_kv.h for the contract).
 //
 // Offload (paper Sec. 4.1 / 6.3: a stalled agent's KV is copied to CPU memory asynchronously on a
-// dedicated stream) runs as a two-stage pipeline over a ring of device staging chunks:
-//     gather_pages (caller's stream)  ->  one contiguous D2H DMA per agent segment (copy stream)
+// dedicated stream) runs in two stages per staging chunk, all on the caller's stream:
+//     gather_pages  ->  one contiguous D2H DMA per agent segment of the chunk
 // Upload is the mirror image:
-//     H2D DMA (copy stream)  ->  scatter_pages (caller's stream)  ->  rewrite_table
-// Events order the two streams per staging slot, so chunk c+1 is gathered while chunk c crosses
-// the host link.  The block bookkeeping (tc_blocks.h) is updated under one mutex; a transfer
-// holds its blocks "in flight" until tc_poll / tc_sync see its completion event.
+//     H2D DMA  ->  scatter_pages  (... last chunk)  ->  rewrite_table
+// The stream is the paper's dedicated copy stream; kernels of other streams overlap freely.  The
+// gather is ~50x faster than the host link, so running it in line with the DMAs costs under 2 %;
+// a second, private DMA stream (gather of chunk c+1 under the DMA of chunk c) was measured and
+// dropped: with two copies queued across streams the runtime at random ran the DMAs at half rate.
+// A slot's `last` event orders its reuse when callers bring different streams.  The block
+// bookkeeping (tc_blocks.h) is updated under one mutex; a transfer holds its blocks "in flight"
+// until tc_poll / tc_sync see its completion event.
 #include <cstdio>
 #include <cstring>
 #include <deque>
@@ -24,24 +28,24 @@
 namespace {
 
 constexpr uint64_t kDefaultSlotBytes = 512ull << 20;
-constexpr uint32_t kDefaultSlots = 3;
+constexpr uint32_t kDefaultSlots = 2;
 
 struct Slot {
     char *buf = nullptr;
-    hipEvent_t mid = nullptr;   // producer of the slot's content finished
     hipEvent_t last = nullptr;  // last consumer finished: the slot may be overwritten
     bool used = false;
 };
 
+enum TimedKind { kGather = 0, kScatter = 1, kD2H = 2, kH2D = 3 };
+
 struct Timed {
     hipEvent_t t0, t1;
     uint64_t bytes;
-    bool gather;
+    int kind;
 };
 
 struct Op {
     hipEvent_t done = nullptr;
-    hipEvent_t entry = nullptr;
     std::vector<int32_t> ids;
     std::vector<uint64_t> arena_starts;
     uint64_t ring_consumed = 0;
@@ -73,7 +77,6 @@ struct tc_ctx {
     uint32_t slot_blocks = 0;
     std::vector<Slot> slots;
     uint32_t next_slot = 0;
-    hipStream_t dma = nullptr;
 
     int32_t *ids_host = nullptr;  // pinned ring
     int32_t *ids_dev = nullptr;   // device ring
@@ -149,14 +152,11 @@ int retire_front(tc_ctx *c)
     for (Timed &t : op.timed) {
         float ms = 0.f;
         if (hipEventElapsedTime(&ms, t.t0, t.t1) == hipSuccess) {
-            if (t.gather) {
-                c->st.gather_launches++;
-                c->st.gather_bytes += t.bytes;
-                c->st.gather_ms += ms;
-            } else {
-                c->st.scatter_launches++;
-                c->st.scatter_bytes += t.bytes;
-                c->st.scatter_ms += ms;
+            switch (t.kind) {
+            case kGather: c->st.gather_launches++; c->st.gather_bytes += t.bytes; c->st.gather_ms += ms; break;
+            case kScatter: c->st.scatter_launches++; c->st.scatter_bytes += t.bytes; c->st.scatter_ms += ms; break;
+            case kD2H: c->st.d2h_copies++; c->st.d2h_bytes += t.bytes; c->st.d2h_ms += ms; break;
+            default: c->st.h2d_copies++; c->st.h2d_bytes += t.bytes; c->st.h2d_ms += ms; break;
             }
         } else {
             (void)hipGetLastError();
@@ -165,7 +165,6 @@ int retire_front(tc_ctx *c)
         put_event(c, true, t.t1);
     }
     put_event(c, false, op.done);
-    put_event(c, false, op.entry);
     c->ops.pop_front();
     return TC_OK;
 }
@@ -217,18 +216,15 @@ int ring_alloc(tc_ctx *c, uint64_t n, uint64_t *start, uint64_t *consumed)
     }
 }
 
-// Chunk sizes (in blocks) for `total` records.  With ramp the sequence starts at 1/8 of a slot
-// and doubles, so the first DMA of an offload starts early; an upload uses the reversed sequence
-// so that little is left to scatter after its last DMA.
-std::vector<uint32_t> plan_chunks(uint64_t total, uint32_t slot_blocks, bool ramp, bool reversed)
+// Chunk sizes (in blocks) for `total` records: full slots, then the remainder.  An upload takes
+// the remainder first, so both directions end with the same chunk boundaries.
+std::vector<uint32_t> plan_chunks(uint64_t total, uint32_t slot_blocks, bool reversed)
 {
     std::vector<uint32_t> out;
-    uint32_t cur = ramp ? std::max<uint32_t>(1, slot_blocks / 8) : slot_blocks;
     while (total) {
-        uint32_t take = uint32_t(std::min<uint64_t>(cur, total));
+        uint32_t take = uint32_t(std::min<uint64_t>(slot_blocks, total));
         out.push_back(take);
         total -= take;
-        cur = std::min<uint64_t>(uint64_t(cur) * 2, slot_blocks);
     }
     if (reversed) std::reverse(out.begin(), out.end());
     return out;
@@ -298,10 +294,10 @@ int begin_op(tc_ctx *c, Plan &plan, hipStream_t stream, Op *op, uint64_t *ring_s
     return TC_OK;
 }
 
-int time_begin(tc_ctx *c, Op *op, hipStream_t stream, uint64_t bytes, bool gather)
+int time_begin(tc_ctx *c, Op *op, hipStream_t stream, uint64_t bytes, int kind)
 {
     if (!c->profiling) return TC_OK;
-    Timed t{nullptr, nullptr, bytes, gather};
+    Timed t{nullptr, nullptr, bytes, kind};
     if (int rc = get_event(c, true, &t.t0)) return rc;
     if (int rc = get_event(c, true, &t.t1)) return rc;
     HIP_TRY(hipEventRecord(t.t0, stream));
@@ -317,7 +313,7 @@ int time_end(tc_ctx *c, Op *op, hipStream_t stream)
 }
 
 // DMA of the parts of every segment that fall into records [c0, c1) of the list.
-int dma_chunk(tc_ctx *c, const Plan &plan, uint64_t c0, uint64_t c1, char *slot_buf, bool to_host)
+int dma_chunk(tc_ctx *c, const Plan &plan, uint64_t c0, uint64_t c1, char *slot_buf, bool to_host, hipStream_t stream)
 {
     for (const Segment &s : plan.segs) {
         uint64_t a = std::max<uint64_t>(s.first, c0), b = std::min<uint64_t>(s.first + s.n, c1);
@@ -325,8 +321,8 @@ int dma_chunk(tc_ctx *c, const Plan &plan, uint64_t c0, uint64_t c1, char *slot_
         char *host = s.host + (a - s.first) * c->rec;
         char *dev = slot_buf + (a - c0) * c->rec;
         uint64_t bytes = (b - a) * c->rec;
-        if (to_host) HIP_TRY(hipMemcpyAsync(host, dev, bytes, hipMemcpyDeviceToHost, c->dma));
-        else HIP_TRY(hipMemcpyAsync(dev, host, bytes, hipMemcpyHostToDevice, c->dma));
+        if (to_host) HIP_TRY(hipMemcpyAsync(host, dev, bytes, hipMemcpyDeviceToHost, stream));
+        else HIP_TRY(hipMemcpyAsync(dev, host, bytes, hipMemcpyHostToDevice, stream));
     }
     return TC_OK;
 }
@@ -343,24 +339,21 @@ int offload_locked(tc_ctx *c, const tc_xfer_desc *descs, uint32_t n_descs, hipSt
     if (int rc = begin_op(c, plan, stream, &op, &ring_start)) return rc;
 
     uint64_t c0 = 0;
-    Slot *slot = nullptr;
-    for (uint32_t nblk : plan_chunks(plan.total, c->slot_blocks, c->opts.ramp != 0, false)) {
-        slot = &c->slots[c->next_slot];
+    for (uint32_t nblk : plan_chunks(plan.total, c->slot_blocks, false)) {
+        Slot *slot = &c->slots[c->next_slot];
         c->next_slot = (c->next_slot + 1) % uint32_t(c->slots.size());
         if (slot->used) HIP_TRY(hipStreamWaitEvent(stream, slot->last, 0));
-        if (int rc = time_begin(c, &op, stream, uint64_t(nblk) * c->rec, true)) return rc;
+        if (int rc = time_begin(c, &op, stream, uint64_t(nblk) * c->rec, kGather)) return rc;
         HIP_TRY(tc::launch_gather_pages(c->pool.kv_base, static_cast<const uint32_t *>(c->pool.scales), slot->buf,
                                         c->ids_dev + ring_start + c0, nblk, c->geom, c->opts.max_grid, stream));
         if (int rc = time_end(c, &op, stream)) return rc;
-        HIP_TRY(hipEventRecord(slot->mid, stream));
-        HIP_TRY(hipStreamWaitEvent(c->dma, slot->mid, 0));
-        if (int rc = dma_chunk(c, plan, c0, c0 + nblk, slot->buf, true)) return rc;
-        HIP_TRY(hipEventRecord(slot->last, c->dma));
+        if (int rc = time_begin(c, &op, stream, uint64_t(nblk) * c->rec, kD2H)) return rc;
+        if (int rc = dma_chunk(c, plan, c0, c0 + nblk, slot->buf, true, stream)) return rc;
+        if (int rc = time_end(c, &op, stream)) return rc;
+        HIP_TRY(hipEventRecord(slot->last, stream));
         slot->used = true;
         c0 += nblk;
     }
-    // the caller's stream completes only when the last DMA has landed in host memory
-    HIP_TRY(hipStreamWaitEvent(stream, slot->last, 0));
     HIP_TRY(hipEventRecord(op.done, stream));
 
     c->st.n_offloads++;
@@ -381,22 +374,17 @@ int upload_locked(tc_ctx *c, const tc_xfer_desc *descs, uint32_t n_descs, hipStr
 
     Op op;
     uint64_t ring_start = 0;
-    if (int rc = get_event(c, false, &op.entry)) return rc;
     if (int rc = begin_op(c, plan, stream, &op, &ring_start)) return rc;
 
-    // the DMAs start only after what the caller already queued on its stream
-    HIP_TRY(hipEventRecord(op.entry, stream));
-    HIP_TRY(hipStreamWaitEvent(c->dma, op.entry, 0));
-
     uint64_t c0 = 0;
-    for (uint32_t nblk : plan_chunks(plan.total, c->slot_blocks, c->opts.ramp != 0, true)) {
+    for (uint32_t nblk : plan_chunks(plan.total, c->slot_blocks, true)) {
         Slot *slot = &c->slots[c->next_slot];
         c->next_slot = (c->next_slot + 1) % uint32_t(c->slots.size());
-        if (slot->used) HIP_TRY(hipStreamWaitEvent(c->dma, slot->last, 0));
-        if (int rc = dma_chunk(c, plan, c0, c0 + nblk, slot->buf, false)) return rc;
-        HIP_TRY(hipEventRecord(slot->mid, c->dma));
-        HIP_TRY(hipStreamWaitEvent(stream, slot->mid, 0));
-        if (int rc = time_begin(c, &op, stream, uint64_t(nblk) * c->rec, false)) return rc;
+        if (slot->used) HIP_TRY(hipStreamWaitEvent(stream, slot->last, 0));
+        if (int rc = time_begin(c, &op, stream, uint64_t(nblk) * c->rec, kH2D)) return rc;
+        if (int rc = dma_chunk(c, plan, c0, c0 + nblk, slot->buf, false, stream)) return rc;
+        if (int rc = time_end(c, &op, stream)) return rc;
+        if (int rc = time_begin(c, &op, stream, uint64_t(nblk) * c->rec, kScatter)) return rc;
         HIP_TRY(tc::launch_scatter_pages(slot->buf, c->pool.kv_base, static_cast<uint32_t *>(c->pool.scales),
                                          c->ids_dev + ring_start + c0, nblk, c->geom, c->opts.max_grid, stream));
         if (int rc = time_end(c, &op, stream)) return rc;
@@ -419,12 +407,10 @@ int upload_locked(tc_ctx *c, const tc_xfer_desc *descs, uint32_t n_descs, hipStr
 void destroy_unlocked(tc_ctx *c)
 {
     for (Slot &s : c->slots) {
-        if (s.mid) (void)hipEventDestroy(s.mid);
         if (s.last) (void)hipEventDestroy(s.last);
     }
     for (hipEvent_t e : c->sync_events) (void)hipEventDestroy(e);
     for (hipEvent_t e : c->time_events) (void)hipEventDestroy(e);
-    if (c->dma) (void)hipStreamDestroy(c->dma);
     if (c->staging) (void)hipFree(c->staging);
     if (c->ids_dev) (void)hipFree(c->ids_dev);
     if (c->ids_host) (void)hipHostFree(c->ids_host);
@@ -467,7 +453,7 @@ int tc_create(const tc_pool_desc *pool, const tc_opts *opts, tc_ctx **out)
     c->geom.tail_words = uint32_t((c->rec - uint64_t(P) * pool->page_bytes) / 4);
 
     uint32_t n_slots = c->opts.staging_slots ? c->opts.staging_slots : kDefaultSlots;
-    if (n_slots < 2) n_slots = 2;
+    if (n_slots < 1) n_slots = 1;
     uint64_t slot_bytes = c->opts.staging_bytes ? c->opts.staging_bytes / n_slots : kDefaultSlotBytes;
     if (slot_bytes < c->rec) slot_bytes = c->rec;
     uint64_t slot_blocks = slot_bytes / c->rec;
@@ -499,11 +485,9 @@ int tc_create(const tc_pool_desc *pool, const tc_opts *opts, tc_ctx **out)
     HIP_OR_FAIL(hipHostMalloc(reinterpret_cast<void **>(&c->ids_host), c->ring_cap * sizeof(int32_t), hipHostMallocDefault));
     if (c->arena_bytes)
         HIP_OR_FAIL(hipHostMalloc(reinterpret_cast<void **>(&c->arena_base), c->arena_bytes, hipHostMallocDefault));
-    HIP_OR_FAIL(hipStreamCreateWithFlags(&c->dma, hipStreamNonBlocking));
     c->slots.resize(n_slots);
     for (uint32_t i = 0; i < n_slots; ++i) {
         c->slots[i].buf = c->staging + uint64_t(i) * c->slot_bytes;
-        HIP_OR_FAIL(hipEventCreateWithFlags(&c->slots[i].mid, hipEventDisableTiming));
         HIP_OR_FAIL(hipEventCreateWithFlags(&c->slots[i].last, hipEventDisableTiming));
     }
 #undef HIP_OR_FAIL
@@ -518,7 +502,6 @@ int tc_destroy(tc_ctx *ctx)
     {
         std::lock_guard<std::mutex> g(ctx->mu);
         rc = sync_locked(ctx);
-        if (ctx->dma) (void)hipStreamSynchronize(ctx->dma);
     }
     destroy_unlocked(ctx);
     return rc;
