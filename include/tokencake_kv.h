@@ -160,8 +160,8 @@ void *tc_arena_base(const tc_ctx *ctx);
  * "achievable HBM" reference and the calibration kernel for the traffic counters.
  * bytes must be a multiple of 16. */
 int tc_copy_contiguous(void *dst, const void *src, uint64_t bytes, void *stream);
-/* `iters` passes of a[i] = b[i] + s*c[i] over n fp32 (DEVICE): the HBM-streaming kernel that the
- * copy stream is overlapped with.  n must be a multiple of 4. */
+/* `iters` launches of a[i] = b[i] + s*c[i] over n fp32 (DEVICE): the HBM-streaming neighbour that
+ * the copy stream is overlapped with.  n must be a multiple of 4. */
 int tc_hbm_stream(float *a, const float *b, const float *c, uint64_t n, float s, uint32_t iters, void *stream);
 /* Comparators without a gather kernel: mode 0 = one hipMemcpyAsync per page, mode 1 = one
  * hipMemcpy2DAsync per block.  direction 0 = offload, 1 = upload.  No bookkeeping. */

@@ -490,6 +490,12 @@ int tc_create(const tc_pool_desc *pool, const tc_opts *opts, tc_ctx **out)
         c->slots[i].buf = c->staging + uint64_t(i) * c->slot_bytes;
         HIP_OR_FAIL(hipEventCreateWithFlags(&c->slots[i].last, hipEventDisableTiming));
     }
+    // first transfers should not pay for event creation
+    for (int i = 0; i < 8; ++i) {
+        hipEvent_t e = nullptr;
+        HIP_OR_FAIL(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+        c->sync_events.push_back(e);
+    }
 #undef HIP_OR_FAIL
     *out = c;
     return TC_OK;

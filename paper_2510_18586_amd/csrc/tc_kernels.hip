@@ -112,16 +112,20 @@ __global__ __launch_bounds__(kThreads) void copy_contiguous_kernel(u32x4 *__rest
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
+// One pass of a = b + s*c; a workgroup covers 4 consecutive 4 KiB rows and retires, so that
+// workgroups of other streams interleave with it as they would with an ordinary memory-bound kernel.
 __global__ __launch_bounds__(kThreads) void hbm_stream_kernel(f32x4 *__restrict__ a, const f32x4 *__restrict__ b,
-                                                               const f32x4 *__restrict__ c, uint64_t n4, float s,
-                                                               uint32_t iters)
+                                                               const f32x4 *__restrict__ c, uint64_t n4, float s)
 {
-    const uint64_t stride = uint64_t(gridDim.x) * kThreads;
-    for (uint32_t it = 0; it < iters; ++it)
-        for (uint64_t i = uint64_t(blockIdx.x) * kThreads + threadIdx.x; i < n4; i += stride) {
+    const uint64_t base = uint64_t(blockIdx.x) * (kThreads * 4) + threadIdx.x;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const uint64_t i = base + u * kThreads;
+        if (i < n4) {
             f32x4 x = b[i], y = c[i];
             a[i] = x + s * y;
         }
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -202,11 +206,12 @@ hipError_t launch_hbm_stream(float *a, const float *b, const float *c, uint64_t 
 {
     if (n == 0 || iters == 0) return hipSuccess;
     const uint64_t n4 = n / 4;
-    uint64_t grid = (n4 + kThreads - 1) / kThreads;
-    if (grid > 256 * 32) grid = 256 * 32;  // 32 workgroups per CU, grid-stride over the rest
-    hipLaunchKernelGGL(hbm_stream_kernel, dim3(uint32_t(grid)), dim3(kThreads), 0, stream,
-                       reinterpret_cast<f32x4 *>(a), reinterpret_cast<const f32x4 *>(b),
-                       reinterpret_cast<const f32x4 *>(c), n4, s, iters);
+    const uint64_t grid = (n4 + kThreads * 4 - 1) / (kThreads * 4);
+    if (grid > 0x7fffffffull) return hipErrorInvalidValue;
+    for (uint32_t it = 0; it < iters; ++it)
+        hipLaunchKernelGGL(hbm_stream_kernel, dim3(uint32_t(grid)), dim3(kThreads), 0, stream,
+                           reinterpret_cast<f32x4 *>(a), reinterpret_cast<const f32x4 *>(b),
+                           reinterpret_cast<const f32x4 *>(c), n4, s);
     return hipGetLastError();
 }
 
