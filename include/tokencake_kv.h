@@ -155,6 +155,42 @@ int tc_set_profiling(tc_ctx *ctx, int on);
 /* The pinned arena (NULL / 0 without one). */
 void *tc_arena_base(const tc_ctx *ctx);
 
+/* ---- scheduling arithmetic around the copies (host only; Sec. 4.2, 4.3) ------------------ */
+/* Transfer cost, Eq. 2: T_transfer(N) = (off_a + off_b*N) + (up_a + up_b*N), milliseconds. */
+typedef struct {
+    double off_a_ms, off_b_ms_per_block;
+    double up_a_ms, up_b_ms_per_block;
+} tc_cost_model;
+
+/* A request in the waiting queue as Alg. 1 sees it. */
+typedef struct {
+    uint32_t kv_blocks;      /* incremental KV demand, in blocks              */
+    double work_tokens;      /* total work, in tokens of decode throughput    */
+} tc_waiting_req;
+
+/* Least-squares fit of both lines from m >= 2 measurements (n_blocks[i], offload_ms[i], upload_ms[i]):
+ * "calibrated from measured per-block transfer constants on the target platform".  TC_ERR_INVAL
+ * when m < 2 or all sizes are equal. */
+int tc_cost_fit(const uint32_t *n_blocks, const double *offload_ms, const double *upload_ms, uint32_t m,
+                tc_cost_model *out);
+/* Measures the model on this context: for each size it claims that many free blocks and arena slots,
+ * offloads them and uploads the same bytes back into the same blocks (`reps` times, median), so
+ * the pool is unchanged afterwards.  Blocks on `stream` until done.  TC_ERR_NOMEM /
+ * TC_ERR_HOST_NOMEM when the largest size does not fit. */
+int tc_calibrate(tc_ctx *ctx, const uint32_t *sizes, uint32_t m, uint32_t reps, void *stream, tc_cost_model *out);
+/* Eq. 2. */
+double tc_estimate_transfer_ms(const tc_cost_model *model, uint32_t n_blocks);
+/* Alg. 1 (ShouldOffload): 0 = reject, 1 = offload; *chosen = index of the first waiting request that
+ * fits the freed blocks and the token capacity of the scheduling window, or -1.  Negative on bad
+ * arguments. */
+int tc_should_offload(const tc_cost_model *model, uint32_t req_blocks, double t_fc_ms,
+                      double v_throughput_tokens_per_ms, const tc_waiting_req *queue, uint32_t n_queue,
+                      int32_t *chosen);
+/* Eq. 3: blocks this step may spend on uploads without touching what critical waiters need. */
+uint32_t tc_upload_budget(uint32_t gpu_free, uint32_t d_critical, uint32_t shared_free);
+/* Eq. 4: blocks to reserve for one candidate this step: min(remain, ceil(deficit / 2), budget). */
+uint32_t tc_gradual_reserve(uint32_t remain, uint32_t deficit, uint32_t budget);
+
 /* ---- measurement helpers: not on the hot path ------------------------------------------- */
 /* dst[i] = src[i]: contiguous DEVICE->DEVICE copy with the gather kernel's access width; the
  * "achievable HBM" reference and the calibration kernel for the traffic counters.

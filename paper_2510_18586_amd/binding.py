@@ -19,6 +19,8 @@ __all__ = [
     "tc_free", "tc_filter_private", "tc_host_alloc", "tc_host_free", "tc_offload", "tc_upload",
     "tc_offload_batch", "tc_upload_batch", "tc_poll", "tc_sync", "tc_stats", "tc_set_profiling",
     "tc_arena_base", "tc_copy_contiguous", "tc_hbm_stream", "tc_naive_transfer",
+    "tc_cost_model", "tc_waiting_req", "tc_cost_fit", "tc_calibrate", "tc_estimate_transfer_ms",
+    "tc_should_offload", "tc_upload_budget", "tc_gradual_reserve",
 ]
 
 TC_OK = 0
@@ -69,6 +71,20 @@ class tc_stats_t(ctypes.Structure):
 
     def as_dict(self):
         return {k: getattr(self, k) for k, _ in self._fields_}
+
+
+class tc_cost_model(ctypes.Structure):
+    _fields_ = [
+        ("off_a_ms", ctypes.c_double), ("off_b_ms_per_block", ctypes.c_double),
+        ("up_a_ms", ctypes.c_double), ("up_b_ms_per_block", ctypes.c_double),
+    ]
+
+    def as_tuple(self):
+        return (self.off_a_ms, self.off_b_ms_per_block, self.up_a_ms, self.up_b_ms_per_block)
+
+
+class tc_waiting_req(ctypes.Structure):
+    _fields_ = [("kv_blocks", ctypes.c_uint32), ("work_tokens", ctypes.c_double)]
 
 
 class TcError(RuntimeError):
@@ -127,6 +143,13 @@ def _load():
         "tc_copy_contiguous": (ci, [vp, vp, u64, vp]),
         "tc_hbm_stream": (ci, [vp, vp, vp, u64, ctypes.c_float, u32, vp]),
         "tc_naive_transfer": (ci, [vp, vp, u32, vp, ci, ci, vp]),
+        "tc_cost_fit": (ci, [vp, vp, vp, u32, ctypes.POINTER(tc_cost_model)]),
+        "tc_calibrate": (ci, [vp, vp, u32, u32, vp, ctypes.POINTER(tc_cost_model)]),
+        "tc_estimate_transfer_ms": (ctypes.c_double, [ctypes.POINTER(tc_cost_model), u32]),
+        "tc_should_offload": (ci, [ctypes.POINTER(tc_cost_model), u32, ctypes.c_double, ctypes.c_double,
+                                   ctypes.POINTER(tc_waiting_req), u32, ctypes.POINTER(ctypes.c_int32)]),
+        "tc_upload_budget": (u32, [u32, u32, u32]),
+        "tc_gradual_reserve": (u32, [u32, u32, u32]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -294,3 +317,49 @@ def tc_hbm_stream(a, b, c, n, s=0.5, iters=1, stream=None):
 def tc_naive_transfer(ctx, block_ids, host_buf, mode, direction, stream=None):
     a, p, n = _ids(block_ids)
     return _load().tc_naive_transfer(ctx, p, n, _ptr(host_buf), mode, direction, _stream(stream))
+
+
+def _model(model):
+    return model if isinstance(model, tc_cost_model) else tc_cost_model(*model)
+
+
+def tc_cost_fit(n_blocks, offload_ms, upload_ms):
+    """Returns (rc, tc_cost_model)."""
+    n = np.ascontiguousarray(n_blocks, dtype=np.uint32)
+    o = np.ascontiguousarray(offload_ms, dtype=np.float64)
+    u = np.ascontiguousarray(upload_ms, dtype=np.float64)
+    out = tc_cost_model()
+    m = int(n.size) if n.size == o.size == u.size else 0
+    rc = _load().tc_cost_fit(n.ctypes.data, o.ctypes.data, u.ctypes.data, m, ctypes.byref(out))
+    return rc, out
+
+
+def tc_calibrate(ctx, sizes, reps=3, stream=None):
+    """Returns (rc, tc_cost_model) measured on this context."""
+    n = np.ascontiguousarray(sizes, dtype=np.uint32)
+    out = tc_cost_model()
+    rc = _load().tc_calibrate(ctx, n.ctypes.data, int(n.size), reps, _stream(stream), ctypes.byref(out))
+    return rc, out
+
+
+def tc_estimate_transfer_ms(model, n_blocks):
+    return float(_load().tc_estimate_transfer_ms(ctypes.byref(_model(model)), n_blocks))
+
+
+def tc_should_offload(model, req_blocks, t_fc_ms, v_throughput_tokens_per_ms, waiting):
+    """waiting: sequence of (kv_blocks, work_tokens).  Returns (rc, chosen index): rc 1 = offload, 0 = reject."""
+    q = (tc_waiting_req * max(len(waiting), 1))()
+    for i, (b, w) in enumerate(waiting):
+        q[i] = tc_waiting_req(int(b), float(w))
+    chosen = ctypes.c_int32(-1)
+    rc = _load().tc_should_offload(ctypes.byref(_model(model)), req_blocks, t_fc_ms, v_throughput_tokens_per_ms,
+                                   q, len(waiting), ctypes.byref(chosen))
+    return rc, chosen.value
+
+
+def tc_upload_budget(gpu_free, d_critical, shared_free):
+    return int(_load().tc_upload_budget(gpu_free, d_critical, shared_free))
+
+
+def tc_gradual_reserve(remain, deficit, budget):
+    return int(_load().tc_gradual_reserve(remain, deficit, budget))

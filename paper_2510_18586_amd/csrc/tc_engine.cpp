@@ -670,6 +670,59 @@ int tc_set_profiling(tc_ctx *ctx, int on)
     return TC_OK;
 }
 
+int tc_calibrate(tc_ctx *ctx, const uint32_t *sizes, uint32_t m, uint32_t reps, void *stream, tc_cost_model *out)
+{
+    if (!ctx || !sizes || !out || m < 2 || reps == 0) return TC_ERR_INVAL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    uint32_t largest = 0;
+    for (uint32_t i = 0; i < m; ++i) largest = std::max(largest, sizes[i]);
+    if (largest == 0) return TC_ERR_INVAL;
+    std::vector<int32_t> ids(largest);
+    void *host = nullptr;
+    if (int rc = tc_alloc(ctx, largest, ids.data())) return rc;
+    if (int rc = tc_host_alloc(ctx, largest, &host)) {
+        (void)tc_free(ctx, ids.data(), largest);
+        return rc;
+    }
+    hipEvent_t e[3] = {nullptr, nullptr, nullptr};
+    int rc = TC_OK;
+    for (auto &ev : e)
+        if (hipEventCreate(&ev) != hipSuccess) rc = TC_ERR_HIP;
+    std::vector<double> off_ms(m), up_ms(m);
+    for (uint32_t i = 0; i < m && rc == TC_OK; ++i) {
+        std::vector<float> o, u;
+        for (uint32_t r = 0; r <= reps && rc == TC_OK; ++r) {  // the first round warms up
+            if (hipEventRecord(e[0], st) != hipSuccess) rc = TC_ERR_HIP;
+            if (rc == TC_OK) rc = tc_offload(ctx, ids.data(), sizes[i], host, stream);
+            if (rc == TC_OK && hipEventRecord(e[1], st) != hipSuccess) rc = TC_ERR_HIP;
+            // the same bytes go back into the same blocks: the pool ends up as it was
+            if (rc == TC_OK) rc = tc_upload(ctx, host, ids.data(), sizes[i], nullptr, stream);
+            if (rc == TC_OK && hipEventRecord(e[2], st) != hipSuccess) rc = TC_ERR_HIP;
+            if (rc == TC_OK && hipEventSynchronize(e[2]) != hipSuccess) rc = TC_ERR_HIP;
+            float a = 0.f, b = 0.f;
+            if (rc == TC_OK && (hipEventElapsedTime(&a, e[0], e[1]) != hipSuccess ||
+                                hipEventElapsedTime(&b, e[1], e[2]) != hipSuccess))
+                rc = TC_ERR_HIP;
+            if (r > 0) {
+                o.push_back(a);
+                u.push_back(b);
+            }
+        }
+        if (rc != TC_OK) break;
+        std::sort(o.begin(), o.end());
+        std::sort(u.begin(), u.end());
+        off_ms[i] = o[o.size() / 2];
+        up_ms[i] = u[u.size() / 2];
+    }
+    for (auto &ev : e)
+        if (ev) (void)hipEventDestroy(ev);
+    (void)tc_sync(ctx);
+    (void)tc_host_free(ctx, host);
+    (void)tc_free(ctx, ids.data(), largest);
+    if (rc != TC_OK) return rc;
+    return tc_cost_fit(sizes, off_ms.data(), up_ms.data(), m, out);
+}
+
 int tc_copy_contiguous(void *dst, const void *src, uint64_t bytes, void *stream)
 {
     if ((bytes && (!dst || !src)) || bytes % 16) return TC_ERR_INVAL;

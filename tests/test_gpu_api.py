@@ -236,3 +236,42 @@ def test_shared_prefix_blocks_stay_put():
         assert np.array_equal(gp.scales_all_to_host(), scales_h)
     finally:
         gp.close()
+
+
+def test_calibrated_cost_model_predicts_a_transfer_and_leaves_the_pool_alone():
+    """Eq. 2 closed on this platform: tc_calibrate fits T(N) from its own transfers; the estimate for
+    a size it did not measure is within 5 % of a transfer timed here; the gate of Alg. 1 then uses it."""
+    import time
+    shape = W.CONFIGS[1].with_blocks(400)
+    gp = GpuPool(shape, seed=9, host_arena_bytes=330 * 2 * 1024 * 1024)
+    try:
+        before = gp.page_checksums()
+        stream = torch.cuda.Stream()
+        rc, model = K.tc_calibrate(gp.ctx, [32, 64, 128, 256], 3, stream)
+        assert rc == 0
+        assert torch.equal(gp.page_checksums(), before), "calibration must not change the pool"
+        st = _stats(gp)
+        assert st.gpu_blocks_free == 400 and st.host_slots_used == 0
+        # 2 MiB per block at roughly 57 GB/s is ~0.037 ms per block and direction
+        assert 0.03 < model.off_b_ms_per_block < 0.06 and 0.03 < model.up_b_ms_per_block < 0.06
+        assert abs(model.off_a_ms) < 0.5 and abs(model.up_a_ms) < 0.5
+        n = 192
+        rc, ids = K.tc_alloc(gp.ctx, n)
+        rc, host = K.tc_host_alloc(gp.ctx, n)
+        ts = []
+        for _ in range(4):
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            K.check(K.tc_offload(gp.ctx, ids, host, stream))
+            K.check(K.tc_upload(gp.ctx, host, ids, None, stream))
+            stream.synchronize()
+            ts.append((time.perf_counter() - t) * 1e3)
+        measured = float(np.median(ts[1:]))
+        predicted = K.tc_estimate_transfer_ms(model, n)
+        assert abs(predicted - measured) / measured < 0.05, (predicted, measured)
+        # a 2 s tool call leaves a window; a 10 ms one does not cover the round trip of 192 blocks
+        assert K.tc_should_offload(model, n, 2000.0, 5.0, [(500, 10.0), (100, 4000.0)]) == (1, 1)
+        assert K.tc_should_offload(model, n, 10.0, 5.0, [(100, 1.0)]) == (0, -1)
+        assert K.tc_calibrate(gp.ctx, [32, 500], 1, stream)[0] == K.TC_ERR_NOMEM
+    finally:
+        gp.close()

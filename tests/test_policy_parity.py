@@ -1,0 +1,66 @@
+"""The library's scheduling arithmetic (host only, through the C ABI) against the oracle.
+
+Decisions and integer results must be identical; the fitted constants and the cost estimate are
+double-precision sums in a different order (Kahan-free long double vs math.fsum), so they are
+compared to 1e-9 relative, well inside the 1e-6 ms a decision could ever depend on.
+"""
+import numpy as np
+import pytest
+
+import paper_2510_18586_amd as K
+from oracle import policy
+
+
+def test_fit_and_estimate_match_oracle():
+    rng = np.random.default_rng(5)
+    for _ in range(50):
+        m = int(rng.integers(2, 10))
+        n = np.sort(rng.choice(np.arange(1, 1500), size=m, replace=False)).astype(np.uint32)
+        off = 0.06 + 0.0374 * n + rng.normal(0, 0.02, m)
+        up = 0.08 + 0.0375 * n + rng.normal(0, 0.02, m)
+        rc, model = K.tc_cost_fit(n, off, up)
+        assert rc == 0
+        want = policy.fit_linear(list(map(int, n)), list(off)) + policy.fit_linear(list(map(int, n)), list(up))
+        np.testing.assert_allclose(model.as_tuple(), want, rtol=1e-9, atol=1e-12)
+        for blocks in (0, 1, 256, 100000):
+            got = K.tc_estimate_transfer_ms(model, blocks)
+            assert abs(got - policy.estimate_transfer_ms(model.as_tuple(), blocks)) <= 1e-9 * max(1.0, abs(got))
+    assert K.tc_cost_fit([5, 5], [1.0, 2.0], [1.0, 2.0])[0] == K.TC_ERR_INVAL
+    assert K.tc_cost_fit([5], [1.0], [1.0])[0] == K.TC_ERR_INVAL
+
+
+def test_paper_numbers_through_the_abi():
+    # Sec. 7.6: 15.8 ms at 64 blocks and 79.8 ms at 320 blocks predict the printed 63.7 ms at 256
+    rc, model = K.tc_cost_fit([64, 320], [7.9, 39.9], [7.9, 39.9])
+    assert rc == 0 and abs(K.tc_estimate_transfer_ms(model, 256) - 63.7) <= 0.15
+
+
+def test_should_offload_matches_oracle():
+    rng = np.random.default_rng(6)
+    model = (0.05, 0.0374, 0.07, 0.0375)
+    n_true = 0
+    for _ in range(2000):
+        blocks = int(rng.integers(0, 1100))
+        queue = [(int(rng.integers(0, 1200)), float(rng.uniform(0, 60000))) for _ in range(int(rng.integers(0, 9)))]
+        v = float(rng.uniform(0.1, 40))
+        t_fc = float(rng.choice([0.0, rng.uniform(0, 100), rng.uniform(0, 5000)]))
+        rc, k = K.tc_should_offload(model, blocks, t_fc, v, queue)
+        want, k_want = policy.should_offload(model, blocks, t_fc, v, queue)
+        assert rc == int(want) and k == k_want
+        n_true += rc
+    assert 200 < n_true < 1800, "the cases should exercise both outcomes"
+    # exactly at the boundary T_fc == T_transfer the stall is too short
+    t = policy.estimate_transfer_ms(model, 256)
+    assert K.tc_should_offload(model, 256, t, 10.0, [(1, 0.0)]) == (0, -1)
+    assert K.tc_should_offload(model, 256, np.nextafter(t, np.inf), 10.0, [(1, 0.0)]) == (1, 0)
+
+
+def test_budget_and_gradual_reserve_match_oracle():
+    rng = np.random.default_rng(7)
+    for _ in range(3000):
+        a, b, c = (int(x) for x in rng.integers(0, 40000, size=3))
+        assert K.tc_upload_budget(a, b, c) == policy.upload_budget(a, b, c)
+        assert K.tc_gradual_reserve(a, b, c) == policy.gradual_reserve(a, b, c)
+    big = 2**32 - 1
+    assert K.tc_gradual_reserve(big, big, big) == policy.gradual_reserve(big, big, big) == 2**31
+    assert K.tc_upload_budget(big, big, 0) == 0
