@@ -191,6 +191,38 @@ uint32_t tc_upload_budget(uint32_t gpu_free, uint32_t d_critical, uint32_t share
 /* Eq. 4: blocks to reserve for one candidate this step: min(remain, ceil(deficit / 2), budget). */
 uint32_t tc_gradual_reserve(uint32_t remain, uint32_t deficit, uint32_t budget);
 
+/* ---- request lifecycle and call-duration forecast (host only; Sec. 6.2, Sec. 4.1) -------- */
+/* The five states of Sec. 6.2. */
+enum { TC_RUNNING = 0, TC_PENDING_OFFLOAD = 1, TC_OFFLOADED = 2, TC_PENDING_UPLOAD = 3, TC_UPLOADED = 4 };
+/* What drives them: the two endpoints and the scheduling loop. */
+enum { TC_EV_CALL_START = 0, TC_EV_OFFLOAD_ISSUED = 1, TC_EV_OFFLOAD_DONE = 2, TC_EV_UPLOAD_ISSUED = 3,
+       TC_EV_UPLOAD_DONE = 4, TC_EV_CALL_FINISH = 5 };
+/* What the caller has to do after a step. */
+enum { TC_ACT_NONE = 0, TC_ACT_RESUME = 1, TC_ACT_UPLOAD_NOW = 2, TC_ACT_WAIT = 3 };
+
+typedef struct {
+    uint8_t state;           /* TC_RUNNING ...                                          */
+    uint8_t finish_seen;     /* call_finish arrived while the KV was away or in flight  */
+    uint8_t copy_in_flight;  /* an offload or upload of this request has been issued    */
+    uint8_t reserved;
+} tc_req_state;
+
+/* One transition.  Sec. 4.1: a request whose KV is already uploaded resumes at once on call_finish
+ * (TC_ACT_RESUME); if the tool returns while the KV is on the CPU an immediate upload is due
+ * (TC_ACT_UPLOAD_NOW); while a copy is in flight the finish is remembered (TC_ACT_WAIT) and acted
+ * on when the copy completes.  TC_ERR_INVAL, and *req unchanged, for an event the state does not allow. */
+int tc_lifecycle_step(tc_req_state *req, int event, int *action);
+
+typedef struct tc_forecaster tc_forecaster;
+/* Eq. 1 with weight alpha on the user's estimate; gamma is the weight of a new observation in the
+ * moving average; default_ms is the system-wide constant used when nothing is known. */
+int tc_forecaster_create(double alpha, double gamma, double default_ms, tc_forecaster **out);
+int tc_forecaster_destroy(tc_forecaster *f);
+/* Feeds the elapsed time that call_finish reports back into the type's moving average. */
+int tc_forecaster_observe(tc_forecaster *f, uint32_t fn_type, double elapsed_ms);
+/* Estimate for a type; has_user = 0 when the graph gives no predict_time. */
+double tc_forecaster_estimate(const tc_forecaster *f, uint32_t fn_type, int has_user, double t_user_ms);
+
 /* ---- measurement helpers: not on the hot path ------------------------------------------- */
 /* dst[i] = src[i]: contiguous DEVICE->DEVICE copy with the gather kernel's access width; the
  * "achievable HBM" reference and the calibration kernel for the traffic counters.

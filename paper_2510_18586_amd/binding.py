@@ -21,6 +21,8 @@ __all__ = [
     "tc_arena_base", "tc_copy_contiguous", "tc_hbm_stream", "tc_naive_transfer",
     "tc_cost_model", "tc_waiting_req", "tc_cost_fit", "tc_calibrate", "tc_estimate_transfer_ms",
     "tc_should_offload", "tc_upload_budget", "tc_gradual_reserve",
+    "tc_req_state", "tc_lifecycle_step", "tc_forecaster_create", "tc_forecaster_destroy",
+    "tc_forecaster_observe", "tc_forecaster_estimate",
 ]
 
 TC_OK = 0
@@ -87,6 +89,14 @@ class tc_waiting_req(ctypes.Structure):
     _fields_ = [("kv_blocks", ctypes.c_uint32), ("work_tokens", ctypes.c_double)]
 
 
+class tc_req_state(ctypes.Structure):
+    _fields_ = [("state", ctypes.c_uint8), ("finish_seen", ctypes.c_uint8),
+                ("copy_in_flight", ctypes.c_uint8), ("reserved", ctypes.c_uint8)]
+
+    def as_tuple(self):
+        return (self.state, bool(self.finish_seen), bool(self.copy_in_flight))
+
+
 class TcError(RuntimeError):
     def __init__(self, code):
         super().__init__(f"tokencake_kv error {code}: {tc_strerror(code)}")
@@ -150,6 +160,11 @@ def _load():
                                    ctypes.POINTER(tc_waiting_req), u32, ctypes.POINTER(ctypes.c_int32)]),
         "tc_upload_budget": (u32, [u32, u32, u32]),
         "tc_gradual_reserve": (u32, [u32, u32, u32]),
+        "tc_lifecycle_step": (ci, [ctypes.POINTER(tc_req_state), ci, ctypes.POINTER(ci)]),
+        "tc_forecaster_create": (ci, [ctypes.c_double, ctypes.c_double, ctypes.c_double, ctypes.POINTER(vp)]),
+        "tc_forecaster_destroy": (ci, [vp]),
+        "tc_forecaster_observe": (ci, [vp, u32, ctypes.c_double]),
+        "tc_forecaster_estimate": (ctypes.c_double, [vp, u32, ci, ctypes.c_double]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -363,3 +378,29 @@ def tc_upload_budget(gpu_free, d_critical, shared_free):
 
 def tc_gradual_reserve(remain, deficit, budget):
     return int(_load().tc_gradual_reserve(remain, deficit, budget))
+
+
+def tc_lifecycle_step(req, event):
+    """req: tc_req_state (updated in place on success).  Returns (rc, action)."""
+    action = ctypes.c_int(0)
+    rc = _load().tc_lifecycle_step(ctypes.byref(req), event, ctypes.byref(action))
+    return rc, action.value
+
+
+def tc_forecaster_create(alpha, gamma, default_ms):
+    """Returns (rc, handle)."""
+    out = ctypes.c_void_p()
+    rc = _load().tc_forecaster_create(alpha, gamma, default_ms, ctypes.byref(out))
+    return rc, out.value
+
+
+def tc_forecaster_destroy(f):
+    return _load().tc_forecaster_destroy(f)
+
+
+def tc_forecaster_observe(f, fn_type, elapsed_ms):
+    return _load().tc_forecaster_observe(f, fn_type, elapsed_ms)
+
+
+def tc_forecaster_estimate(f, fn_type, t_user_ms=None):
+    return float(_load().tc_forecaster_estimate(f, fn_type, int(t_user_ms is not None), t_user_ms or 0.0))

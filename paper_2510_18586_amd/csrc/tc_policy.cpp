@@ -1,7 +1,11 @@
 // Host-side scheduling arithmetic that consumes the copy path's measurements: the linear
-// transfer-cost model (paper Eq. 2), the ShouldOffload gate (Alg. 1), the upload budget (Eq. 3)
-// and the gradual reservation (Eq. 4).  No GPU work here; tc_calibrate lives in the engine.
+// transfer-cost model (paper Eq. 2), the ShouldOffload gate (Alg. 1), the upload budget (Eq. 3),
+// the gradual reservation (Eq. 4), the five-state request lifecycle (Sec. 6.2) and the call-duration
+// forecast (Eq. 1).  No GPU work here; tc_calibrate lives in the engine.
 #include <cmath>
+#include <mutex>
+#include <new>
+#include <unordered_map>
 
 #include "tokencake_kv.h"
 
@@ -81,6 +85,139 @@ uint32_t tc_gradual_reserve(uint32_t remain, uint32_t deficit, uint32_t budget)
     if (remain < r) r = remain;
     if (budget < r) r = budget;
     return r;
+}
+
+int tc_lifecycle_step(tc_req_state *req, int event, int *action)
+{
+    if (!req || req->state > TC_UPLOADED) return TC_ERR_INVAL;
+    tc_req_state r = *req;
+    int act = TC_ACT_NONE;
+    bool ok = false;
+    const bool fin = r.finish_seen != 0, fly = r.copy_in_flight != 0;
+    switch (event) {
+    case TC_EV_CALL_START:
+        if (r.state == TC_RUNNING && !fin && !fly) {
+            r.state = TC_PENDING_OFFLOAD;
+            ok = true;
+        }
+        break;
+    case TC_EV_OFFLOAD_ISSUED:
+        if (r.state == TC_PENDING_OFFLOAD && !fin && !fly) {
+            r.copy_in_flight = 1;
+            ok = true;
+        }
+        break;
+    case TC_EV_OFFLOAD_DONE:
+        if (r.state == TC_PENDING_OFFLOAD && fly) {
+            r.state = TC_OFFLOADED;
+            r.copy_in_flight = 0;
+            if (fin) act = TC_ACT_UPLOAD_NOW;  // the tool came back while the copy ran
+            ok = true;
+        }
+        break;
+    case TC_EV_UPLOAD_ISSUED:
+        if (r.state == TC_OFFLOADED) {
+            r.state = TC_PENDING_UPLOAD;
+            r.copy_in_flight = 1;
+            ok = true;
+        }
+        break;
+    case TC_EV_UPLOAD_DONE:
+        if (r.state == TC_PENDING_UPLOAD && fly) {
+            r.copy_in_flight = 0;
+            if (fin) {
+                r.state = TC_RUNNING;
+                r.finish_seen = 0;
+                act = TC_ACT_RESUME;
+            } else {
+                r.state = TC_UPLOADED;
+            }
+            ok = true;
+        }
+        break;
+    case TC_EV_CALL_FINISH:
+        if (fin) break;
+        if (r.state == TC_UPLOADED) {
+            r.state = TC_RUNNING;
+            r.copy_in_flight = 0;
+            act = TC_ACT_RESUME;
+            ok = true;
+        } else if (r.state == TC_OFFLOADED) {
+            r.finish_seen = 1;
+            r.copy_in_flight = 0;
+            act = TC_ACT_UPLOAD_NOW;
+            ok = true;
+        } else if (r.state == TC_PENDING_UPLOAD) {
+            r.finish_seen = 1;
+            act = TC_ACT_WAIT;
+            ok = true;
+        } else if (r.state == TC_PENDING_OFFLOAD) {
+            if (fly) {
+                r.finish_seen = 1;
+                act = TC_ACT_WAIT;
+            } else {
+                r.state = TC_RUNNING;  // the KV never left the GPU
+                act = TC_ACT_RESUME;
+            }
+            ok = true;
+        }
+        break;
+    default: break;
+    }
+    if (!ok) return TC_ERR_INVAL;
+    *req = r;
+    if (action) *action = act;
+    return TC_OK;
+}
+
+}  // extern "C"
+
+struct tc_forecaster {
+    double alpha, gamma, default_ms;
+    mutable std::mutex mu;
+    std::unordered_map<uint32_t, double> history;
+};
+
+extern "C" {
+
+int tc_forecaster_create(double alpha, double gamma, double default_ms, tc_forecaster **out)
+{
+    if (!out) return TC_ERR_INVAL;
+    *out = nullptr;
+    if (!(alpha >= 0.0 && alpha <= 1.0) || !(gamma > 0.0 && gamma <= 1.0) || !(default_ms >= 0.0)) return TC_ERR_INVAL;
+    tc_forecaster *f = new (std::nothrow) tc_forecaster;
+    if (!f) return TC_ERR_INVAL;
+    f->alpha = alpha;
+    f->gamma = gamma;
+    f->default_ms = default_ms;
+    *out = f;
+    return TC_OK;
+}
+
+int tc_forecaster_destroy(tc_forecaster *f)
+{
+    delete f;
+    return TC_OK;
+}
+
+int tc_forecaster_observe(tc_forecaster *f, uint32_t fn_type, double elapsed_ms)
+{
+    if (!f || !(elapsed_ms >= 0.0)) return TC_ERR_INVAL;
+    std::lock_guard<std::mutex> g(f->mu);
+    auto it = f->history.find(fn_type);
+    if (it == f->history.end()) f->history.emplace(fn_type, elapsed_ms);
+    else it->second = f->gamma * elapsed_ms + (1.0 - f->gamma) * it->second;
+    return TC_OK;
+}
+
+double tc_forecaster_estimate(const tc_forecaster *f, uint32_t fn_type, int has_user, double t_user_ms)
+{
+    if (!f) return std::nan("");
+    std::lock_guard<std::mutex> g(f->mu);
+    auto it = f->history.find(fn_type);
+    if (it == f->history.end()) return has_user ? t_user_ms : f->default_ms;
+    if (!has_user) return it->second;
+    return f->alpha * t_user_ms + (1.0 - f->alpha) * it->second;
 }
 
 }  // extern "C"

@@ -1,0 +1,174 @@
+"""The pieces around the copy path working together on the GPU: forecast (Eq. 1) -> ShouldOffload
+(Alg. 1, with a cost model calibrated on this device, Eq. 2) -> offload -> gradual reservation
+(Eq. 4) with piecewise uploads -> lifecycle (Sec. 6.2) deciding resume / immediate upload.
+
+Every decision the library takes is compared with the oracle's on the spot; every agent that went
+through a round trip must find its KV unchanged behind its rewritten block table.
+"""
+import heapq
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2510_18586_amd as K
+import tc_workloads as W
+from oracle import lifecycle as L
+from oracle import policy
+from harness import DEV, GpuPool
+
+pytestmark = pytest.mark.gpu
+
+
+def test_temporal_loop_on_a_seeded_trace():
+    shape = W.CONFIGS[3].with_blocks(3072)                      # 32B-shaped records (4 MiB), 12 GiB pool
+    rng = W.rng_for(3, salt=21)
+    agents, events = W.dag_trace(rng, n_agents=60, depth=4, median_tokens=1024, cap_tokens=4096,
+                                 block_size=shape.block_size)
+    rec = 2 * shape.num_layers * shape.page_bytes
+    gp = GpuPool(shape, seed=W.seed_for(3, 21), host_arena_bytes=1024 * rec)
+    try:
+        stream = torch.cuda.Stream()
+        rc, model = K.tc_calibrate(gp.ctx, [16, 64, 128], 2, stream)
+        assert rc == 0
+        m = model.as_tuple()
+        rc, fc = K.tc_forecaster_create(0.5, 0.5, 2000.0)
+        assert rc == 0
+        fc_model = L.Forecaster(0.5, 0.5, 2000.0)
+        pool_model = oracle.OracleBlockPool(gp.NB)
+        pool_model.free(pool_model.alloc(128))     # the calibration claimed and released its largest size
+        lead_ms, step_ms, v_tok_per_ms = 200.0, 50.0, 4.0
+        tables = torch.full((len(agents), 260), -1, dtype=torch.int32, device=DEV)
+        A = [dict(req=K.tc_req_state(0, 0, 0, 0), model=(L.RUNNING, False, False)) for _ in agents]
+        counts = dict(approved=0, rejected=0, resumed_at_once=0, immediate=0, pieces=0)
+
+        heap = [(t * 1e3, k, kind, i) for k, (t, _, kind, i) in enumerate(events) if kind != "upload_due"]
+        heapq.heapify(heap)
+        seq = len(heap) + len(events)
+
+        def push(t, kind, i):
+            nonlocal seq
+            seq += 1
+            heapq.heappush(heap, (t, seq, kind, i))
+
+        def lifecycle(i, event):
+            a = A[i]
+            rc, act = K.tc_lifecycle_step(a["req"], event)
+            a["model"], want = L.step(a["model"], event)
+            assert rc == 0 and act == want and a["req"].as_tuple() == a["model"]
+            return act
+
+        def alloc(n):
+            rc, ids = K.tc_alloc(gp.ctx, n)
+            assert rc == 0 and ids.tolist() == pool_model.alloc(n)
+            return ids
+
+        def sync():
+            K.check(K.tc_sync(gp.ctx))
+            pool_model.retire_all()
+
+        def upload_piece(i, t, everything):
+            """One scheduling step of the gradual upload of agent i."""
+            a = A[i]
+            if a["req"].state == L.OFFLOADED:
+                assert lifecycle(i, L.UPLOAD_ISSUED) == L.NONE
+            n, done = agents[i]["blocks"], a["done"]
+            sync()
+            budget = K.tc_upload_budget(pool_model.n_free(), 0, 0)
+            assert budget == policy.upload_budget(pool_model.n_free(), 0, 0)
+            piece = K.tc_gradual_reserve(budget, n - done, budget)
+            assert piece == policy.gradual_reserve(budget, n - done, budget)
+            if everything:
+                piece = n - done                         # the tool is back: no more waiting
+            ids = alloc(piece)
+            K.check(K.tc_upload(gp.ctx, a["buf"] + done * rec, ids, tables[i].data_ptr() + 4 * done, stream))
+            pool_model.begin_op(ids.tolist())
+            a["new"][done:done + piece] = ids
+            a["done"] = done + piece
+            counts["pieces"] += 1
+            if a["done"] < n:
+                push(t + step_ms, "reserve", i)
+            else:
+                K.check(K.tc_host_free(gp.ctx, a["buf"]))
+                push(t + 0.001, "upload_done", i)
+
+        def verify_and_resume(i):
+            a, n = A[i], agents[i]["blocks"]
+            stream.synchronize()
+            assert np.array_equal(tables[i].cpu().numpy()[:n], a["ids"])
+            assert torch.equal(gp.block_checksums(a["ids"]), a["sig"]), f"agent {i}: KV changed"
+
+        while heap:
+            t, _, kind, i = heapq.heappop(heap)
+            a, n = A[i], agents[i]["blocks"]
+            ftype = i % 4
+            user = 2000.0 if ftype < 2 else None
+            if kind == "start":
+                a["ids"] = alloc(n)
+                tables[i, :n] = torch.from_numpy(a["ids"]).to(DEV)
+            elif kind == "call_start":
+                a["t_call"] = t
+                assert lifecycle(i, L.CALL_START) == L.NONE
+                t_fc = K.tc_forecaster_estimate(fc, ftype, user)
+                assert t_fc == pytest.approx(fc_model.estimate(ftype, user), rel=1e-12)
+                queue = [(int(rng.integers(8, 400)), float(rng.uniform(100, 6000))) for _ in range(3)]
+                ok, pick = K.tc_should_offload(model, n, t_fc, v_tok_per_ms, queue)
+                assert (bool(ok), pick) == policy.should_offload(m, n, t_fc, v_tok_per_ms, queue)
+                rc, buf = K.tc_host_alloc(gp.ctx, n) if ok else (K.TC_ERR_HOST_NOMEM, None)
+                if not ok or rc != 0:
+                    counts["rejected"] += 1
+                    continue
+                counts["approved"] += 1
+                a.update(sig=gp.block_checksums(a["ids"]), buf=buf, done=0, new=np.full(n, -1, dtype=np.int32))
+                K.check(K.tc_offload(gp.ctx, a["ids"], buf, stream))
+                pool_model.begin_op(a["ids"].tolist())
+                K.check(K.tc_free(gp.ctx, a["ids"]))
+                pool_model.free(a["ids"].tolist())
+                assert lifecycle(i, L.OFFLOAD_ISSUED) == L.NONE
+                push(t + K.tc_estimate_transfer_ms(model, n) / 2, "offload_done", i)
+                push(t + max(0.0, t_fc - lead_ms), "upload_due", i)
+            elif kind == "offload_done":
+                sync()
+                if lifecycle(i, L.OFFLOAD_DONE) == L.UPLOAD_NOW:
+                    counts["immediate"] += 1
+                    upload_piece(i, t, everything=True)
+            elif kind in ("upload_due", "reserve"):
+                if a["req"].state == L.OFFLOADED and not a["req"].finish_seen or \
+                        (kind == "reserve" and a["req"].state == L.PENDING_UPLOAD and a["done"] < n):
+                    upload_piece(i, t, everything=bool(a["req"].finish_seen))
+                elif a["req"].state == L.PENDING_OFFLOAD and kind == "upload_due":
+                    push(t + step_ms, "upload_due", i)       # the offload itself is not through yet
+            elif kind == "upload_done":
+                sync()
+                a["ids"] = a["new"].copy()
+                if lifecycle(i, L.UPLOAD_DONE) == L.RESUME:
+                    verify_and_resume(i)
+            elif kind == "call_finish":
+                elapsed = t - a["t_call"]
+                assert K.tc_forecaster_observe(fc, ftype, elapsed) == 0
+                fc_model.observe(ftype, elapsed)
+                act = lifecycle(i, L.CALL_FINISH)
+                if act == L.RESUME:
+                    if "sig" in a:
+                        counts["resumed_at_once"] += 1
+                        verify_and_resume(i)
+                elif act == L.UPLOAD_NOW:
+                    counts["immediate"] += 1
+                    upload_piece(i, t, everything=True)
+                # WAIT: a copy is in flight; its completion event takes it from here
+            elif kind == "finish":
+                if a["req"].state != L.RUNNING:            # still coming back: finish once it has resumed
+                    push(t + step_ms, "finish", i)
+                    continue
+                K.check(K.tc_free(gp.ctx, a["ids"]))
+                pool_model.free(a["ids"].tolist())
+        sync()
+        rc, st = K.tc_stats(gp.ctx)
+        assert st.gpu_blocks_free == gp.NB and st.host_slots_used == 0
+        assert counts["approved"] > 5 and counts["rejected"] > 0, counts
+        assert counts["resumed_at_once"] > 0 and counts["immediate"] > 0, counts
+        assert counts["pieces"] > counts["approved"], counts       # uploads really came in pieces
+        K.tc_forecaster_destroy(fc)
+    finally:
+        gp.close()

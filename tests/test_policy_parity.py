@@ -64,3 +64,61 @@ def test_budget_and_gradual_reserve_match_oracle():
     big = 2**32 - 1
     assert K.tc_gradual_reserve(big, big, big) == policy.gradual_reserve(big, big, big) == 2**31
     assert K.tc_upload_budget(big, big, 0) == 0
+
+
+def test_lifecycle_matches_oracle_on_every_state_and_event():
+    from oracle import lifecycle as L
+    for state in range(5):
+        for fin in (False, True):
+            for fly in (False, True):
+                for event in range(-1, 7):
+                    req = K.tc_req_state(state, fin, fly, 0)
+                    rc, action = K.tc_lifecycle_step(req, event)
+                    try:
+                        want, want_action = L.step((state, fin, fly), event)
+                    except L.Invalid:
+                        assert rc == K.TC_ERR_INVAL and req.as_tuple() == (state, fin, fly)
+                        continue
+                    assert rc == 0 and req.as_tuple() == want and action == want_action, (state, fin, fly, event)
+    assert K.tc_lifecycle_step(K.tc_req_state(9, 0, 0, 0), 0)[0] == K.TC_ERR_INVAL
+
+
+def test_lifecycle_random_walks_match_oracle():
+    from oracle import lifecycle as L
+    rng = np.random.default_rng(8)
+    resumes = 0
+    for _ in range(300):
+        req, model = K.tc_req_state(0, 0, 0, 0), (L.RUNNING, False, False)
+        for _ in range(40):
+            e = int(rng.integers(0, 6))
+            rc, action = K.tc_lifecycle_step(req, e)
+            try:
+                model, want_action = L.step(model, e)
+            except L.Invalid:
+                assert rc == K.TC_ERR_INVAL
+            else:
+                assert rc == 0 and action == want_action
+                resumes += action == L.RESUME
+            assert req.as_tuple() == model
+    assert resumes > 100
+
+
+def test_forecaster_matches_oracle():
+    from oracle import lifecycle as L
+    rng = np.random.default_rng(9)
+    for alpha, gamma, default in ((0.3, 0.25, 5000.0), (0.0, 1.0, 0.0), (1.0, 0.5, 10.0)):
+        rc, f = K.tc_forecaster_create(alpha, gamma, default)
+        assert rc == 0
+        o = L.Forecaster(alpha, gamma, default)
+        for _ in range(400):
+            t = int(rng.integers(0, 6))
+            if rng.random() < 0.5:
+                x = float(rng.exponential(2000.0))
+                assert K.tc_forecaster_observe(f, t, x) == 0
+                o.observe(t, x)
+            user = float(rng.uniform(10, 9000)) if rng.random() < 0.5 else None
+            got, want = K.tc_forecaster_estimate(f, t, user), o.estimate(t, user)
+            assert got == want or abs(got - want) <= 1e-12 * abs(want)
+        K.tc_forecaster_destroy(f)
+    assert K.tc_forecaster_create(1.5, 0.5, 1.0)[0] == K.TC_ERR_INVAL
+    assert K.tc_forecaster_create(0.5, 0.0, 1.0)[0] == K.TC_ERR_INVAL
