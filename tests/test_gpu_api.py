@@ -275,3 +275,121 @@ def test_calibrated_cost_model_predicts_a_transfer_and_leaves_the_pool_alone():
         assert K.tc_calibrate(gp.ctx, [32, 500], 1, stream)[0] == K.TC_ERR_NOMEM
     finally:
         gp.close()
+
+
+def test_whole_pool_moves_in_one_call_over_many_chunks():
+    """Maximum size: every block of the pool is a source, then a destination (reversed order)."""
+    rng = W.rng_for(1, salt=31)
+    shape = W.CONFIGS[1].with_blocks(160)                       # 320 MiB pool
+    L, NB, pb = shape.num_layers, shape.num_blocks, shape.page_bytes
+    pool_h = W.make_pool_host(shape, rng)
+    ids = rng.permutation(NB).astype(np.int32)
+    gp = GpuPool(shape, pool_h, None, staging_bytes=2 * 7 * 2 * 1024 * 1024, staging_slots=2)   # 7 records per chunk
+    try:
+        host = pinned_bytes(NB * gp.rec)
+        rc, got = K.tc_alloc(gp.ctx, NB)
+        assert rc == 0 and K.tc_alloc(gp.ctx, 1)[0] == K.TC_ERR_NOMEM
+        K.check(K.tc_offload(gp.ctx, ids, host))
+        want = np.empty(NB * gp.rec, dtype=np.uint8)
+        oracle.offload(pool_h, None, L, NB, pb, 0, ids, want)
+        torch.cuda.synchronize()
+        assert np.array_equal(host.numpy(), want)
+        new_ids = ids[::-1].copy()
+        table = torch.full((NB,), -1, dtype=torch.int32, device=DEV)
+        table_h = np.full(NB, -1, dtype=np.int32)
+        oracle.upload(want, L, NB, pb, 0, new_ids, pool_h, None, table_h)
+        K.check(K.tc_upload(gp.ctx, host, new_ids, table))
+        torch.cuda.synchronize()
+        assert np.array_equal(gp.pool_to_host(), pool_h)
+        assert np.array_equal(table.cpu().numpy(), table_h)
+        # one id too many can only be a repeat
+        assert K.tc_offload(gp.ctx, np.concatenate([ids, ids[:1]]), host) == K.TC_ERR_DUP
+    finally:
+        gp.close()
+
+
+def test_two_streams_share_one_staging_slot():
+    """An offload and an upload of different agents issued back to back on different streams must not
+    trample each other's chunk in the single staging slot."""
+    rng = W.rng_for(1, salt=32)
+    shape = W.CONFIGS[1].with_blocks(128)
+    L, NB, pb = shape.num_layers, shape.num_blocks, shape.page_bytes
+    pool_h = W.make_pool_host(shape, rng)
+    perm = W.pick_ids(rng, NB, 90)
+    a_src, b_src, b_dst = perm[:30], perm[30:60], perm[60:90]
+    gp = GpuPool(shape, pool_h, None, staging_bytes=4 * 2 * 1024 * 1024, staging_slots=1)       # 4 records per chunk
+    try:
+        rec = gp.rec
+        s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+        K.check(K.tc_alloc_at(gp.ctx, perm))
+        host_a, host_b = pinned_bytes(30 * rec), pinned_bytes(30 * rec)
+        K.check(K.tc_offload(gp.ctx, b_src, host_b, s1))
+        s1.synchronize()
+        want_b = np.empty(30 * rec, dtype=np.uint8)
+        oracle.offload(pool_h, None, L, NB, pb, 0, b_src, want_b)
+        assert np.array_equal(host_b.numpy(), want_b)
+        want_a = np.empty(30 * rec, dtype=np.uint8)
+        oracle.offload(pool_h, None, L, NB, pb, 0, a_src, want_a)       # a_src is not touched by b's upload
+        for _ in range(3):
+            host_a.fill_(0)
+            K.check(K.tc_offload(gp.ctx, a_src, host_a, s1))            # chunks of the two transfers
+            K.check(K.tc_upload(gp.ctx, host_b, b_dst, None, s2))       # interleave in the one slot
+            torch.cuda.synchronize()
+            assert np.array_equal(host_a.numpy(), want_a)
+        oracle.upload(want_b, L, NB, pb, 0, b_dst, pool_h, None, None)
+        assert np.array_equal(gp.pool_to_host(), pool_h)
+    finally:
+        gp.close()
+
+
+def test_calls_from_several_host_threads():
+    """The context serialises callers: four threads, each with its own stream and agent."""
+    import threading
+    rng = W.rng_for(1, salt=33)
+    shape = W.CONFIGS[1].with_blocks(256)
+    L, NB, pb = shape.num_layers, shape.num_blocks, shape.page_bytes
+    pool_h = W.make_pool_host(shape, rng)
+    perm = W.pick_ids(rng, NB, 4 * 2 * 24)
+    gp = GpuPool(shape, pool_h, None, staging_bytes=2 * 8 * 2 * 1024 * 1024, staging_slots=2,
+                 host_arena_bytes=100 * 2 * 1024 * 1024)
+    try:
+        rec = gp.rec
+        K.check(K.tc_alloc_at(gp.ctx, perm))
+        errors, bufs = [], [None] * 4
+        tables = torch.full((4, 24), -1, dtype=torch.int32, device=DEV)
+
+        def worker(k):
+            try:
+                torch.cuda.set_device(0)
+                stream = torch.cuda.Stream()
+                src, dst = perm[48 * k: 48 * k + 24], perm[48 * k + 24: 48 * k + 48]
+                rc, buf = K.tc_host_alloc(gp.ctx, 24)
+                K.check(rc)
+                bufs[k] = buf
+                for _ in range(3):
+                    K.check(K.tc_offload(gp.ctx, src, buf, stream))
+                    K.check(K.tc_upload(gp.ctx, buf, dst, tables[k], stream))
+                    K.check(K.tc_poll(gp.ctx))
+                stream.synchronize()
+            except Exception as e:      # noqa: BLE001
+                errors.append(e)
+
+        threads = [threading.Thread(target=worker, args=(k,)) for k in range(4)]
+        for t in threads:
+            t.start()
+        for t in threads:
+            t.join()
+        assert not errors, errors
+        K.check(K.tc_sync(gp.ctx))
+        for k in range(4):
+            src, dst = perm[48 * k: 48 * k + 24], perm[48 * k + 24: 48 * k + 48]
+            want = np.empty(24 * rec, dtype=np.uint8)
+            oracle.offload(pool_h, None, L, NB, pb, 0, src, want)
+            from harness import host_view
+            assert np.array_equal(host_view(bufs[k], 24 * rec), want)
+            oracle.upload(want, L, NB, pb, 0, dst, pool_h, None, None)
+            assert np.array_equal(tables[k].cpu().numpy(), dst)
+        assert np.array_equal(gp.pool_to_host(), pool_h)
+        assert _stats(gp).ops_in_flight == 0
+    finally:
+        gp.close()
