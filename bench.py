@@ -103,6 +103,30 @@ def cpu_baseline(shape, ids, new_ids, budget_s=12.0):
             break
     o, u = float(np.median(t_off)), float(np.median(t_up))
     payload = n * rec
+
+    # the same oracle called from one thread per host core on disjoint runs of blocks (context only)
+    from concurrent.futures import ThreadPoolExecutor
+    workers = max(1, min(os.cpu_count() or 1, 16))
+    cuts = np.linspace(0, n, workers + 1).astype(int)
+
+    def part(k, direction):
+        a, b = cuts[k], cuts[k + 1]
+        if a == b:
+            return
+        if direction == 0:
+            oracle.offload(pool, None, L, NB, pb, 0, ids[a:b], host[a * rec:b * rec])
+        else:
+            oracle.upload(host[a * rec:b * rec], L, NB, pb, 0, new_ids[a:b], pool, None, table[a:b])
+
+    par = []
+    with ThreadPoolExecutor(workers) as ex:
+        for direction in (0, 1):
+            ts = []
+            for _ in range(5):
+                t = time.perf_counter()
+                list(ex.map(lambda k: part(k, direction), range(workers)))
+                ts.append(time.perf_counter() - t)
+            par.append(float(np.median(ts)))
     res = {
         "value": round(2 * payload / (o + u) / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
         "sample": f"the same agent ({n} blocks, {payload >> 20} MiB each way), offload+upload on a sparse host "
@@ -110,6 +134,9 @@ def cpu_baseline(shape, ids, new_ids, budget_s=12.0):
         "offload_GBps": round(payload / o / 1e9, 3), "upload_GBps": round(payload / u / 1e9, 3),
         "upload_ms_per_1k_tokens": round(u * 1e3 / (n * shape.block_size / 1024), 3),
         "host_cores_available": os.cpu_count(),
+        "parallel_calls": {"threads": workers, "value": round(2 * payload / (par[0] + par[1]) / 1e9, 3),
+                           "offload_GBps": round(payload / par[0] / 1e9, 3),
+                           "upload_GBps": round(payload / par[1] / 1e9, 3)},
     }
     del pool, v
     return res
