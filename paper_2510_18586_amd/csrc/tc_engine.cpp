@@ -49,6 +49,7 @@ struct Op {
     std::vector<int32_t> ids;
     std::vector<uint64_t> arena_starts;
     uint64_t ring_consumed = 0;
+    uint64_t ring_prev_tail = 0;  // to undo the newest allocation
     std::vector<Timed> timed;
 };
 
@@ -193,7 +194,7 @@ int sync_locked(tc_ctx *c)
 }
 
 // n consecutive entries of the id rings; waits for old transfers when the ring is full.
-int ring_alloc(tc_ctx *c, uint64_t n, uint64_t *start, uint64_t *consumed)
+int ring_alloc(tc_ctx *c, uint64_t n, uint64_t *start, uint64_t *consumed, uint64_t *prev_tail)
 {
     if (n > c->ring_cap) return TC_ERR_INVAL;
     for (;;) {
@@ -204,6 +205,7 @@ int ring_alloc(tc_ctx *c, uint64_t n, uint64_t *start, uint64_t *consumed)
             at = 0;
         }
         if (c->ring_used + waste + n <= c->ring_cap) {
+            *prev_tail = c->ring_tail;
             c->ring_used += waste + n;
             c->ring_tail = (at + n) % c->ring_cap;
             *start = at;
@@ -277,10 +279,19 @@ int validate(tc_ctx *c, const tc_xfer_desc *descs, uint32_t n_descs, Plan *plan)
 int begin_op(tc_ctx *c, Plan &plan, hipStream_t stream, Op *op, uint64_t *ring_start)
 {
     if (int rc = get_event(c, false, &op->done)) return rc;
-    if (int rc = ring_alloc(c, plan.total, ring_start, &op->ring_consumed)) return rc;
+    if (int rc = ring_alloc(c, plan.total, ring_start, &op->ring_consumed, &op->ring_prev_tail)) {
+        put_event(c, false, op->done);
+        return rc;
+    }
     std::memcpy(c->ids_host + *ring_start, plan.ids.data(), plan.total * sizeof(int32_t));
-    HIP_TRY(hipMemcpyAsync(c->ids_dev + *ring_start, c->ids_host + *ring_start, plan.total * sizeof(int32_t),
-                           hipMemcpyHostToDevice, stream));
+    if (hipMemcpyAsync(c->ids_dev + *ring_start, c->ids_host + *ring_start, plan.total * sizeof(int32_t),
+                       hipMemcpyHostToDevice, stream) != hipSuccess) {
+        (void)hipGetLastError();
+        c->ring_used -= op->ring_consumed;
+        c->ring_tail = op->ring_prev_tail;
+        put_event(c, false, op->done);
+        return TC_ERR_HIP;
+    }
     c->blocks->begin_transfer(plan.ids.data(), uint32_t(plan.total));
     for (const Segment &s : plan.segs) {
         if (c->arena_base && s.host >= c->arena_base && s.host < c->arena_base + c->arena_bytes) {
@@ -292,6 +303,20 @@ int begin_op(tc_ctx *c, Plan &plan, hipStream_t stream, Op *op, uint64_t *ring_s
     }
     op->ids = std::move(plan.ids);
     return TC_OK;
+}
+
+int abort_op(tc_ctx *c, Op *op, int rc)
+{
+    c->blocks->end_transfer(op->ids.data(), uint32_t(op->ids.size()));
+    for (uint64_t s : op->arena_starts) c->arena->end_transfer(s);
+    c->ring_used -= op->ring_consumed;  // the newest allocation: the tail steps back over it
+    c->ring_tail = op->ring_prev_tail;
+    for (Timed &t : op->timed) {
+        put_event(c, true, t.t0);
+        put_event(c, true, t.t1);
+    }
+    put_event(c, false, op->done);
+    return rc;
 }
 
 int time_begin(tc_ctx *c, Op *op, hipStream_t stream, uint64_t bytes, int kind)
@@ -338,23 +363,27 @@ int offload_locked(tc_ctx *c, const tc_xfer_desc *descs, uint32_t n_descs, hipSt
     uint64_t ring_start = 0;
     if (int rc = begin_op(c, plan, stream, &op, &ring_start)) return rc;
 
-    uint64_t c0 = 0;
-    for (uint32_t nblk : plan_chunks(plan.total, c->slot_blocks, false)) {
-        Slot *slot = &c->slots[c->next_slot];
-        c->next_slot = (c->next_slot + 1) % uint32_t(c->slots.size());
-        if (slot->used) HIP_TRY(hipStreamWaitEvent(stream, slot->last, 0));
-        if (int rc = time_begin(c, &op, stream, uint64_t(nblk) * c->rec, kGather)) return rc;
-        HIP_TRY(tc::launch_gather_pages(c->pool.kv_base, static_cast<const uint32_t *>(c->pool.scales), slot->buf,
-                                        c->ids_dev + ring_start + c0, nblk, c->geom, c->opts.max_grid, stream));
-        if (int rc = time_end(c, &op, stream)) return rc;
-        if (int rc = time_begin(c, &op, stream, uint64_t(nblk) * c->rec, kD2H)) return rc;
-        if (int rc = dma_chunk(c, plan, c0, c0 + nblk, slot->buf, true, stream)) return rc;
-        if (int rc = time_end(c, &op, stream)) return rc;
-        HIP_TRY(hipEventRecord(slot->last, stream));
-        slot->used = true;
-        c0 += nblk;
-    }
-    HIP_TRY(hipEventRecord(op.done, stream));
+    auto enqueue = [&]() -> int {
+        uint64_t c0 = 0;
+        for (uint32_t nblk : plan_chunks(plan.total, c->slot_blocks, false)) {
+            Slot *slot = &c->slots[c->next_slot];
+            c->next_slot = (c->next_slot + 1) % uint32_t(c->slots.size());
+            if (slot->used) HIP_TRY(hipStreamWaitEvent(stream, slot->last, 0));
+            if (int rc = time_begin(c, &op, stream, uint64_t(nblk) * c->rec, kGather)) return rc;
+            HIP_TRY(tc::launch_gather_pages(c->pool.kv_base, static_cast<const uint32_t *>(c->pool.scales), slot->buf,
+                                            c->ids_dev + ring_start + c0, nblk, c->geom, c->opts.max_grid, stream));
+            if (int rc = time_end(c, &op, stream)) return rc;
+            if (int rc = time_begin(c, &op, stream, uint64_t(nblk) * c->rec, kD2H)) return rc;
+            if (int rc = dma_chunk(c, plan, c0, c0 + nblk, slot->buf, true, stream)) return rc;
+            if (int rc = time_end(c, &op, stream)) return rc;
+            HIP_TRY(hipEventRecord(slot->last, stream));
+            slot->used = true;
+            c0 += nblk;
+        }
+        HIP_TRY(hipEventRecord(op.done, stream));
+        return TC_OK;
+    };
+    if (int rc = enqueue()) return abort_op(c, &op, rc);
 
     c->st.n_offloads++;
     c->st.blocks_offloaded += plan.total;
@@ -376,26 +405,30 @@ int upload_locked(tc_ctx *c, const tc_xfer_desc *descs, uint32_t n_descs, hipStr
     uint64_t ring_start = 0;
     if (int rc = begin_op(c, plan, stream, &op, &ring_start)) return rc;
 
-    uint64_t c0 = 0;
-    for (uint32_t nblk : plan_chunks(plan.total, c->slot_blocks, true)) {
-        Slot *slot = &c->slots[c->next_slot];
-        c->next_slot = (c->next_slot + 1) % uint32_t(c->slots.size());
-        if (slot->used) HIP_TRY(hipStreamWaitEvent(stream, slot->last, 0));
-        if (int rc = time_begin(c, &op, stream, uint64_t(nblk) * c->rec, kH2D)) return rc;
-        if (int rc = dma_chunk(c, plan, c0, c0 + nblk, slot->buf, false, stream)) return rc;
-        if (int rc = time_end(c, &op, stream)) return rc;
-        if (int rc = time_begin(c, &op, stream, uint64_t(nblk) * c->rec, kScatter)) return rc;
-        HIP_TRY(tc::launch_scatter_pages(slot->buf, c->pool.kv_base, static_cast<uint32_t *>(c->pool.scales),
-                                         c->ids_dev + ring_start + c0, nblk, c->geom, c->opts.max_grid, stream));
-        if (int rc = time_end(c, &op, stream)) return rc;
-        HIP_TRY(hipEventRecord(slot->last, stream));
-        slot->used = true;
-        c0 += nblk;
-    }
-    // the mapping is restored only after the data it points to is in place
-    for (const Segment &s : plan.segs)
-        if (s.table) HIP_TRY(tc::launch_rewrite_table(s.table, c->ids_dev + ring_start + s.first, s.n, stream));
-    HIP_TRY(hipEventRecord(op.done, stream));
+    auto enqueue = [&]() -> int {
+        uint64_t c0 = 0;
+        for (uint32_t nblk : plan_chunks(plan.total, c->slot_blocks, true)) {
+            Slot *slot = &c->slots[c->next_slot];
+            c->next_slot = (c->next_slot + 1) % uint32_t(c->slots.size());
+            if (slot->used) HIP_TRY(hipStreamWaitEvent(stream, slot->last, 0));
+            if (int rc = time_begin(c, &op, stream, uint64_t(nblk) * c->rec, kH2D)) return rc;
+            if (int rc = dma_chunk(c, plan, c0, c0 + nblk, slot->buf, false, stream)) return rc;
+            if (int rc = time_end(c, &op, stream)) return rc;
+            if (int rc = time_begin(c, &op, stream, uint64_t(nblk) * c->rec, kScatter)) return rc;
+            HIP_TRY(tc::launch_scatter_pages(slot->buf, c->pool.kv_base, static_cast<uint32_t *>(c->pool.scales),
+                                             c->ids_dev + ring_start + c0, nblk, c->geom, c->opts.max_grid, stream));
+            if (int rc = time_end(c, &op, stream)) return rc;
+            HIP_TRY(hipEventRecord(slot->last, stream));
+            slot->used = true;
+            c0 += nblk;
+        }
+        // the mapping is restored only after the data it points to is in place
+        for (const Segment &s : plan.segs)
+            if (s.table) HIP_TRY(tc::launch_rewrite_table(s.table, c->ids_dev + ring_start + s.first, s.n, stream));
+        HIP_TRY(hipEventRecord(op.done, stream));
+        return TC_OK;
+    };
+    if (int rc = enqueue()) return abort_op(c, &op, rc);
 
     c->st.n_uploads++;
     c->st.blocks_uploaded += plan.total;
@@ -745,8 +778,8 @@ int tc_naive_transfer(tc_ctx *ctx, const int32_t *block_ids, uint32_t n, void *h
 {
     if (!ctx || (n && (!block_ids || !host_buf)) || mode < 0 || mode > 1 || direction < 0 || direction > 1)
         return TC_ERR_INVAL;
-    if (ctx->pool.scales_per_block) return TC_ERR_INVAL;
     std::lock_guard<std::mutex> g(ctx->mu);
+    if (ctx->pool.scales_per_block) return TC_ERR_INVAL;
     if (int rc = ctx->blocks->check_range(block_ids, n)) return rc;
     if (n && !is_pinned_host(ctx, host_buf, uint64_t(n) * ctx->rec)) return TC_ERR_NOT_PINNED;
     hipStream_t st = static_cast<hipStream_t>(stream);
