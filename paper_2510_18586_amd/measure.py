@@ -24,6 +24,7 @@ import numpy as np
 
 
 def _sync_time(torch, fn, reps=5, warm=1):
+    """Median wall time of fn() + device synchronisation."""
     ts = []
     for i in range(reps + warm):
         torch.cuda.synchronize()
