@@ -523,6 +523,15 @@ int tc_create(const tc_pool_desc *pool, const tc_opts *opts, tc_ctx **out)
         c->slots[i].buf = c->staging + uint64_t(i) * c->slot_bytes;
         HIP_OR_FAIL(hipEventCreateWithFlags(&c->slots[i].last, hipEventDisableTiming));
     }
+    // Touch what the first transfers will touch, once, here: the runtime maps pinned pages for the
+    // copy engines lazily, and a first DMA into fresh arena pages was seen to take up to three times
+    // as long.  One pass of zeros from the staging ring over the whole arena pays for that now (this
+    // is the recycled CPU block pool of Sec. 6.3: allocate once, never go back to the system).
+    const uint64_t ring_bytes = c->slot_bytes * n_slots;
+    HIP_OR_FAIL(hipMemset(c->staging, 0, ring_bytes));
+    for (uint64_t off = 0; off < c->arena_bytes; off += ring_bytes)
+        HIP_OR_FAIL(hipMemcpy(c->arena_base + off, c->staging, std::min(ring_bytes, c->arena_bytes - off),
+                              hipMemcpyDeviceToHost));
     // first transfers should not pay for event creation
     for (int i = 0; i < 8; ++i) {
         hipEvent_t e = nullptr;
