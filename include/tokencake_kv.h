@@ -17,7 +17,7 @@
  *               scales_per_block in {0, 1, P}
  *   host record rec = roundup256(P*page_bytes + 4*scales_per_block) bytes per block:
  *               [page 0 | ... | page P-1 | scale words | zero pad]
- *   host buffer HOST pinned memory, n consecutive records, record j = block ids[j]
+ *   host buffer HOST pinned memory, 16-B aligned, n consecutive records, record j = block ids[j]
  *
  * Conventions
  *   - every function returns TC_OK (0) or a negative TC_ERR_* code; nothing throws
@@ -70,7 +70,10 @@ typedef struct {
     uint64_t staging_bytes;     /* device staging ring in total; 0 = default                       */
     uint32_t staging_slots;     /* ring depth, >= 1; 0 = default                                   */
     uint32_t max_grid;          /* cap on workgroups per gather/scatter launch; 0 = one per tile   */
-    uint32_t reserved[2];       /* must be 0                                                       */
+    uint32_t direct_offload;    /* 0 = staged (gather to HBM, then DMA); 1 = the gather kernel writes the
+                                   records straight into the pinned host buffer; 2 = direct only while an
+                                   upload of this context is in flight (the two directions then overlap) */
+    uint32_t direct_grid;       /* workgroups of a direct gather; 0 = default (6)                  */
 } tc_opts;
 
 typedef struct {
@@ -91,6 +94,8 @@ typedef struct {
     uint64_t gather_launches, scatter_launches;
     uint64_t gather_bytes, scatter_bytes;     /* record bytes the timed launches moved one way     */
     double gather_ms, scatter_ms;             /* sum of per-launch durations from HIP events       */
+    uint64_t direct_launches, direct_bytes;   /* direct gathers: bound by the host link, not by HBM */
+    double direct_ms;
     uint64_t d2h_copies, h2d_copies;          /* timed DMA chunks (all copies of one chunk together) */
     uint64_t d2h_bytes, h2d_bytes;
     double d2h_ms, h2d_ms;                    /* event pairs on the stream around each chunk's DMAs */

@@ -29,6 +29,9 @@ namespace {
 
 constexpr uint64_t kDefaultSlotBytes = 512ull << 20;
 constexpr uint32_t kDefaultSlots = 2;
+// A handful of workgroups saturate the host link; more only deepen the queue of host-bound stores
+// that other kernels' memory traffic has to wait behind.
+constexpr uint32_t kDefaultDirectGrid = 6;
 
 struct Slot {
     char *buf = nullptr;
@@ -36,7 +39,7 @@ struct Slot {
     bool used = false;
 };
 
-enum TimedKind { kGather = 0, kScatter = 1, kD2H = 2, kH2D = 3 };
+enum TimedKind { kGather = 0, kScatter = 1, kD2H = 2, kH2D = 3, kDirect = 4 };
 
 struct Timed {
     hipEvent_t t0, t1;
@@ -46,6 +49,7 @@ struct Timed {
 
 struct Op {
     hipEvent_t done = nullptr;
+    bool is_upload = false;
     std::vector<int32_t> ids;
     std::vector<uint64_t> arena_starts;
     uint64_t ring_consumed = 0;
@@ -156,6 +160,7 @@ int retire_front(tc_ctx *c)
             switch (t.kind) {
             case kGather: c->st.gather_launches++; c->st.gather_bytes += t.bytes; c->st.gather_ms += ms; break;
             case kScatter: c->st.scatter_launches++; c->st.scatter_bytes += t.bytes; c->st.scatter_ms += ms; break;
+            case kDirect: c->st.direct_launches++; c->st.direct_bytes += t.bytes; c->st.direct_ms += ms; break;
             case kD2H: c->st.d2h_copies++; c->st.d2h_bytes += t.bytes; c->st.d2h_ms += ms; break;
             default: c->st.h2d_copies++; c->st.h2d_bytes += t.bytes; c->st.h2d_ms += ms; break;
             }
@@ -264,6 +269,7 @@ int validate(tc_ctx *c, const tc_xfer_desc *descs, uint32_t n_descs, Plan *plan)
     plan->total = total;
     if (int rc = c->blocks->check_transfer(plan->ids.data(), uint32_t(total))) return rc;
     for (const Segment &s : plan->segs) {
+        if (reinterpret_cast<uintptr_t>(s.host) % 16) return TC_ERR_INVAL;
         if (!is_pinned_host(c, s.host, uint64_t(s.n) * c->rec)) return TC_ERR_NOT_PINNED;
         if (c->arena_base && s.host >= c->arena_base && s.host < c->arena_base + c->arena_bytes) {
             uint64_t off = uint64_t(s.host - c->arena_base);
@@ -363,6 +369,30 @@ int offload_locked(tc_ctx *c, const tc_xfer_desc *descs, uint32_t n_descs, hipSt
     uint64_t ring_start = 0;
     if (int rc = begin_op(c, plan, stream, &op, &ring_start)) return rc;
 
+    // Direct path: the gather kernel writes each agent's records straight into its pinned host buffer.
+    // Slightly slower alone than gather + SDMA, but kernel-driven D2H traffic overlaps with H2D DMAs,
+    // which two SDMA copies of opposite direction do not.
+    bool direct = c->opts.direct_offload == 1;
+    if (c->opts.direct_offload == 2)
+        for (const Op &o : c->ops) direct = direct || o.is_upload;
+    auto enqueue_direct = [&]() -> int {
+        const uint32_t grid = c->opts.direct_grid ? c->opts.direct_grid : kDefaultDirectGrid;
+        std::vector<void *> dev_view(plan.segs.size());
+        for (size_t k = 0; k < plan.segs.size(); ++k)  // the address the GPU sees the pinned buffer at
+            if (hipHostGetDevicePointer(&dev_view[k], plan.segs[k].host, 0) != hipSuccess) {
+                (void)hipGetLastError();
+                return TC_ERR_NOT_PINNED;
+            }
+        for (size_t k = 0; k < plan.segs.size(); ++k) {
+            const Segment &s = plan.segs[k];
+            if (int rc = time_begin(c, &op, stream, uint64_t(s.n) * c->rec, kDirect)) return rc;
+            HIP_TRY(tc::launch_gather_pages(c->pool.kv_base, static_cast<const uint32_t *>(c->pool.scales), dev_view[k],
+                                            c->ids_dev + ring_start + s.first, s.n, c->geom, grid, true, stream));
+            if (int rc = time_end(c, &op, stream)) return rc;
+        }
+        HIP_TRY(hipEventRecord(op.done, stream));
+        return TC_OK;
+    };
     auto enqueue = [&]() -> int {
         uint64_t c0 = 0;
         for (uint32_t nblk : plan_chunks(plan.total, c->slot_blocks, false)) {
@@ -371,7 +401,7 @@ int offload_locked(tc_ctx *c, const tc_xfer_desc *descs, uint32_t n_descs, hipSt
             if (slot->used) HIP_TRY(hipStreamWaitEvent(stream, slot->last, 0));
             if (int rc = time_begin(c, &op, stream, uint64_t(nblk) * c->rec, kGather)) return rc;
             HIP_TRY(tc::launch_gather_pages(c->pool.kv_base, static_cast<const uint32_t *>(c->pool.scales), slot->buf,
-                                            c->ids_dev + ring_start + c0, nblk, c->geom, c->opts.max_grid, stream));
+                                            c->ids_dev + ring_start + c0, nblk, c->geom, c->opts.max_grid, false, stream));
             if (int rc = time_end(c, &op, stream)) return rc;
             if (int rc = time_begin(c, &op, stream, uint64_t(nblk) * c->rec, kD2H)) return rc;
             if (int rc = dma_chunk(c, plan, c0, c0 + nblk, slot->buf, true, stream)) return rc;
@@ -383,7 +413,7 @@ int offload_locked(tc_ctx *c, const tc_xfer_desc *descs, uint32_t n_descs, hipSt
         HIP_TRY(hipEventRecord(op.done, stream));
         return TC_OK;
     };
-    if (int rc = enqueue()) return abort_op(c, &op, rc);
+    if (int rc = direct ? enqueue_direct() : enqueue()) return abort_op(c, &op, rc);
 
     c->st.n_offloads++;
     c->st.blocks_offloaded += plan.total;
@@ -429,6 +459,7 @@ int upload_locked(tc_ctx *c, const tc_xfer_desc *descs, uint32_t n_descs, hipStr
         return TC_OK;
     };
     if (int rc = enqueue()) return abort_op(c, &op, rc);
+    op.is_upload = true;
 
     c->st.n_uploads++;
     c->st.blocks_uploaded += plan.total;
@@ -470,6 +501,7 @@ int tc_create(const tc_pool_desc *pool, const tc_opts *opts, tc_ctx **out)
     if (S != 0 && S != 1 && S != P) return TC_ERR_INVAL;
     if ((S != 0) != (pool->scales != nullptr)) return TC_ERR_INVAL;
     if (S && (reinterpret_cast<uintptr_t>(pool->scales) % 4)) return TC_ERR_INVAL;
+    if (opts && opts->direct_offload > 2) return TC_ERR_INVAL;
     if (!is_device_ptr(pool->kv_base) || (S && !is_device_ptr(pool->scales))) return TC_ERR_NOT_PINNED;
 
     tc_ctx *c = new (std::nothrow) tc_ctx;

@@ -16,9 +16,11 @@ struct PageGeom {
     uint32_t tail_words;   // 32-bit words from the end of the pages to the end of the record
 };
 
-// staging[k] <- record of block ids[k] for k < n (pages, scale words, zero pad).
+// staging[k] <- record of block ids[k] for k < n (pages, scale words, zero pad).  `staging` is a
+// device staging chunk, or (streaming_stores = true) pinned host memory written over the host link.
 hipError_t launch_gather_pages(const void *pool, const uint32_t *scales, void *staging, const int32_t *ids_dev,
-                               uint32_t n, const PageGeom &g, uint32_t max_grid, hipStream_t stream);
+                               uint32_t n, const PageGeom &g, uint32_t max_grid, bool streaming_stores,
+                               hipStream_t stream);
 // block ids[k] <- record k of staging.
 hipError_t launch_scatter_pages(const void *staging, void *pool, uint32_t *scales, const int32_t *ids_dev,
                                 uint32_t n, const PageGeom &g, uint32_t max_grid, hipStream_t stream);

@@ -131,7 +131,7 @@ __global__ __launch_bounds__(kThreads) void hbm_stream_kernel(f32x4 *__restrict_
 // ---------------------------------------------------------------------------------------------
 template <bool GATHER>
 static hipError_t launch_page_copy(void *pool, uint32_t *scales, void *staging, const int32_t *ids_dev, uint32_t n,
-                                   const PageGeom &g, uint32_t max_grid, hipStream_t stream)
+                                   const PageGeom &g, uint32_t max_grid, bool streaming_stores, hipStream_t stream)
 {
     if (n == 0) return hipSuccess;
     // widest tile that a page still fills
@@ -162,7 +162,7 @@ static hipError_t launch_page_copy(void *pool, uint32_t *scales, void *staging, 
     case 2: TC_LAUNCH(2, NL, NS); break;     \
     default: TC_LAUNCH(1, NL, NS); break;    \
     }
-    if (GATHER) { TC_LAUNCH_U(true, false) }
+    if (GATHER && !streaming_stores) { TC_LAUNCH_U(true, false) }
     else { TC_LAUNCH_U(true, true) }
 #undef TC_LAUNCH_U
 #undef TC_LAUNCH
@@ -170,16 +170,17 @@ static hipError_t launch_page_copy(void *pool, uint32_t *scales, void *staging, 
 }
 
 hipError_t launch_gather_pages(const void *pool, const uint32_t *scales, void *staging, const int32_t *ids_dev,
-                               uint32_t n, const PageGeom &g, uint32_t max_grid, hipStream_t stream)
+                               uint32_t n, const PageGeom &g, uint32_t max_grid, bool streaming_stores,
+                               hipStream_t stream)
 {
     return launch_page_copy<true>(const_cast<void *>(pool), const_cast<uint32_t *>(scales), staging, ids_dev, n, g,
-                                  max_grid, stream);
+                                  max_grid, streaming_stores, stream);
 }
 
 hipError_t launch_scatter_pages(const void *staging, void *pool, uint32_t *scales, const int32_t *ids_dev,
                                 uint32_t n, const PageGeom &g, uint32_t max_grid, hipStream_t stream)
 {
-    return launch_page_copy<false>(pool, scales, const_cast<void *>(staging), ids_dev, n, g, max_grid, stream);
+    return launch_page_copy<false>(pool, scales, const_cast<void *>(staging), ids_dev, n, g, max_grid, true, stream);
 }
 
 hipError_t launch_rewrite_table(int32_t *table, const int32_t *ids_dev, uint32_t n, hipStream_t stream)

@@ -46,9 +46,11 @@ def _link_peak(torch, nbytes):
 
 
 class Ctx:
-    def __init__(self, torch, K, W, shape, seed, arena_blocks, fill=True, **opts):
+    def __init__(self, torch, K, W, shape, seed, arena_blocks, fill=True, pool=None, **opts):
         self.torch, self.K, self.shape = torch, K, shape
-        if fill:
+        if pool is not None:
+            self.pool, sc = pool, None
+        elif fill:
             self.pool = W.make_pool_device(shape, seed)
             sc = W.make_scales_device(shape, seed)
         else:
@@ -231,6 +233,37 @@ def m_config3(torch, K, W, emit):
     t_out = _sync_time(torch, lambda: K.check(K.tc_offload_batch(c.ctx, [(src[i], bufs[i]) for i in range(32)], copy)), reps=3)
     t_in = _sync_time(torch, lambda: K.check(K.tc_upload_batch(
         c.ctx, [(dst[i], bufs[i], tables[i]) for i in range(32, 64)], copy2)), reps=3)
+    # the same with offloads written by the gather kernel straight into pinned memory while uploads are
+    # in flight (direct_offload = 2), and the neighbour's rate next to such direct offloads (= 1)
+    direct = {}
+    for mode in (2, 1):
+        d = Ctx(torch, K, W, shape, 2, total + 8, pool=c.pool, direct_offload=mode)
+        for i in range(64):
+            K.check(K.tc_alloc_at(d.ctx, src[i]))
+        dbufs = [K.tc_host_alloc(d.ctx, int(n))[1] for n in nblk]
+        K.check(K.tc_offload_batch(d.ctx, [(src[i], dbufs[i]) for i in range(64)], copy))
+        K.check(K.tc_sync(d.ctx))
+
+        def dduplex():
+            K.check(K.tc_upload_batch(d.ctx, [(src[i], dbufs[i], tables[i]) for i in range(32, 64)], copy2))
+            K.check(K.tc_offload_batch(d.ctx, [(src[i], dbufs[i]) for i in range(32)], copy))
+
+        if mode == 2:
+            direct["duplex_ms"] = _sync_time(torch, dduplex, reps=3) * 1e3
+        else:
+            t_d = _sync_time(torch, lambda: K.check(K.tc_offload_batch(d.ctx, [(src[i], dbufs[i]) for i in range(64)], copy)), reps=3)
+            direct["offload_batch_GBps"] = nbytes / t_d / 1e9
+
+            def direct_offload():
+                K.check(K.tc_offload_batch(d.ctx, [(src[i], dbufs[i]) for i in range(64)], copy))
+
+            iters = max(1, int(t_d / t_tri))
+            overlapped(direct_offload, iters)
+            t_dov, tri_d = overlapped(direct_offload, iters)
+            direct["overlapped_offload_GBps"] = nbytes / t_dov / 1e9
+            direct["hbm_stream_during_direct_offload_GBps"] = tri_bytes / tri_d / 1e9
+        K.check(K.tc_sync(d.ctx))
+        K.check(K.tc_destroy(d.ctx))
     emit(dict(measurement="config3", agents=64, blocks=total, GiB=nbytes / 2 ** 30,
               link_d2h_GBps=d2h, link_h2d_GBps=h2d,
               offload_batch_GBps=nbytes / t_off / 1e9, offload_64_single_calls_GBps=nbytes / t_off1 / 1e9,
@@ -242,7 +275,12 @@ def m_config3(torch, K, W, emit):
               hbm_stream_during_upload_GBps=tri_bytes / tri_up / 1e9,
               upload_ms_per_1k_tokens=t_up * 1e3 / (total * shape.block_size / 1024),
               duplex_half_out_half_in_GBps=(half_bytes_out + half_bytes_in) / t_dup / 1e9,
-              duplex_ms=t_dup * 1e3, half_out_alone_ms=t_out * 1e3, half_in_alone_ms=t_in * 1e3))
+              duplex_ms=t_dup * 1e3, half_out_alone_ms=t_out * 1e3, half_in_alone_ms=t_in * 1e3,
+              duplex_direct_ms=direct["duplex_ms"],
+              duplex_direct_GBps=(half_bytes_out + half_bytes_in) / (direct["duplex_ms"] * 1e-3) / 1e9,
+              direct_offload_batch_GBps=direct["offload_batch_GBps"],
+              direct_overlapped_offload_GBps=direct["overlapped_offload_GBps"],
+              hbm_stream_during_direct_offload_GBps=direct["hbm_stream_during_direct_offload_GBps"]))
     del a, b, cc
     c.close()
 

@@ -43,7 +43,7 @@ def test_error_strings_and_struct_layout():
     assert ctypes.sizeof(K.tc_pool_desc) == 40
     assert ctypes.sizeof(K.tc_opts) == 32
     assert ctypes.sizeof(K.tc_xfer_desc) == 32
-    assert ctypes.sizeof(K.tc_stats_t) == 24 + 16 + 48 + 32 + 16 + 48
+    assert ctypes.sizeof(K.tc_stats_t) == 24 + 16 + 48 + 32 + 16 + 24 + 48
 
 
 def test_null_arguments_are_rejected_without_a_gpu():

@@ -394,3 +394,44 @@ def test_calls_from_several_host_threads():
         assert _stats(gp).ops_in_flight == 0
     finally:
         gp.close()
+
+
+def test_auto_mode_goes_direct_only_while_an_upload_is_in_flight():
+    """direct_offload = 2: an offload issued while an upload of the same context is in flight is written
+    by the gather kernel straight into pinned memory (so the two directions overlap on the link);
+    otherwise it takes the staged path.  Same bytes either way."""
+    rng = W.rng_for(1, salt=34)
+    shape = W.CONFIGS[1].with_blocks(512)
+    L, NB, pb = shape.num_layers, shape.num_blocks, shape.page_bytes
+    gp = GpuPool(shape, seed=34, direct_offload=2)
+    mirror = None
+    try:
+        from harness import SparseMirror
+        rec = gp.rec
+        perm = W.pick_ids(rng, NB, 3 * 128)
+        a, b, c = perm[:128], perm[128:256], perm[256:]
+        K.check(K.tc_alloc_at(gp.ctx, perm))
+        K.check(K.tc_set_profiling(gp.ctx, 1))
+        mirror = SparseMirror(gp, perm)
+        host_a, host_b = pinned_bytes(128 * rec), pinned_bytes(128 * rec)
+        s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+        K.check(K.tc_offload(gp.ctx, b, host_b, s1))                 # nothing in flight: staged
+        K.check(K.tc_sync(gp.ctx))
+        st = _stats(gp)
+        assert st.direct_launches == 0 and st.gather_launches == 1
+        K.check(K.tc_upload(gp.ctx, host_b, c, None, s2))            # 256 MiB coming in ...
+        K.check(K.tc_offload(gp.ctx, a, host_a, s1))                 # ... while 256 MiB go out: direct
+        K.check(K.tc_sync(gp.ctx))
+        st = _stats(gp)
+        assert st.direct_launches == 1 and st.direct_bytes == 128 * rec and st.gather_launches == 1
+        want = np.empty(128 * rec, dtype=np.uint8)
+        oracle.offload(mirror.pool, None, L, NB, pb, 0, a, want)
+        assert np.array_equal(host_a.numpy(), want)
+        oracle.offload(mirror.pool, None, L, NB, pb, 0, b, want)
+        assert np.array_equal(host_b.numpy(), want)
+        oracle.upload(want, L, NB, pb, 0, c, mirror.pool, None, None)
+        assert np.array_equal(gp.blocks_to_host(c), mirror.blocks(c))
+    finally:
+        if mirror:
+            mirror.close()
+        gp.close()

@@ -103,6 +103,15 @@ def test_odd_shapes_and_scales(shape, n):
     _round_trip_case(shape, 4, n, salt=n)
 
 
+@pytest.mark.parametrize("mode,grid", [(1, 0), (1, 3), (2, 0)])
+def test_direct_offload_writes_the_same_records(mode, grid):
+    # the gather kernel stores straight into the pinned host buffer (no staging, no DMA)
+    shape = W.CONFIGS[1].with_blocks(96)
+    _round_trip_case(shape, 1, 37, salt=40 + mode + grid, direct_offload=mode, direct_grid=grid)
+    _round_trip_case(W.PoolShape("fp8-small", 3, 2, 32, 8, 1, 80, 6, "fp8"), 4, 11, salt=41, direct_offload=mode, direct_grid=grid)
+    _round_trip_case(W.PoolShape("odd-ragged", 2, 5, 128, 16, 1, 40, 1, "fp8"), 4, 9, salt=42, direct_offload=mode, direct_grid=grid)
+
+
 def test_zero_blocks_is_a_no_op():
     _round_trip_case(W.CONFIGS[0], 0, 0, salt=3)
 
