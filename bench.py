@@ -72,6 +72,45 @@ def contiguous_copy_reference(torch, K, nbytes, reps=10):
     return 2 * nbytes / (ms * 1e-3) / 1e12
 
 
+def direct_paths(torch, K, pool, shape, pairs, link, steps=10):
+    """The optional paths without staging, outside the timed region: the gather kernel writes into /
+    the scatter kernel reads from the pinned buffer itself (link-bound kernels, no HBM stage)."""
+    L, NB, pb = shape.num_layers, shape.num_blocks, shape.page_bytes
+    n = len(pairs[0][0])
+    payload = n * 2 * L * pb
+    rc, ctx = K.tc_create(pool, None, L, NB, pb, shape.block_size, 0, host_arena_bytes=payload + 2 * L * pb,
+                          direct_offload=1, direct_upload=1)
+    K.check(rc)
+    rc, host = K.tc_host_alloc(ctx, n)
+    K.check(rc)
+    stream = torch.cuda.Stream()
+    off, up = [], []
+    for k in range(steps + 2):
+        src, dst = pairs[(k + 7) % len(pairs)]
+        K.check(K.tc_alloc_at(ctx, src))
+        K.check(K.tc_alloc_at(ctx, dst))
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        ev[0].record(stream)
+        K.check(K.tc_offload(ctx, src, host, stream))
+        ev[1].record(stream)
+        K.check(K.tc_upload(ctx, host, dst, None, stream))
+        ev[2].record(stream)
+        K.check(K.tc_sync(ctx))
+        K.check(K.tc_free(ctx, src))
+        K.check(K.tc_free(ctx, dst))
+        if k >= 2:
+            off.append(ev[0].elapsed_time(ev[1]))
+            up.append(ev[1].elapsed_time(ev[2]))
+    K.check(K.tc_host_free(ctx, host))
+    K.check(K.tc_destroy(ctx))
+    o, u = float(np.median(off)), float(np.median(up))
+    return {"note": "tc_opts.direct_offload = 1 (6 workgroups) / direct_upload = 1 (8 workgroups); not the default",
+            "offload_GBps": round(payload / o / 1e6, 3), "upload_GBps": round(payload / u / 1e6, 3),
+            "offload_ms": round(o, 4), "upload_ms": round(u, 4),
+            "pct_of_pinned_link": {"offload": round(100 * payload / o / 1e6 / link["d2h"], 2),
+                                   "upload": round(100 * payload / u / 1e6 / link["h2d"], 2)}}
+
+
 def cpu_baseline(shape, ids, new_ids, budget_s=12.0):
     """The oracle, as it stands, on the same agent: host mirror with the touched blocks at their true strides."""
     import mmap
@@ -257,6 +296,7 @@ def main():
                                "upload": round(100 * up_gbps / link["h2d"], 2)},
         "roofline": dominant, "roofline_other_kernel": other,
     }
+    out["direct_paths"] = direct_paths(torch, K, pool, shape, pairs, link)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(shape, ids_a, ids_b)
     K.check(K.tc_host_free(ctx, host))

@@ -73,7 +73,9 @@ typedef struct {
     uint32_t direct_offload;    /* 0 = staged (gather to HBM, then DMA); 1 = the gather kernel writes the
                                    records straight into the pinned host buffer; 2 = direct only while an
                                    upload of this context is in flight (the two directions then overlap) */
-    uint32_t direct_grid;       /* workgroups of a direct gather; 0 = default (6)                  */
+    uint32_t direct_upload;     /* 0 = staged (DMA to HBM, then scatter); 1 = the scatter kernel reads the
+                                   records straight from the pinned host buffer                      */
+    uint32_t direct_grid;       /* workgroups of a direct gather / scatter; 0 = defaults (6 / 8)   */
 } tc_opts;
 
 typedef struct {

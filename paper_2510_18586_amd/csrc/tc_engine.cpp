@@ -29,9 +29,10 @@ namespace {
 
 constexpr uint64_t kDefaultSlotBytes = 512ull << 20;
 constexpr uint32_t kDefaultSlots = 2;
-// A handful of workgroups saturate the host link; more only deepen the queue of host-bound stores
+// A handful of workgroups saturate the host link; more only deepen the queue of host-bound requests
 // that other kernels' memory traffic has to wait behind.
-constexpr uint32_t kDefaultDirectGrid = 6;
+constexpr uint32_t kDefaultDirectGatherGrid = 6;
+constexpr uint32_t kDefaultDirectScatterGrid = 8;
 
 struct Slot {
     char *buf = nullptr;
@@ -376,7 +377,7 @@ int offload_locked(tc_ctx *c, const tc_xfer_desc *descs, uint32_t n_descs, hipSt
     if (c->opts.direct_offload == 2)
         for (const Op &o : c->ops) direct = direct || o.is_upload;
     auto enqueue_direct = [&]() -> int {
-        const uint32_t grid = c->opts.direct_grid ? c->opts.direct_grid : kDefaultDirectGrid;
+        const uint32_t grid = c->opts.direct_grid ? c->opts.direct_grid : kDefaultDirectGatherGrid;
         std::vector<void *> dev_view(plan.segs.size());
         for (size_t k = 0; k < plan.segs.size(); ++k)  // the address the GPU sees the pinned buffer at
             if (hipHostGetDevicePointer(&dev_view[k], plan.segs[k].host, 0) != hipSuccess) {
@@ -435,6 +436,27 @@ int upload_locked(tc_ctx *c, const tc_xfer_desc *descs, uint32_t n_descs, hipStr
     uint64_t ring_start = 0;
     if (int rc = begin_op(c, plan, stream, &op, &ring_start)) return rc;
 
+    // Direct path: the scatter kernel reads each agent's records straight from its pinned host buffer.
+    auto enqueue_direct = [&]() -> int {
+        const uint32_t grid = c->opts.direct_grid ? c->opts.direct_grid : kDefaultDirectScatterGrid;
+        std::vector<void *> dev_view(plan.segs.size());
+        for (size_t k = 0; k < plan.segs.size(); ++k)
+            if (hipHostGetDevicePointer(&dev_view[k], plan.segs[k].host, 0) != hipSuccess) {
+                (void)hipGetLastError();
+                return TC_ERR_NOT_PINNED;
+            }
+        for (size_t k = 0; k < plan.segs.size(); ++k) {
+            const Segment &s = plan.segs[k];
+            if (int rc = time_begin(c, &op, stream, uint64_t(s.n) * c->rec, kDirect)) return rc;
+            HIP_TRY(tc::launch_scatter_pages(dev_view[k], c->pool.kv_base, static_cast<uint32_t *>(c->pool.scales),
+                                             c->ids_dev + ring_start + s.first, s.n, c->geom, grid, stream));
+            if (int rc = time_end(c, &op, stream)) return rc;
+        }
+        for (const Segment &s : plan.segs)
+            if (s.table) HIP_TRY(tc::launch_rewrite_table(s.table, c->ids_dev + ring_start + s.first, s.n, stream));
+        HIP_TRY(hipEventRecord(op.done, stream));
+        return TC_OK;
+    };
     auto enqueue = [&]() -> int {
         uint64_t c0 = 0;
         for (uint32_t nblk : plan_chunks(plan.total, c->slot_blocks, true)) {
@@ -458,7 +480,7 @@ int upload_locked(tc_ctx *c, const tc_xfer_desc *descs, uint32_t n_descs, hipStr
         HIP_TRY(hipEventRecord(op.done, stream));
         return TC_OK;
     };
-    if (int rc = enqueue()) return abort_op(c, &op, rc);
+    if (int rc = c->opts.direct_upload ? enqueue_direct() : enqueue()) return abort_op(c, &op, rc);
     op.is_upload = true;
 
     c->st.n_uploads++;
@@ -501,7 +523,7 @@ int tc_create(const tc_pool_desc *pool, const tc_opts *opts, tc_ctx **out)
     if (S != 0 && S != 1 && S != P) return TC_ERR_INVAL;
     if ((S != 0) != (pool->scales != nullptr)) return TC_ERR_INVAL;
     if (S && (reinterpret_cast<uintptr_t>(pool->scales) % 4)) return TC_ERR_INVAL;
-    if (opts && opts->direct_offload > 2) return TC_ERR_INVAL;
+    if (opts && (opts->direct_offload > 2 || opts->direct_upload > 1)) return TC_ERR_INVAL;
     if (!is_device_ptr(pool->kv_base) || (S && !is_device_ptr(pool->scales))) return TC_ERR_NOT_PINNED;
 
     tc_ctx *c = new (std::nothrow) tc_ctx;

@@ -41,7 +41,7 @@ def test_error_strings_and_struct_layout():
     assert "unknown" in K.tc_strerror(-99)
     # the ctypes mirrors must match the C layout (checked against sizes the compiler would give)
     assert ctypes.sizeof(K.tc_pool_desc) == 40
-    assert ctypes.sizeof(K.tc_opts) == 32
+    assert ctypes.sizeof(K.tc_opts) == 40
     assert ctypes.sizeof(K.tc_xfer_desc) == 32
     assert ctypes.sizeof(K.tc_stats_t) == 24 + 16 + 48 + 32 + 16 + 24 + 48
 

@@ -103,13 +103,15 @@ def test_odd_shapes_and_scales(shape, n):
     _round_trip_case(shape, 4, n, salt=n)
 
 
-@pytest.mark.parametrize("mode,grid", [(1, 0), (1, 3), (2, 0)])
-def test_direct_offload_writes_the_same_records(mode, grid):
-    # the gather kernel stores straight into the pinned host buffer (no staging, no DMA)
-    shape = W.CONFIGS[1].with_blocks(96)
-    _round_trip_case(shape, 1, 37, salt=40 + mode + grid, direct_offload=mode, direct_grid=grid)
-    _round_trip_case(W.PoolShape("fp8-small", 3, 2, 32, 8, 1, 80, 6, "fp8"), 4, 11, salt=41, direct_offload=mode, direct_grid=grid)
-    _round_trip_case(W.PoolShape("odd-ragged", 2, 5, 128, 16, 1, 40, 1, "fp8"), 4, 9, salt=42, direct_offload=mode, direct_grid=grid)
+@pytest.mark.parametrize("off,up,grid", [(1, 0, 0), (1, 1, 3), (0, 1, 0), (2, 1, 0)])
+def test_direct_paths_move_the_same_bytes(off, up, grid):
+    # the gather kernel stores straight into the pinned host buffer / the scatter kernel reads straight
+    # from it (no staging, no DMA)
+    opts = dict(direct_offload=off, direct_upload=up, direct_grid=grid)
+    _round_trip_case(W.CONFIGS[1].with_blocks(96), 1, 37, salt=40 + off + 3 * up + grid, **opts)
+    _round_trip_case(W.PoolShape("fp8-small", 3, 2, 32, 8, 1, 80, 6, "fp8"), 4, 11, salt=41, **opts)
+    _round_trip_case(W.PoolShape("odd-ragged", 2, 5, 128, 16, 1, 40, 1, "fp8"), 4, 9, salt=42, **opts)
+    _round_trip_case(W.CONFIGS[0], 0, 8, salt=43, **opts)
 
 
 def test_zero_blocks_is_a_no_op():
