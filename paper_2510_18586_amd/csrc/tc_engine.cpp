@@ -449,7 +449,7 @@ int upload_locked(tc_ctx *c, const tc_xfer_desc *descs, uint32_t n_descs, hipStr
             const Segment &s = plan.segs[k];
             if (int rc = time_begin(c, &op, stream, uint64_t(s.n) * c->rec, kDirect)) return rc;
             HIP_TRY(tc::launch_scatter_pages(dev_view[k], c->pool.kv_base, static_cast<uint32_t *>(c->pool.scales),
-                                             c->ids_dev + ring_start + s.first, s.n, c->geom, grid, stream));
+                                             c->ids_dev + ring_start + s.first, s.n, c->geom, grid, true, stream));
             if (int rc = time_end(c, &op, stream)) return rc;
         }
         for (const Segment &s : plan.segs)
@@ -468,7 +468,7 @@ int upload_locked(tc_ctx *c, const tc_xfer_desc *descs, uint32_t n_descs, hipStr
             if (int rc = time_end(c, &op, stream)) return rc;
             if (int rc = time_begin(c, &op, stream, uint64_t(nblk) * c->rec, kScatter)) return rc;
             HIP_TRY(tc::launch_scatter_pages(slot->buf, c->pool.kv_base, static_cast<uint32_t *>(c->pool.scales),
-                                             c->ids_dev + ring_start + c0, nblk, c->geom, c->opts.max_grid, stream));
+                                             c->ids_dev + ring_start + c0, nblk, c->geom, c->opts.max_grid, false, stream));
             if (int rc = time_end(c, &op, stream)) return rc;
             HIP_TRY(hipEventRecord(slot->last, stream));
             slot->used = true;

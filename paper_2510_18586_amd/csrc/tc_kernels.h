@@ -17,13 +17,12 @@ struct PageGeom {
 };
 
 // staging[k] <- record of block ids[k] for k < n (pages, scale words, zero pad).  `staging` is a
-// device staging chunk, or (streaming_stores = true) pinned host memory written over the host link.
+// device staging chunk, or (direct = true) the GPU's view of pinned host memory.
 hipError_t launch_gather_pages(const void *pool, const uint32_t *scales, void *staging, const int32_t *ids_dev,
-                               uint32_t n, const PageGeom &g, uint32_t max_grid, bool streaming_stores,
-                               hipStream_t stream);
-// block ids[k] <- record k of staging.
+                               uint32_t n, const PageGeom &g, uint32_t max_grid, bool direct, hipStream_t stream);
+// block ids[k] <- record k of staging (same meaning of `direct`).
 hipError_t launch_scatter_pages(const void *staging, void *pool, uint32_t *scales, const int32_t *ids_dev,
-                                uint32_t n, const PageGeom &g, uint32_t max_grid, hipStream_t stream);
+                                uint32_t n, const PageGeom &g, uint32_t max_grid, bool direct, hipStream_t stream);
 // table[i] = ids[i], i < n.
 hipError_t launch_rewrite_table(int32_t *table, const int32_t *ids_dev, uint32_t n, hipStream_t stream);
 

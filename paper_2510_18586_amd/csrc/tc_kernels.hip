@@ -37,7 +37,9 @@ __device__ __forceinline__ void st16(u32x4 *p, u32x4 v)
 // One work item = (block k of the chunk, plane p, tile t of the page).  Items are ordered with
 // the tile fastest, then the plane: consecutive workgroups write (gather) or read (scatter)
 // consecutive staging addresses.
-template <int U, bool NTL, bool NTS, bool GATHER>
+// DIRECT marks the launches whose "staging" side is pinned host memory: the same code, but a
+// distinct kernel for the profiler, because those launches are bound by the host link, not by HBM.
+template <int U, bool NTL, bool NTS, bool GATHER, bool DIRECT>
 __global__ __launch_bounds__(kThreads) void page_copy_kernel(
     u32x4 *__restrict__ pool, uint32_t *__restrict__ scales, u32x4 *__restrict__ staging,
     const int32_t *__restrict__ ids, uint32_t n_items, uint32_t tiles, PageGeom g)
@@ -131,7 +133,7 @@ __global__ __launch_bounds__(kThreads) void hbm_stream_kernel(f32x4 *__restrict_
 // ---------------------------------------------------------------------------------------------
 template <bool GATHER>
 static hipError_t launch_page_copy(void *pool, uint32_t *scales, void *staging, const int32_t *ids_dev, uint32_t n,
-                                   const PageGeom &g, uint32_t max_grid, bool streaming_stores, hipStream_t stream)
+                                   const PageGeom &g, uint32_t max_grid, bool direct, hipStream_t stream)
 {
     if (n == 0) return hipSuccess;
     // widest tile that a page still fills
@@ -151,36 +153,36 @@ static hipError_t launch_page_copy(void *pool, uint32_t *scales, void *staging, 
     uint32_t grid = n_items;
     if (max_grid && grid > max_grid) grid = max_grid;
 
-#define TC_LAUNCH(UU, NL, NS)                                                                                \
-    hipLaunchKernelGGL((page_copy_kernel<UU, NL, NS, GATHER>), dim3(grid), dim3(kThreads), 0, stream,        \
+#define TC_LAUNCH(UU, NL, NS, DR)                                                                              \
+    hipLaunchKernelGGL((page_copy_kernel<UU, NL, NS, GATHER, DR>), dim3(grid), dim3(kThreads), 0, stream,        \
                        static_cast<u32x4 *>(pool), scales, static_cast<u32x4 *>(staging), ids_dev, n_items, \
                        tiles, g)
-#define TC_LAUNCH_U(NL, NS)                  \
-    switch (U) {                             \
-    case 8: TC_LAUNCH(8, NL, NS); break;     \
-    case 4: TC_LAUNCH(4, NL, NS); break;     \
-    case 2: TC_LAUNCH(2, NL, NS); break;     \
-    default: TC_LAUNCH(1, NL, NS); break;    \
+#define TC_LAUNCH_U(NL, NS, DR)                  \
+    switch (U) {                                 \
+    case 8: TC_LAUNCH(8, NL, NS, DR); break;     \
+    case 4: TC_LAUNCH(4, NL, NS, DR); break;     \
+    case 2: TC_LAUNCH(2, NL, NS, DR); break;     \
+    default: TC_LAUNCH(1, NL, NS, DR); break;    \
     }
-    if (GATHER && !streaming_stores) { TC_LAUNCH_U(true, false) }
-    else { TC_LAUNCH_U(true, true) }
+    if (direct) { TC_LAUNCH_U(true, true, true) }
+    else if (GATHER) { TC_LAUNCH_U(true, false, false) }
+    else { TC_LAUNCH_U(true, true, false) }
 #undef TC_LAUNCH_U
 #undef TC_LAUNCH
     return hipGetLastError();
 }
 
 hipError_t launch_gather_pages(const void *pool, const uint32_t *scales, void *staging, const int32_t *ids_dev,
-                               uint32_t n, const PageGeom &g, uint32_t max_grid, bool streaming_stores,
-                               hipStream_t stream)
+                               uint32_t n, const PageGeom &g, uint32_t max_grid, bool direct, hipStream_t stream)
 {
     return launch_page_copy<true>(const_cast<void *>(pool), const_cast<uint32_t *>(scales), staging, ids_dev, n, g,
-                                  max_grid, streaming_stores, stream);
+                                  max_grid, direct, stream);
 }
 
 hipError_t launch_scatter_pages(const void *staging, void *pool, uint32_t *scales, const int32_t *ids_dev,
-                                uint32_t n, const PageGeom &g, uint32_t max_grid, hipStream_t stream)
+                                uint32_t n, const PageGeom &g, uint32_t max_grid, bool direct, hipStream_t stream)
 {
-    return launch_page_copy<false>(pool, scales, const_cast<void *>(staging), ids_dev, n, g, max_grid, true, stream);
+    return launch_page_copy<false>(pool, scales, const_cast<void *>(staging), ids_dev, n, g, max_grid, direct, stream);
 }
 
 hipError_t launch_rewrite_table(int32_t *table, const int32_t *ids_dev, uint32_t n, hipStream_t stream)

@@ -133,22 +133,24 @@ def m_naive(torch, K, W, emit):
 
 def m_config1(torch, K, W, emit):
     shape = W.CONFIGS[0]
-    c = Ctx(torch, K, W, shape, 0, 16)
-    rng = W.rng_for(0)
-    ids = W.pick_ids(rng, shape.num_blocks, 8)
-    new = W.pick_ids(rng, shape.num_blocks, 8, exclude=ids)
-    rc, host = K.tc_host_alloc(c.ctx, 8)
-    K.check(rc)
-    K.check(K.tc_alloc_at(c.ctx, ids))
-    K.check(K.tc_alloc_at(c.ctx, new))
-    stream = torch.cuda.Stream()
-    table = torch.zeros(8, dtype=torch.int32, device="cuda:0")
-    t_off = _sync_time(torch, lambda: K.check(K.tc_offload(c.ctx, ids, host, stream)), reps=50, warm=5)
-    t_up = _sync_time(torch, lambda: K.check(K.tc_upload(c.ctx, host, new, table, stream)), reps=50, warm=5)
-    emit(dict(measurement="config1", payload_KiB=8 * c.rec / 1024, offload_us=t_off * 1e6, upload_us=t_up * 1e6,
-              offload_GBps=8 * c.rec / t_off / 1e9, upload_GBps=8 * c.rec / t_up / 1e9,
-              note="latency-bound: 256 KiB per direction"))
-    c.close()
+    out = dict(measurement="config1", note="latency-bound: 256 KiB per direction")
+    for tag, opts in (("", {}), ("direct_", dict(direct_offload=1, direct_upload=1))):
+        c = Ctx(torch, K, W, shape, 0, 16, **opts)
+        rng = W.rng_for(0)
+        ids = W.pick_ids(rng, shape.num_blocks, 8)
+        new = W.pick_ids(rng, shape.num_blocks, 8, exclude=ids)
+        rc, host = K.tc_host_alloc(c.ctx, 8)
+        K.check(rc)
+        K.check(K.tc_alloc_at(c.ctx, ids))
+        K.check(K.tc_alloc_at(c.ctx, new))
+        stream = torch.cuda.Stream()
+        table = torch.zeros(8, dtype=torch.int32, device="cuda:0")
+        t_off = _sync_time(torch, lambda: K.check(K.tc_offload(c.ctx, ids, host, stream)), reps=50, warm=5)
+        t_up = _sync_time(torch, lambda: K.check(K.tc_upload(c.ctx, host, new, table, stream)), reps=50, warm=5)
+        out.update({"payload_KiB": 8 * c.rec / 1024, tag + "offload_us": t_off * 1e6, tag + "upload_us": t_up * 1e6,
+                    tag + "offload_GBps": 8 * c.rec / t_off / 1e9, tag + "upload_GBps": 8 * c.rec / t_up / 1e9})
+        c.close()
+    emit(out)
 
 
 def m_config3(torch, K, W, emit):
