@@ -27,7 +27,9 @@
  *   - tc_offload / tc_upload are asynchronous: they return after enqueueing on
  *     `stream` (a hipStream_t passed as void*; NULL = the default stream).  Work
  *     later enqueued on the same stream is ordered after them; the host buffer /
- *     the pool may be read once the stream (or tc_sync) has completed.
+ *     the pool may be read once the stream (or tc_sync) has completed.  Transfers
+ *     of one context that touch the same blocks or the same arena allocation are
+ *     ordered among themselves even when they are put on different streams.
  *   - the caller owns the pool, the scales, block tables and any host buffer not
  *     obtained from tc_host_alloc.  The context owns its staging ring and arena.
  *   - one context serves one GPU (the device current at tc_create); calls on one

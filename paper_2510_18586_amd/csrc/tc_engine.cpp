@@ -17,6 +17,7 @@
 #include <deque>
 #include <mutex>
 #include <new>
+#include <unordered_map>
 #include <vector>
 
 #include <hip/hip_runtime_api.h>
@@ -50,6 +51,8 @@ struct Timed {
 
 struct Op {
     hipEvent_t done = nullptr;
+    uint64_t ticket = 0;           // consecutive in issue order
+    hipStream_t stream = nullptr;  // where it was enqueued
     bool is_upload = false;
     std::vector<int32_t> ids;
     std::vector<uint64_t> arena_starts;
@@ -89,6 +92,11 @@ struct tc_ctx {
     uint64_t ring_cap = 0, ring_tail = 0, ring_used = 0;
 
     std::deque<Op> ops;
+    uint64_t next_ticket = 1;
+    // Hazards between transfers that callers put on different streams: the last transfer that
+    // touched a block / an arena allocation; a later one on another stream waits for its event.
+    std::vector<uint64_t> block_ticket;
+    std::unordered_map<uint64_t, uint64_t> arena_ticket;
     std::vector<hipEvent_t> sync_events, time_events;  // recycled
     bool profiling = false;
     tc_stats_t st{};
@@ -153,7 +161,11 @@ int retire_front(tc_ctx *c)
 {
     Op &op = c->ops.front();
     c->blocks->end_transfer(op.ids.data(), uint32_t(op.ids.size()));
-    for (uint64_t s : op.arena_starts) c->arena->end_transfer(s);
+    for (uint64_t s : op.arena_starts) {
+        c->arena->end_transfer(s);
+        auto it = c->arena_ticket.find(s);
+        if (it != c->arena_ticket.end() && it->second == op.ticket) c->arena_ticket.erase(it);
+    }
     c->ring_used -= op.ring_consumed;
     for (Timed &t : op.timed) {
         float ms = 0.f;
@@ -283,8 +295,48 @@ int validate(tc_ctx *c, const tc_xfer_desc *descs, uint32_t n_descs, Plan *plan)
 }
 
 // Common start of a transfer: ids into the rings, blocks and arena runs marked in flight.
+// Orders this transfer after unretired transfers on OTHER streams that touched the same blocks or
+// the same arena allocations (same-stream order is implicit).
+int wait_for_hazards(tc_ctx *c, const Plan &plan, hipStream_t stream)
+{
+    if (c->ops.empty()) return TC_OK;
+    const uint64_t front = c->ops.front().ticket;
+    std::vector<uint64_t> waits;
+    auto consider = [&](uint64_t t) {
+        if (t < front) return;  // retired (or never set)
+        const Op &o = c->ops[size_t(t - front)];
+        if (o.stream == stream) return;
+        for (uint64_t w : waits)
+            if (w == t) return;
+        waits.push_back(t);
+    };
+    for (int32_t id : plan.ids) consider(c->block_ticket[size_t(id)]);
+    for (const Segment &s : plan.segs) {
+        if (c->arena_base && s.host >= c->arena_base && s.host < c->arena_base + c->arena_bytes) {
+            uint64_t start, room;
+            if (c->arena->locate(uint64_t(s.host - c->arena_base) / c->rec, &start, &room)) {
+                auto it = c->arena_ticket.find(start);
+                if (it != c->arena_ticket.end()) consider(it->second);
+            }
+        }
+    }
+    for (uint64_t t : waits) HIP_TRY(hipStreamWaitEvent(stream, c->ops[size_t(t - front)].done, 0));
+    return TC_OK;
+}
+
+// The transfer is enqueued: remember it as the last one on its blocks and arena allocations.
+void publish_op(tc_ctx *c, Op &&op, hipStream_t stream)
+{
+    op.ticket = c->next_ticket++;
+    op.stream = stream;
+    for (int32_t id : op.ids) c->block_ticket[size_t(id)] = op.ticket;
+    for (uint64_t s : op.arena_starts) c->arena_ticket[s] = op.ticket;
+    c->ops.push_back(std::move(op));
+}
+
 int begin_op(tc_ctx *c, Plan &plan, hipStream_t stream, Op *op, uint64_t *ring_start)
 {
+    if (int rc = wait_for_hazards(c, plan, stream)) return rc;
     if (int rc = get_event(c, false, &op->done)) return rc;
     if (int rc = ring_alloc(c, plan.total, ring_start, &op->ring_consumed, &op->ring_prev_tail)) {
         put_event(c, false, op->done);
@@ -419,7 +471,7 @@ int offload_locked(tc_ctx *c, const tc_xfer_desc *descs, uint32_t n_descs, hipSt
     c->st.n_offloads++;
     c->st.blocks_offloaded += plan.total;
     c->st.bytes_offloaded += plan.total * c->rec;
-    c->ops.push_back(std::move(op));
+    publish_op(c, std::move(op), stream);
     return TC_OK;
 }
 
@@ -486,7 +538,7 @@ int upload_locked(tc_ctx *c, const tc_xfer_desc *descs, uint32_t n_descs, hipStr
     c->st.n_uploads++;
     c->st.blocks_uploaded += plan.total;
     c->st.bytes_uploaded += plan.total * c->rec;
-    c->ops.push_back(std::move(op));
+    publish_op(c, std::move(op), stream);
     return TC_OK;
 }
 
@@ -553,6 +605,7 @@ int tc_create(const tc_pool_desc *pool, const tc_opts *opts, tc_ctx **out)
     c->arena = new (std::nothrow) tc::HostArena(arena_slots);
     c->arena_bytes = arena_slots * c->rec;
     c->ring_cap = std::max<uint64_t>(4ull * pool->num_blocks, 1024);
+    c->block_ticket.assign(pool->num_blocks, 0);
 
     auto fail = [&](int code) {
         destroy_unlocked(c);

@@ -436,3 +436,46 @@ def test_auto_mode_goes_direct_only_while_an_upload_is_in_flight():
         if mirror:
             mirror.close()
         gp.close()
+
+
+def test_transfers_on_different_streams_respect_block_and_buffer_hazards():
+    """An upload into blocks that an offload on another stream is still reading, and an upload from an
+    arena buffer that an offload on another stream is still writing, must each wait for that offload."""
+    shape = W.CONFIGS[1].with_blocks(600)
+    L, NB, pb = shape.num_layers, shape.num_blocks, shape.page_bytes
+    rng = W.rng_for(1, salt=35)
+    gp = GpuPool(shape, seed=35, host_arena_bytes=520 * 2 * 1024 * 1024)
+    mirror = None
+    try:
+        from harness import SparseMirror, host_view
+        rec = gp.rec
+        n = 256                                            # 512 MiB: each transfer takes ~10 ms
+        perm = W.pick_ids(rng, NB, 2 * n)
+        a, b = perm[:n], perm[n:]
+        K.check(K.tc_alloc_at(gp.ctx, perm))
+        mirror = SparseMirror(gp, perm)
+        rc, buf_a = K.tc_host_alloc(gp.ctx, n)
+        rc, buf_b = K.tc_host_alloc(gp.ctx, n)
+        s1, s2, s3 = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+        want_a = np.empty(n * rec, dtype=np.uint8)
+        want_b = np.empty(n * rec, dtype=np.uint8)
+        oracle.offload(mirror.pool, None, L, NB, pb, 0, a, want_a)
+        oracle.offload(mirror.pool, None, L, NB, pb, 0, b, want_b)
+        K.check(K.tc_offload(gp.ctx, b, buf_b, s1))
+        K.check(K.tc_sync(gp.ctx))
+        for _ in range(3):
+            K.check(K.tc_offload(gp.ctx, a, buf_a, s1))        # reads blocks a, writes buf_a (s1)
+            K.check(K.tc_upload(gp.ctx, buf_b, a, None, s2))   # overwrites blocks a with b's bytes (s2): must wait
+            K.check(K.tc_upload(gp.ctx, buf_a, b, None, s3))   # reads buf_a (s3): must wait for the offload too
+            K.check(K.tc_sync(gp.ctx))
+            assert np.array_equal(host_view(buf_a, n * rec), want_a), "the upload overtook the offload's reads"
+            assert np.array_equal(gp.blocks_to_host(b), mirror.blocks(a)), "the upload read buf_a before it was written"
+            assert np.array_equal(gp.blocks_to_host(a), mirror.blocks(b))
+            # put the pool back the way the mirror has it
+            K.check(K.tc_upload(gp.ctx, buf_a, a, None, s1))
+            K.check(K.tc_upload(gp.ctx, buf_b, b, None, s1))
+            K.check(K.tc_sync(gp.ctx))
+    finally:
+        if mirror:
+            mirror.close()
+        gp.close()
