@@ -11,6 +11,8 @@ import paper_2510_18586_amd as K
 import tc_workloads as W
 
 DEV = "cuda:0"
+GUARD_BYTES = 1 << 16          # keeps the pool 256-B aligned
+GUARD_VALUE = 0xC3
 
 
 class GpuPool:
@@ -20,8 +22,13 @@ class GpuPool:
         self.shape = shape
         self.L, self.NB, self.pb = shape.num_layers, shape.num_blocks, shape.page_bytes
         self.P, self.S = shape.planes, shape.scales_per_block
+        self._guarded = None
         if pool_host is not None:
-            self.pool = torch.from_numpy(pool_host).to(DEV)
+            # guard bytes in front of and behind the pool: a kernel that writes outside it is caught at close()
+            g = GUARD_BYTES
+            self._guarded = torch.full((g + pool_host.size + g,), GUARD_VALUE, dtype=torch.uint8, device=DEV)
+            self.pool = self._guarded[g:g + pool_host.size]
+            self.pool.copy_(torch.from_numpy(pool_host))
             self.scales = torch.from_numpy(scales_host.view(np.int32)).to(DEV) if self.S else None
         else:
             self.pool = W.make_pool_device(shape, seed, DEV)
@@ -36,6 +43,11 @@ class GpuPool:
         if self.ctx:
             K.check(K.tc_destroy(self.ctx))
             self.ctx = None
+        if self._guarded is not None:
+            g, n = GUARD_BYTES, self._guarded.numel()
+            ok = bool((self._guarded[:g] == GUARD_VALUE).all()) and bool((self._guarded[n - g:] == GUARD_VALUE).all())
+            self._guarded = None
+            assert ok, "bytes outside the pool were written"
         self.pool = self.scales = None
         torch.cuda.empty_cache()
 
