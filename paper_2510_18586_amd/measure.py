@@ -1,6 +1,6 @@
 """Measurements beyond the headline benchmark line, for all five configurations.
 
-    python -m paper_2510_18586_amd.measure [--only sweep,naive,config1,config3,config4,config5] [--out FILE]
+    python -m paper_2510_18586_amd.measure [--only sweep,naive,config1,config3,config4,config4_replay,config5] [--out FILE]
 
 Prints one JSON object per measurement (and writes them to --out).  Needs a GPU.  Times are
 wall-clock around enqueue + synchronisation unless stated; GB = 1e9 bytes.
@@ -13,6 +13,8 @@ wall-clock around enqueue + synchronisation unless stated; GB = 1e9 bytes.
   config3  64 agents offloaded / uploaded as a batch, alone and while an HBM-streaming kernel
            runs on another stream; the neighbour's own bandwidth alone and overlapped
   config4  32B shape (4 MiB per block): per-agent transfer rates over the trace's agent sizes
+  config4_replay  the 200-agent trace in real time (about 27 s): share of uploads that are complete when
+           the tool returns, stall otherwise, per-transfer rates
   config5  70B fp8 shape with scales: one wave of private blocks as a batch
 """
 import argparse
@@ -318,6 +320,93 @@ def m_config4(torch, K, W, emit):
     c.close()
 
 
+def m_config4_replay(torch, K, W, emit, speed=1.0):
+    """Real-time replay of the config-4 trace: every call offloads (if the 16 GiB arena has room), the
+    upload is issued 200 ms before the predicted finish (constant 2 s prediction) or at the finish when
+    the tool returns early.  Reports how often the KV is back when the tool returns, the stall when it
+    is not, and the per-transfer rates."""
+    shape = W.CONFIGS[3]
+    agents, events = W.dag_trace(W.rng_for(3), block_size=shape.block_size)
+    c = Ctx(torch, K, W, shape, 3, 4096, fill=False)
+    stream = torch.cuda.Stream()
+    tables = torch.full((len(agents), 1025), -1, dtype=torch.int32, device="cuda:0")
+    A = [dict(state="new") for _ in agents]
+    ops = []            # (kind, agent, bytes, e0, e1)
+    stalls, ready, rejected = [], 0, 0
+
+    def timed(kind, i, nbytes, fn):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        fn()
+        e1.record(stream)
+        ops.append((kind, i, nbytes, e0, e1))
+        return e1
+
+    def upload(i):
+        a, n = A[i], agents[i]["blocks"]
+        rc, new = K.tc_alloc(c.ctx, n)
+        if rc != 0:
+            return False
+        a["up_done"] = timed("upload", i, n * c.rec, lambda: K.check(K.tc_upload(c.ctx, a["buf"], new, tables[i], stream)))
+        K.check(K.tc_host_free(c.ctx, a["buf"]))
+        a.update(state="uploaded", ids=new)
+        return True
+
+    t_wall0 = time.perf_counter()
+    for t, _, kind, i in events:
+        delay = t / speed - (time.perf_counter() - t_wall0)
+        if delay > 0:
+            time.sleep(delay)
+        a, n = A[i], agents[i]["blocks"]
+        K.check(K.tc_poll(c.ctx))
+        if kind == "start":
+            rc, ids = K.tc_alloc(c.ctx, n)
+            K.check(rc)
+            a.update(state="running", ids=ids)
+        elif kind == "call_start":
+            rc, buf = K.tc_host_alloc(c.ctx, n)
+            if rc != 0:
+                rejected += 1
+                a["state"] = "kept"
+                continue
+            a["buf"] = buf
+            timed("offload", i, n * c.rec, lambda: K.check(K.tc_offload(c.ctx, a["ids"], buf, stream)))
+            K.check(K.tc_free(c.ctx, a["ids"]))
+            a["state"] = "offloaded"
+        elif kind == "upload_due":
+            if a["state"] == "offloaded":
+                upload(i)
+        elif kind == "call_finish":
+            if a["state"] == "offloaded":
+                while not upload(i):            # blocks are still pending-free: wait for the copy stream
+                    K.check(K.tc_sync(c.ctx))
+            if a["state"] == "uploaded":
+                t0 = time.perf_counter()
+                if a["up_done"].query():
+                    ready += 1
+                    stalls.append(0.0)
+                else:
+                    a["up_done"].synchronize()
+                    stalls.append((time.perf_counter() - t0) * 1e3)
+                a["state"] = "running"
+        elif kind == "finish":
+            K.check(K.tc_free(c.ctx, a["ids"]))
+    torch.cuda.synchronize()
+    K.check(K.tc_sync(c.ctx))
+    rates = {k: np.array([nb / (e0.elapsed_time(e1) * 1e-3) / 1e9 for kk, _, nb, e0, e1 in ops if kk == k]) for k in ("offload", "upload")}
+    ms1k = np.array([e0.elapsed_time(e1) / (nb / c.rec * shape.block_size / 1024) for kk, _, nb, e0, e1 in ops if kk == "upload"])
+    stalls = np.array(stalls)
+    q = lambda x: [float(np.percentile(x, p)) for p in (5, 50, 95)]
+    emit(dict(measurement="config4_replay", agents=len(agents), speed=speed, wall_s=time.perf_counter() - t_wall0,
+              offloads=len(rates["offload"]), rejected_cpu_capacity=rejected,
+              uploads_complete_before_call_finish=ready, uploads=len(stalls),
+              fraction_ready=ready / max(1, len(stalls)),
+              stall_ms_when_not_ready_p50_p95_max=[float(np.percentile(stalls[stalls > 0], p)) for p in (50, 95, 100)] if (stalls > 0).any() else [0, 0, 0],
+              offload_GBps_p5_p50_p95=q(rates["offload"]), upload_GBps_p5_p50_p95=q(rates["upload"]),
+              upload_ms_per_1k_tokens_p5_p50_p95=q(ms1k)))
+    c.close()
+
+
 def m_config5(torch, K, W, emit):
     shape = W.CONFIGS[4]
     rng = W.rng_for(4, salt=53)
@@ -354,7 +443,8 @@ def m_config5(torch, K, W, emit):
     c.close()
 
 
-ALL = dict(sweep=m_sweep, naive=m_naive, config1=m_config1, config3=m_config3, config4=m_config4, config5=m_config5)
+ALL = dict(sweep=m_sweep, naive=m_naive, config1=m_config1, config3=m_config3, config4=m_config4,
+           config4_replay=m_config4_replay, config5=m_config5)
 
 
 def main():
