@@ -1,6 +1,6 @@
 """Measurements beyond the headline benchmark line, for all five configurations.
 
-    python -m paper_2510_18586_amd.measure [--only sweep,naive,config1,config3,config4,config4_replay,config5] [--out FILE]
+    python -m paper_2510_18586_amd.measure [--only sweep,naive,config1,config3,config4,config4_replay,forecast_noise,config5] [--out FILE]
 
 Prints one JSON object per measurement (and writes them to --out).  Needs a GPU.  Times are
 wall-clock around enqueue + synchronisation unless stated; GB = 1e9 bytes.
@@ -15,6 +15,7 @@ wall-clock around enqueue + synchronisation unless stated; GB = 1e9 bytes.
   config4  32B shape (4 MiB per block): per-agent transfer rates over the trace's agent sizes
   config4_replay  the 200-agent trace in real time (about 27 s): share of uploads that are complete when
            the tool returns, stall otherwise, per-transfer rates
+  forecast_noise  that replay with the forecaster of Eq. 1 and noisy user estimates (sigma 0, 0.25, 0.5)
   config5  70B fp8 shape with scales: one wave of private blocks as a batch
 """
 import argparse
@@ -320,19 +321,19 @@ def m_config4(torch, K, W, emit):
     c.close()
 
 
-def m_config4_replay(torch, K, W, emit, speed=1.0):
-    """Real-time replay of the config-4 trace: every call offloads (if the 16 GiB arena has room), the
-    upload is issued 200 ms before the predicted finish (constant 2 s prediction) or at the finish when
-    the tool returns early.  Reports how often the KV is back when the tool returns, the stall when it
-    is not, and the per-transfer rates."""
-    shape = W.CONFIGS[3]
-    agents, events = W.dag_trace(W.rng_for(3), block_size=shape.block_size)
-    c = Ctx(torch, K, W, shape, 3, 4096, fill=False)
+def _replay(torch, K, W, ctx_obj, agents, events, speed, predict_ms=None, observe=None, lead_ms=200.0):
+    """Real-time replay of a trace on one copy stream.  predict_ms(i) -> predicted call duration at
+    call_start (None = the trace's own upload times); observe(i, elapsed_ms) at call_finish."""
+    import heapq
+    c, shape = ctx_obj, ctx_obj.shape
     stream = torch.cuda.Stream()
     tables = torch.full((len(agents), 1025), -1, dtype=torch.int32, device="cuda:0")
     A = [dict(state="new") for _ in agents]
-    ops = []            # (kind, agent, bytes, e0, e1)
-    stalls, ready, rejected = [], 0, 0
+    ops, stalls, ready, rejected = [], [], 0, 0
+    heap = [(t * 1e3, k, kind, i) for k, (t, _, kind, i) in enumerate(events)
+            if not (predict_ms and kind == "upload_due")]
+    heapq.heapify(heap)
+    seq = 10 * len(events)
 
     def timed(kind, i, nbytes, fn):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -353,8 +354,9 @@ def m_config4_replay(torch, K, W, emit, speed=1.0):
         return True
 
     t_wall0 = time.perf_counter()
-    for t, _, kind, i in events:
-        delay = t / speed - (time.perf_counter() - t_wall0)
+    while heap:
+        t, _, kind, i = heapq.heappop(heap)
+        delay = t * 1e-3 / speed - (time.perf_counter() - t_wall0)
         if delay > 0:
             time.sleep(delay)
         a, n = A[i], agents[i]["blocks"]
@@ -364,6 +366,10 @@ def m_config4_replay(torch, K, W, emit, speed=1.0):
             K.check(rc)
             a.update(state="running", ids=ids)
         elif kind == "call_start":
+            a["t_call"] = t
+            if predict_ms:
+                seq += 1
+                heapq.heappush(heap, (t + max(0.0, predict_ms(i) - lead_ms), seq, "upload_due", i))
             rc, buf = K.tc_host_alloc(c.ctx, n)
             if rc != 0:
                 rejected += 1
@@ -377,6 +383,8 @@ def m_config4_replay(torch, K, W, emit, speed=1.0):
             if a["state"] == "offloaded":
                 upload(i)
         elif kind == "call_finish":
+            if observe:
+                observe(i, t - a["t_call"])
             if a["state"] == "offloaded":
                 while not upload(i):            # blocks are still pending-free: wait for the copy stream
                     K.check(K.tc_sync(c.ctx))
@@ -397,13 +405,47 @@ def m_config4_replay(torch, K, W, emit, speed=1.0):
     ms1k = np.array([e0.elapsed_time(e1) / (nb / c.rec * shape.block_size / 1024) for kk, _, nb, e0, e1 in ops if kk == "upload"])
     stalls = np.array(stalls)
     q = lambda x: [float(np.percentile(x, p)) for p in (5, 50, 95)]
-    emit(dict(measurement="config4_replay", agents=len(agents), speed=speed, wall_s=time.perf_counter() - t_wall0,
-              offloads=len(rates["offload"]), rejected_cpu_capacity=rejected,
-              uploads_complete_before_call_finish=ready, uploads=len(stalls),
-              fraction_ready=ready / max(1, len(stalls)),
-              stall_ms_when_not_ready_p50_p95_max=[float(np.percentile(stalls[stalls > 0], p)) for p in (50, 95, 100)] if (stalls > 0).any() else [0, 0, 0],
-              offload_GBps_p5_p50_p95=q(rates["offload"]), upload_GBps_p5_p50_p95=q(rates["upload"]),
-              upload_ms_per_1k_tokens_p5_p50_p95=q(ms1k)))
+    late = stalls[stalls > 0]
+    return dict(speed=speed, wall_s=time.perf_counter() - t_wall0, offloads=len(rates["offload"]),
+                rejected_cpu_capacity=rejected, uploads=len(stalls), uploads_complete_before_call_finish=ready,
+                fraction_ready=ready / max(1, len(stalls)), mean_stall_ms=float(stalls.mean()) if len(stalls) else 0.0,
+                stall_ms_when_not_ready_p50_p95_max=[float(np.percentile(late, p)) for p in (50, 95, 100)] if len(late) else [0, 0, 0],
+                offload_GBps_p5_p50_p95=q(rates["offload"]), upload_GBps_p5_p50_p95=q(rates["upload"]),
+                upload_ms_per_1k_tokens_p5_p50_p95=q(ms1k))
+
+
+def m_config4_replay(torch, K, W, emit, speed=1.0):
+    """Real-time replay of the config-4 trace: every call offloads (if the 16 GiB arena has room), the
+    upload is issued 200 ms before the predicted finish (constant 2 s prediction) or at the finish when
+    the tool returns early.  Reports how often the KV is back when the tool returns, the stall when it
+    is not, and the per-transfer rates."""
+    shape = W.CONFIGS[3]
+    agents, events = W.dag_trace(W.rng_for(3), block_size=shape.block_size)
+    c = Ctx(torch, K, W, shape, 3, 4096, fill=False)
+    res = _replay(torch, K, W, c, agents, events, speed)
+    emit(dict(measurement="config4_replay", agents=len(agents), **res))
+    c.close()
+
+
+def m_forecast_noise(torch, K, W, emit, speed=2.0):
+    """The same trace (twice as fast) with the library's forecaster (Eq. 1) in place of the constant
+    prediction: the user's estimate of a call is its true duration times lognormal noise of the given
+    sigma, the history term is the per-type moving average fed by call_finish."""
+    shape = W.CONFIGS[3]
+    agents, events = W.dag_trace(W.rng_for(3), block_size=shape.block_size)
+    c = Ctx(torch, K, W, shape, 3, 4096, fill=False)
+    rows = []
+    for sigma in (0.0, 0.25, 0.5):
+        rng = W.rng_for(3, salt=70)
+        user = [a["call_s"] * 1e3 * float(np.exp(rng.normal(0.0, sigma))) for a in agents]
+        rc, f = K.tc_forecaster_create(0.8, 0.3, 2000.0)
+        K.check(rc)
+        res = _replay(torch, K, W, c, agents, events, speed,
+                      predict_ms=lambda i: K.tc_forecaster_estimate(f, i % 4, user[i]),
+                      observe=lambda i, ms: K.check(K.tc_forecaster_observe(f, i % 4, ms)))
+        K.tc_forecaster_destroy(f)
+        rows.append(dict(noise_sigma=sigma, **res))
+    emit(dict(measurement="forecast_noise", agents=len(agents), alpha=0.8, gamma=0.3, rows=rows))
     c.close()
 
 
@@ -444,7 +486,7 @@ def m_config5(torch, K, W, emit):
 
 
 ALL = dict(sweep=m_sweep, naive=m_naive, config1=m_config1, config3=m_config3, config4=m_config4,
-           config4_replay=m_config4_replay, config5=m_config5)
+           config4_replay=m_config4_replay, forecast_noise=m_forecast_noise, config5=m_config5)
 
 
 def main():
