@@ -16,6 +16,8 @@ import pytest
 import oracle
 import tc_workloads as W
 
+O = oracle      # the oracle under test; test_oracle_mutants.py swaps in deliberately broken builds
+
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "block_size_anchors.txt")
 
 
@@ -39,31 +41,31 @@ def unique_pool(P, NB, pb, salt=0):
 # ------------------------------------------------------------------ paper anchors
 def test_block_bytes_matches_paper():
     for L, H, D, bs, eb, want in _golden("block_bytes"):
-        pb = oracle.page_bytes(bs, H, D, eb)
+        pb = O.page_bytes(bs, H, D, eb)
         assert 2 * L * pb == want
-        assert oracle.record_bytes(L, pb, 0) == want  # no scales, already a 256-B multiple
+        assert O.record_bytes(L, pb, 0) == want  # no scales, already a 256-B multiple
 
 
 def test_tokens_to_blocks_matches_paper():
     for tokens, bs, want in _golden("tokens_to_blocks"):
-        assert oracle.blocks_for_tokens(tokens, bs) == want
-    assert oracle.blocks_for_tokens(1, 16) == 1
-    assert oracle.blocks_for_tokens(17, 16) == 2
-    assert oracle.blocks_for_tokens(0, 16) == 0
+        assert O.blocks_for_tokens(tokens, bs) == want
+    assert O.blocks_for_tokens(1, 16) == 1
+    assert O.blocks_for_tokens(17, 16) == 2
+    assert O.blocks_for_tokens(0, 16) == 0
 
 
 def test_benchmark_config_record_sizes():
     # the benchmark configurations: 2 MiB per block for the 8B shape; 4 MiB for 64 layers;
     # 5 MiB of fp8 pages + 160 scale words (640 B), padded to a 256-B multiple
     c = W.CONFIGS
-    assert oracle.record_bytes(c[0].num_layers, c[0].page_bytes, 0) == 32 * 1024
-    assert oracle.record_bytes(c[1].num_layers, c[1].page_bytes, 0) == 2 * 1024 * 1024
-    assert oracle.record_bytes(c[3].num_layers, c[3].page_bytes, 0) == 4 * 1024 * 1024
+    assert O.record_bytes(c[0].num_layers, c[0].page_bytes, 0) == 32 * 1024
+    assert O.record_bytes(c[1].num_layers, c[1].page_bytes, 0) == 2 * 1024 * 1024
+    assert O.record_bytes(c[3].num_layers, c[3].page_bytes, 0) == 4 * 1024 * 1024
     assert c[4].page_bytes == 32 * 1024
-    assert oracle.record_bytes(c[4].num_layers, c[4].page_bytes, 160) == 5 * 1024 * 1024 + 768
-    assert oracle.record_bytes(1, 16, 0) == 256   # pad up
-    assert oracle.record_bytes(1, 16, 1) == 256
-    assert oracle.record_bytes(2, 64, 4) == 512   # 256 + 16 -> 512
+    assert O.record_bytes(c[4].num_layers, c[4].page_bytes, 160) == 5 * 1024 * 1024 + 768
+    assert O.record_bytes(1, 16, 0) == 256   # pad up
+    assert O.record_bytes(1, 16, 1) == 256
+    assert O.record_bytes(2, 64, 4) == 512   # 256 + 16 -> 512
 
 
 # ------------------------------------------------------------------ numpy as the definition
@@ -74,9 +76,9 @@ def test_offload_is_numpy_take(L, NB, pb, S, n):
     pool = unique_pool(P, NB, pb)
     scales = rng.integers(0, 2**32, size=S * NB, dtype=np.uint32) if S else None
     ids = W.pick_ids(rng, NB, n)
-    rec = oracle.record_bytes(L, pb, S)
+    rec = O.record_bytes(L, pb, S)
     host = np.full(n * rec, 0xAB, dtype=np.uint8)
-    oracle.offload(pool, scales, L, NB, pb, S, ids, host)
+    O.offload(pool, scales, L, NB, pb, S, ids, host)
 
     h = host.reshape(n, rec)
     # pages: the library's own gather along the block axis, blocks moved to the front
@@ -92,7 +94,7 @@ def test_offload_is_numpy_take(L, NB, pb, S, n):
 def test_upload_is_numpy_put(L, NB, pb, S, n):
     P = 2 * L
     rng = np.random.default_rng(7 + NB)
-    rec = oracle.record_bytes(L, pb, S)
+    rec = O.record_bytes(L, pb, S)
     pool0 = unique_pool(P, NB, pb, salt=5)
     scales0 = rng.integers(0, 2**32, size=S * NB, dtype=np.uint32) if S else None
     host = rng.integers(0, 256, size=n * rec, dtype=np.uint8)
@@ -100,7 +102,7 @@ def test_upload_is_numpy_put(L, NB, pb, S, n):
     table = np.full(n + 3, -7, dtype=np.int32)
 
     pool, scales = pool0.copy(), (scales0.copy() if S else None)
-    oracle.upload(host, L, NB, pb, S, new_ids, pool, scales, table[1:])
+    O.upload(host, L, NB, pb, S, new_ids, pool, scales, table[1:])
 
     want = pool0.reshape(P, NB, pb).copy()
     want[:, new_ids, :] = host.reshape(n, rec)[:, : P * pb].reshape(n, P, pb).transpose(1, 0, 2)
@@ -121,11 +123,11 @@ def _round_trip(shape, rng, n, scramble=True, same_ids=False):
     scales0 = W.make_scales_host(shape, rng)
     ids = W.pick_ids(rng, NB, n)
     new_ids = ids.copy() if same_ids else W.pick_ids(rng, NB, n, exclude=ids)
-    rec = oracle.record_bytes(L, pb, S)
+    rec = O.record_bytes(L, pb, S)
     host = np.empty(n * rec, dtype=np.uint8)
     pool = pool0.copy()
     scales = scales0.copy() if S else None
-    oracle.offload(pool, scales, L, NB, pb, S, ids, host)
+    O.offload(pool, scales, L, NB, pb, S, ids, host)
     assert np.array_equal(pool, pool0), "offload must not write the pool"
     scr = np.zeros(NB, dtype=bool)
     if scramble:  # the freed source blocks get reused by somebody else
@@ -137,7 +139,7 @@ def _round_trip(shape, rng, n, scramble=True, same_ids=False):
     table = np.full(n + 2, -1, dtype=np.int32)
     table[:n] = ids
     table0 = table.copy()
-    oracle.upload(host, L, NB, pb, S, new_ids, pool, scales, table)
+    O.upload(host, L, NB, pb, S, new_ids, pool, scales, table)
     return pool0, scales0, pool, scales, ids, new_ids, table0, table, scr
 
 
@@ -181,12 +183,12 @@ def test_remapped_table_addresses_same_logical_tokens():
     for t in range(n * bs):
         for layer in range(L):
             for kv in (0, 1):
-                before = oracle.read_token(pool0, L, NB, pb, bs, table0, t, layer, kv)
-                after = oracle.read_token(pool, L, NB, pb, bs, table, t, layer, kv)
+                before = O.read_token(pool0, L, NB, pb, bs, table0, t, layer, kv)
+                after = O.read_token(pool, L, NB, pb, bs, table, t, layer, kv)
                 assert np.array_equal(before, after)
     # read_token itself against numpy on the 5-d view [L][2][NB][bs][token bytes]
     v = pool0.reshape(L, 2, NB, bs, pb // bs)
-    assert np.array_equal(oracle.read_token(pool0, L, NB, pb, bs, table0, 37, 1, 0), v[1, 0, table0[37 // bs], 37 % bs])
+    assert np.array_equal(O.read_token(pool0, L, NB, pb, bs, table0, 37, 1, 0), v[1, 0, table0[37 // bs], 37 % bs])
 
 
 # ------------------------------------------------------------------ brute force on tiny pools
@@ -198,12 +200,12 @@ def test_brute_force_all_id_tuples():
             for S in (0, 1, P):
                 pool = unique_pool(P, NB, pb, salt=NB)
                 scales = (np.arange(S * NB, dtype=np.uint32) * np.uint32(2246822519) + np.uint32(9)) if S else None
-                rec = oracle.record_bytes(L, pb, S)
+                rec = O.record_bytes(L, pb, S)
                 for n in range(0, min(3, NB) + 1):
                     for ids in itertools.permutations(range(NB), n):
                         ids_a = np.array(ids, dtype=np.int32)
                         host = np.full(max(n, 1) * rec, 0xEE, dtype=np.uint8)
-                        oracle.offload(pool, scales, L, NB, pb, S, ids_a, host)
+                        O.offload(pool, scales, L, NB, pb, S, ids_a, host)
                         for j in range(n):
                             for p in range(P):
                                 for b in range(pb):
@@ -221,7 +223,7 @@ def test_brute_force_all_id_tuples():
                             pool2 = np.zeros_like(pool)
                             sc2 = np.zeros(S * NB, dtype=np.uint32) if S else None
                             tbl = np.full(n + 1, -3, dtype=np.int32)
-                            oracle.upload(host, L, NB, pb, S, np.array(new, dtype=np.int32), pool2, sc2, tbl)
+                            O.upload(host, L, NB, pb, S, np.array(new, dtype=np.int32), pool2, sc2, tbl)
                             want = np.zeros_like(pool)
                             for i in range(n):
                                 for p in range(P):
@@ -241,16 +243,16 @@ def test_empty_and_bad_ids():
     L, NB, pb = 2, 8, 32
     pool = unique_pool(2 * L, NB, pb)
     host = np.full(256, 0x11, dtype=np.uint8)
-    oracle.offload(pool, None, L, NB, pb, 0, np.zeros(0, dtype=np.int32), host)
+    O.offload(pool, None, L, NB, pb, 0, np.zeros(0, dtype=np.int32), host)
     assert (host == 0x11).all()
     before = pool.copy()
     for bad in ([-1], [NB], [0, 2**31 - 1]):
         h = np.full(len(bad) * 256, 0x11, dtype=np.uint8)
-        with pytest.raises(oracle.OracleError):
-            oracle.offload(pool, None, L, NB, pb, 0, np.array(bad, dtype=np.int32), h)
+        with pytest.raises(O.OracleError):
+            O.offload(pool, None, L, NB, pb, 0, np.array(bad, dtype=np.int32), h)
         assert (h == 0x11).all(), "nothing may be written when an id is bad"
-        with pytest.raises(oracle.OracleError):
-            oracle.upload(h, L, NB, pb, 0, np.array(bad, dtype=np.int32), pool, None, None)
+        with pytest.raises(O.OracleError):
+            O.upload(h, L, NB, pb, 0, np.array(bad, dtype=np.int32), pool, None, None)
         assert np.array_equal(pool, before)
 
 
@@ -261,5 +263,5 @@ def test_opaque_bytes_survive():
     special = np.array([0x7FC1, 0xFFFF, 0x8000, 0x0001, 0x7F80, 0xFF81, 0x0000, 0x7FFF], dtype=np.uint16).view(np.uint8)
     pool[(0 * NB + 2) * pb : (0 * NB + 2) * pb + 16] = special
     host = np.empty(256, dtype=np.uint8)
-    oracle.offload(pool, None, L, NB, pb, 0, np.array([2], dtype=np.int32), host)
+    O.offload(pool, None, L, NB, pb, 0, np.array([2], dtype=np.int32), host)
     assert np.array_equal(host[:16], special)
