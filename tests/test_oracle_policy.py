@@ -49,7 +49,8 @@ def test_should_offload_hand_worked():
     t_tr = policy.estimate_transfer_ms(model, 256)
     assert abs(t_tr - 20.68) < 1e-12
     queue = [(300, 10), (200, 5000), (100, 900), (50, 100)]
-    assert policy.should_offload(model, 256, 20.68, 1.0, queue) == (False, -1)      # stall == transfer
+    assert policy.should_offload(model, 256, t_tr, 1.0, [(1, 0.0)]) == (False, -1)  # stall == transfer: "<=" rejects
+    assert policy.should_offload(model, 256, float(np.nextafter(t_tr, np.inf)), 1.0, [(1, 0.0)]) == (True, 0)
     assert policy.should_offload(model, 256, 20.0, 1.0, queue) == (False, -1)       # stall too short
     # window 100 ms at 10 tokens/ms = 1 000 tokens: #0 needs too many blocks, #1 too much work, #2 fits
     assert policy.should_offload(model, 256, 120.68, 10.0, queue) == (True, 2)

@@ -1,0 +1,105 @@
+"""The same question for the oracle's Python parts (bookkeeping model, scheduling arithmetic,
+lifecycle, forecast): a planted mistake in a copy of the source must make at least one pin fail.
+CPU only; the copies are exec'd into throw-away modules and swapped into the pin modules' namespaces."""
+import inspect
+import os
+import types
+
+import pytest
+
+import oracle
+import test_oracle_block_pool as pins_pool
+import test_oracle_lifecycle as pins_life
+import test_oracle_policy as pins_policy
+
+ODIR = os.path.dirname(oracle.__file__)
+
+CASES = {
+    # (source file, pin module, names to swap in the pin module): {description: (old, new)}
+    ("policy.py", pins_policy, ("policy",)): {
+        "a stall equal to the transfer time is accepted": ("if t_fc_ms <= t_transfer:", "if t_fc_ms < t_transfer:"),
+        "last fit instead of first fit": ("for k, (kv_blocks, work_tokens) in enumerate(waiting):",
+                                          "for k, (kv_blocks, work_tokens) in reversed(list(enumerate(waiting))):"),
+        "a request needing exactly the freed blocks does not fit": ("if kv_blocks <= req_blocks and", "if kv_blocks < req_blocks and"),
+        "capacity divides by the throughput": ("n_capacity = t_window * v_throughput_tokens_per_ms", "n_capacity = t_window / v_throughput_tokens_per_ms"),
+        "the window forgets the transfer time": ("t_window = t_fc_ms - t_transfer", "t_window = t_fc_ms"),
+        "transfer cost drops the upload": ("return t_offload + t_upload", "return t_offload"),
+        "budget lets the inner term go negative": ("return max(0, b_gpu_free - max(0, d_critical - b_shared_free))",
+                                                   "return max(0, b_gpu_free - (d_critical - b_shared_free))"),
+        "half of the deficit rounds down": ("-(-b_deficit // 2)", "b_deficit // 2"),
+        "the fit's slope is inverted": ("b = sxy / sxx", "b = sxx / sxy"),
+    },
+    ("lifecycle.py", pins_life, ("L",)): {
+        "uploaded + call_finish waits instead of resuming": ("return (RUNNING, False, False), RESUME          # already back", "return (UPLOADED, True, False), WAIT  #"),
+        "offloaded + call_finish does nothing": ("return (OFFLOADED, True, False), UPLOAD_NOW     # returned early", "return (OFFLOADED, True, False), NONE  #"),
+        "a finish during the offload is forgotten": ("return (PENDING_OFFLOAD, True, True), WAIT", "return (PENDING_OFFLOAD, False, True), WAIT"),
+        "an agent resumes while its upload is in flight": ("return (PENDING_UPLOAD, True, in_flight), WAIT", "return (RUNNING, False, False), RESUME"),
+        "the moving average uses alpha": ("self.gamma * elapsed_ms + (1 - self.gamma) * self.history[fn_type]",
+                                          "self.alpha * elapsed_ms + (1 - self.alpha) * self.history[fn_type]"),
+        "Eq. 1 with the weights swapped": ("return self.alpha * t_user_ms + (1 - self.alpha) * h", "return (1 - self.alpha) * t_user_ms + self.alpha * h"),
+        "history wins over the user's estimate entirely": ("return self.alpha * t_user_ms + (1 - self.alpha) * h", "return h"),
+        "the first observation is averaged with the default": ("            self.history[fn_type] = elapsed_ms\n",
+                                                               "            self.history[fn_type] = self.gamma * elapsed_ms + (1 - self.gamma) * self.default_ms\n"),
+    },
+    ("block_pool.py", pins_pool, ("OracleBlockPool", "OracleHostArena", "OracleError")): {
+        "a released block skips pending-free": ("                if self.inflight[b] > 0:\n                    self.pending[b] = True\n                else:\n                    self.free_stack.append(b)",
+                                                "                self.free_stack.append(b)"),
+        "the free list is a queue": ("out = [self.free_stack.pop() for _ in range(n)]", "out = [self.free_stack.pop(0) for _ in range(n)]"),
+        "retiring forgets the pending-free blocks": ("            if self.inflight[b] == 0 and self.pending[b]:\n                self.pending[b] = False\n                self.free_stack.append(b)",
+                                                     "            if self.inflight[b] == 0 and self.pending[b]:\n                self.pending[b] = False"),
+        "a short pool hands out what it has": ("        if n > len(self.free_stack):\n            raise OracleError(\"NOMEM\")", "        n = min(n, len(self.free_stack))"),
+        "one finished read frees a block two copies read": ("if self.inflight[b] == 0 and self.pending[b]:", "if self.pending[b]:"),
+        "shared blocks may move": ("            if self.refcount[b] > 1:\n                raise OracleError(\"SHARED\"", "            if self.refcount[b] > 99:\n                raise OracleError(\"SHARED\""),
+        "the arena takes the last run that fits": ("for k, (start, length) in enumerate(self.free_runs):", "for k, (start, length) in reversed(list(enumerate(self.free_runs))):"),
+        "released runs are not merged": ("if merged and merged[-1][0] + merged[-1][1] == s:", "if False:"),
+        "a busy arena buffer is recycled at once": ("        if self.inflight.get(start, 0) > 0:\n            self.pending.add(start)\n        else:\n            self._release(start)",
+                                                    "        self._release(start)"),
+    },
+}
+
+ALL = [(key, name) for key, d in CASES.items() for name in d]
+
+
+def _load(fname, old, new):
+    text = open(os.path.join(ODIR, fname)).read()
+    assert text.count(old) == 1, f"expected exactly one occurrence of the line to break in {fname}"
+    mod = types.ModuleType("oracle_mutant_" + fname[:-3])
+    exec(compile(text.replace(old, new), fname + " (mutant)", "exec"), mod.__dict__)
+    return mod
+
+
+def _failing(pin_module):
+    failed = []
+    for name, fn in inspect.getmembers(pin_module, inspect.isfunction):
+        if name.startswith("test_") and not inspect.signature(fn).parameters:
+            try:
+                fn()
+            except (AssertionError, KeyError, IndexError, ValueError, ZeroDivisionError, TypeError, pytest.fail.Exception) as e:
+                failed.append(name)
+            except Exception as e:      # noqa: BLE001  the models' own error types
+                if type(e).__name__ in ("OracleError", "Invalid"):
+                    failed.append(name)
+                else:
+                    raise
+    return failed
+
+
+@pytest.mark.parametrize("key,name", ALL, ids=[n for _, n in ALL])
+def test_planted_mistake_is_caught(key, name):
+    fname, pin_module, swap = key
+    old, new = CASES[key][name]
+    mutant = _load(fname, old, new)
+    saved = {s: getattr(pin_module, s) for s in swap}
+    try:
+        for s in swap:
+            setattr(pin_module, s, mutant if s in ("policy", "L") else getattr(mutant, s))
+        failed = _failing(pin_module)
+    finally:
+        for s, v in saved.items():
+            setattr(pin_module, s, v)
+    assert failed, f"no pin noticed: {name}"
+
+
+def test_unmodified_sources_pass():
+    for (fname, pin_module, swap) in CASES:
+        assert _failing(pin_module) == []
