@@ -107,9 +107,15 @@ typedef struct {
 
 /* ---- life cycle ------------------------------------------------------------------------- */
 /* Binds a pool (Sec. 6.3: the block pool owns the GPU<->CPU mapping).  Allocates the staging
- * ring and the pinned arena; `opts` may be NULL for defaults. */
+ * ring, the id rings and the pinned arena on the current device and warms them with one DMA pass;
+ * `opts` may be NULL for defaults.  The pool and the scales stay the caller's and must outlive the
+ * context.  TC_ERR_INVAL for a bad description (zero sizes, page_bytes not a multiple of 16,
+ * misaligned base, scales_per_block not in {0, 1, 2*num_layers}, scales given xor announced, an option
+ * out of range), TC_ERR_NOT_PINNED when kv_base / scales are not device memory, TC_ERR_HOST_NOMEM /
+ * TC_ERR_HIP when an allocation fails; *out is NULL on any error. */
 int tc_create(const tc_pool_desc *pool, const tc_opts *opts, tc_ctx **out);
-/* Waits for every transfer in flight, then frees what the context owns. */
+/* Waits for every transfer in flight, then frees what the context owns (staging, rings, arena:
+ * pointers from tc_host_alloc die with it).  NULL is a no-op. */
 int tc_destroy(tc_ctx *ctx);
 /* Host bytes per block (Sec. 7.6: 48 layers x K,V x 8 x 128 x 16 tokens x 2 B = 3 MiB). */
 uint64_t tc_record_bytes(const tc_ctx *ctx);
@@ -119,19 +125,24 @@ const char *tc_strerror(int code);
 /* Pops n ids off the LIFO free list (first hand-out is 0,1,2,...); reference count := 1.
  * TC_ERR_NOMEM and no change when fewer than n blocks are free. */
 int tc_alloc(tc_ctx *ctx, uint32_t n, int32_t *out_ids /* HOST, n */);
-/* Claims exactly these ids ("reuses the original GPU block when possible"); all must be free. */
+/* Claims exactly these ids ("reuses the original GPU block when possible"); all-or-nothing.
+ * TC_ERR_RANGE / TC_ERR_DUP for bad lists, TC_ERR_NOMEM when one of them is held or pending-free. */
 int tc_alloc_at(tc_ctx *ctx, const int32_t *ids, uint32_t n);
-/* One more owner for each id (shared prefix blocks). */
+/* One more owner for each id (shared prefix blocks).  TC_ERR_RANGE; TC_ERR_INVAL when an id is not
+ * allocated.  No change on error. */
 int tc_ref(tc_ctx *ctx, const int32_t *ids, uint32_t n);
 /* Drops one owner per id.  At zero owners the block is free, unless a transfer touching it is
  * still in flight: then it is pending-free and becomes free when tc_poll / tc_sync retire that
  * transfer ("return to the free pool only after the transfer completes"). */
 int tc_free(tc_ctx *ctx, const int32_t *ids, uint32_t n);
-/* Copies the ids that have exactly one owner, order kept; *m = how many. */
+/* Copies the ids that have exactly one owner, order kept, into out_ids (HOST, room for n); *m = how
+ * many.  TC_ERR_RANGE for a bad id. */
 int tc_filter_private(tc_ctx *ctx, const int32_t *ids, uint32_t n, int32_t *out_ids, uint32_t *m);
 
 /* ---- CPU block pool (Sec. 6.3: fixed-size blocks recycled, never returned to the OS) ----- */
-/* n_blocks consecutive record slots from the pinned arena (first fit); n_blocks = 0 gives NULL. */
+/* n_blocks consecutive record slots from the pinned arena (first fit from the lowest address);
+ * n_blocks = 0 gives NULL.  The memory stays the context's.  TC_ERR_HOST_NOMEM when no run of free
+ * slots is long enough ("CPU capacity is insufficient", Sec. 4.2). */
 int tc_host_alloc(tc_ctx *ctx, uint32_t n_blocks, void **host_buf);
 /* host_buf must be a pointer tc_host_alloc returned (NULL is a no-op).  If a transfer using it
  * is in flight the slots are recycled when that transfer retires. */
@@ -148,7 +159,12 @@ int tc_offload(tc_ctx *ctx, const int32_t *block_ids, uint32_t n, void *host_buf
 int tc_upload(tc_ctx *ctx, const void *host_buf, const int32_t *new_block_ids, uint32_t n,
               int32_t *block_table, void *stream);
 /* Several agents in one call: their records share staging chunks and kernel launches.  Ids must
- * be distinct across the whole batch. */
+ * be distinct across the whole batch; one bad descriptor fails the whole call with no effect.
+ * Errors of all four transfer calls: TC_ERR_INVAL (NULL where data is expected, misaligned host
+ * buffer, buffer longer than its arena allocation, unallocated block), TC_ERR_RANGE, TC_ERR_DUP,
+ * TC_ERR_SHARED, TC_ERR_NOT_PINNED (host buffer not pinned, block table not device memory),
+ * TC_ERR_HIP (a runtime call failed while enqueueing; the bookkeeping is rolled back, work already
+ * enqueued still runs and the transfer must be treated as failed). */
 int tc_offload_batch(tc_ctx *ctx, const tc_xfer_desc *descs, uint32_t n_descs, void *stream);
 int tc_upload_batch(tc_ctx *ctx, const tc_xfer_desc *descs, uint32_t n_descs, void *stream);
 
@@ -158,6 +174,8 @@ int tc_poll(tc_ctx *ctx);
 int tc_sync(tc_ctx *ctx);
 
 /* ---- observation ------------------------------------------------------------------------ */
+/* Snapshot of the counters (the part of the pressure snapshot of Sec. 3.2 that this layer owns:
+ * free / used / pending-free / shared GPU blocks, CPU slots, transfer volume). */
 int tc_stats(tc_ctx *ctx, tc_stats_t *out);
 /* on != 0: bracket every gather / scatter launch with timing events on its stream. */
 int tc_set_profiling(tc_ctx *ctx, int on);
