@@ -51,13 +51,6 @@ class GpuPool:
         self.pool = self.scales = None
         torch.cuda.empty_cache()
 
-    def block_checksums(self, ids):
-        """[P][len(ids)] int64 page checksums (+ scale words as extra rows): torch only."""
-        idx = torch.as_tensor(np.asarray(ids, dtype=np.int64), device=DEV)
-        cs = self.pool.view(torch.int32).view(self.P, self.NB, self.pb // 4)[:, idx].sum(dim=2, dtype=torch.int64)
-        if self.S:
-            cs = torch.cat([cs, self.scales.view(self.S, self.NB)[:, idx].to(torch.int64)], dim=0)
-        return cs
 
     # ---- views / copies (torch only) --------------------------------------
     def pool3(self):
@@ -78,9 +71,32 @@ class GpuPool:
     def scales_all_to_host(self):
         return self.scales.cpu().numpy().view(np.uint32) if self.S else None
 
-    def page_checksums(self):
-        """One int64 per (plane, block): a torch reduction, independent of the library."""
-        return self.pool.view(torch.int32).view(self.P, self.NB, self.pb // 4).sum(dim=2, dtype=torch.int64)
+    def _weights(self):
+        # odd, position-dependent multipliers: a sum that notices words that moved inside a page
+        i = torch.arange(self.pb // 4, dtype=torch.int64, device=DEV)
+        return i * 2654435761 + 0x9E3779B1 | 1
+
+    def page_checksums(self, weighted=False):
+        """One int64 per (plane, block): a torch reduction, independent of the library.  weighted:
+        position-sensitive (wrapping) sum instead of the plain sum of the page's 32-bit words."""
+        v = self.pool.view(torch.int32).view(self.P, self.NB, self.pb // 4)
+        if not weighted:
+            return v.sum(dim=2, dtype=torch.int64)
+        w = self._weights()
+        return torch.stack([(v[p].to(torch.int64) * w).sum(dim=1) for p in range(self.P)])
+
+    def block_checksums(self, ids, weighted=True):
+        """[P][len(ids)] int64 page checksums (+ scale words as extra rows): torch only."""
+        idx = torch.as_tensor(np.asarray(ids, dtype=np.int64), device=DEV)
+        v = self.pool.view(torch.int32).view(self.P, self.NB, self.pb // 4)
+        if weighted:
+            w = self._weights()
+            cs = torch.stack([(v[p, idx].to(torch.int64) * w).sum(dim=1) for p in range(self.P)])
+        else:
+            cs = v[:, idx].sum(dim=2, dtype=torch.int64)
+        if self.S:
+            cs = torch.cat([cs, self.scales.view(self.S, self.NB)[:, idx].to(torch.int64)], dim=0)
+        return cs
 
 
 def pinned_bytes(n):

@@ -102,6 +102,7 @@ def test_config3_64_agents_fragmented_pool_overlapped_with_hbm_stream():
         bufs = [addr for _, addr in bufs]
 
         before = gp.page_checksums()
+        before_w = gp.page_checksums(weighted=True)
         sample = sorted({int(np.argmax(nblk)), int(np.argmin(nblk)), *[int(x) for x in rng.choice(64, 4, replace=False)]})
         mirror = SparseMirror(gp)
         mirrors.append(mirror)
@@ -151,7 +152,8 @@ def test_config3_64_agents_fragmented_pool_overlapped_with_hbm_stream():
         for i in range(64):
             K.check(K.tc_host_free(gp.ctx, bufs[i]))
         ls.sync()
-        after = gp.page_checksums()
+        after = gp.page_checksums(weighted=True)
+        before = before_w
         touched = torch.zeros(gp.NB, dtype=torch.bool, device=DEV)
         for i in range(64):
             src = torch.as_tensor(agents[i].astype(np.int64), device=DEV)
