@@ -76,6 +76,26 @@ class OracleBlockPool:
             self.free_stack.remove(b)
             self.refcount[b] = 1
 
+    def alloc_prefer(self, preferred):
+        """n blocks, all or nothing: preferred[i] itself wherever it is still free (the original GPU
+        block is claimed again when possible), a fresh block from the free list for the rest.  The
+        preferred ids are claimed first, in order; the gaps are then filled in order.  An id that is
+        out of range, taken, pending-free or named earlier in the call is simply no preference."""
+        preferred = [int(b) for b in preferred]
+        if len(preferred) > len(self.free_stack):
+            raise OracleError("NOMEM")
+        out = [None] * len(preferred)
+        for i, b in enumerate(preferred):
+            if 0 <= b < self.NB and b in self.free_stack:
+                self.free_stack.remove(b)
+                self.refcount[b] = 1
+                out[i] = b
+        for i in range(len(out)):
+            if out[i] is None:
+                out[i] = self.free_stack.pop()
+                self.refcount[out[i]] = 1
+        return out
+
     def ref(self, ids):
         ids = [int(b) for b in ids]
         self._check_range(ids)

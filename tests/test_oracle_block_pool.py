@@ -199,3 +199,61 @@ def test_host_arena_random_ops_no_overlap():
             del live[s]
         assert ar.used_slots() == sum(live.values())
         assert ar.used_slots() + sum(l for _, l in ar.free_runs) == N
+
+
+# ---- alloc_prefer: "reuses the original GPU block when possible" (Sec. 6.3) ------------------------
+
+def test_alloc_prefer_hand_worked():
+    bp = OracleBlockPool(8)
+    bp.alloc(8)
+    bp.free([5, 2, 7])                       # stack top: 7, then 2, then 5
+    assert bp.alloc_prefer([2, 4, 5]) == [2, 7, 5]    # 2 and 5 are free again, 4 is taken: fresh block 7
+    assert bp.n_free() == 0
+    with pytest.raises(OracleError) as e:
+        bp.alloc_prefer([1])
+    assert e.value.code == "NOMEM"
+
+
+def test_alloc_prefer_reduces_to_alloc_at_plus_alloc():
+    """Against routines pinned above: claiming the free preferred ids with alloc_at and popping the rest
+    with alloc gives the same ids in the same places and leaves the same free list."""
+    rng = np.random.default_rng(77)
+    for trial in range(200):
+        NB = int(rng.integers(1, 24))
+        a, b = OracleBlockPool(NB), OracleBlockPool(NB)
+        taken = [int(x) for x in rng.permutation(NB)[:int(rng.integers(0, NB + 1))]]
+        for bp in (a, b):
+            bp.alloc_at(taken)
+        back = [int(x) for x in rng.permutation(taken)[:int(rng.integers(0, len(taken) + 1))]]
+        for bp in (a, b):
+            bp.free(back)
+        n = int(rng.integers(0, NB + 2))
+        pref = [int(x) for x in rng.integers(-2, NB + 2, size=n)]       # repeats, taken and bad ids included
+        if n > a.n_free():
+            before = list(a.free_stack)
+            with pytest.raises(OracleError):
+                a.alloc_prefer(pref)
+            assert a.free_stack == before and a.refcount == b.refcount  # all or nothing
+            continue
+        got = a.alloc_prefer(pref)
+        seen, claim = set(), []
+        for x in pref:
+            ok = 0 <= x < NB and b.refcount[x] == 0 and not b.pending[x] and x not in seen
+            claim.append(ok)
+            if ok:
+                seen.add(x)
+        b.alloc_at([x for x, ok in zip(pref, claim) if ok])
+        fresh = iter(b.alloc(n - sum(claim)))
+        want = [x if ok else next(fresh) for x, ok in zip(pref, claim)]
+        assert got == want, (trial, pref)
+        assert a.free_stack == b.free_stack and a.refcount == b.refcount
+
+
+def test_alloc_prefer_never_takes_a_pending_free_block():
+    bp = OracleBlockPool(4)
+    ids = bp.alloc(2)                        # 0, 1
+    bp.begin_op(ids)
+    bp.free(ids)                             # both pending-free while the copy reads them
+    assert bp.alloc_prefer([0, 1]) == [2, 3]
+    bp.retire_all()
+    assert sorted(bp.free_stack) == [0, 1]

@@ -3,6 +3,7 @@ lifecycle, forecast): a planted mistake in a copy of the source must make at lea
 CPU only; the copies are exec'd into throw-away modules and swapped into the pin modules' namespaces."""
 import inspect
 import os
+import struct
 import types
 
 import pytest
@@ -11,6 +12,7 @@ import oracle
 import test_oracle_block_pool as pins_pool
 import test_oracle_lifecycle as pins_life
 import test_oracle_policy as pins_policy
+import test_oracle_residency as pins_res
 
 ODIR = os.path.dirname(oracle.__file__)
 
@@ -52,8 +54,29 @@ CASES = {
         "shared blocks may move": ("            if self.refcount[b] > 1:\n                raise OracleError(\"SHARED\"", "            if self.refcount[b] > 99:\n                raise OracleError(\"SHARED\""),
         "the arena takes the last run that fits": ("for k, (start, length) in enumerate(self.free_runs):", "for k, (start, length) in reversed(list(enumerate(self.free_runs))):"),
         "released runs are not merged": ("if merged and merged[-1][0] + merged[-1][1] == s:", "if False:"),
+        "alloc_prefer claims a pending-free block": ("if 0 <= b < self.NB and b in self.free_stack:", "if 0 <= b < self.NB and self.refcount[b] == 0:"),
+        "alloc_prefer fills the gaps before it claims": ("        for i, b in enumerate(preferred):\n            if 0 <= b < self.NB and b in self.free_stack:",
+                                                         "        for i, b in reversed(list(enumerate(preferred))):\n            if 0 <= b < self.NB and b in self.free_stack:"),
+        "alloc_prefer hands out what it has": ("        if len(preferred) > len(self.free_stack):\n            raise OracleError(\"NOMEM\")", "        preferred = preferred[:len(self.free_stack)]"),
         "a busy arena buffer is recycled at once": ("        if self.inflight.get(start, 0) > 0:\n            self.pending.add(start)\n        else:\n            self._release(start)",
                                                     "        self._release(start)"),
+    },
+    ("residency.py", pins_res, ("R",)): {
+        "FNV-1 instead of FNV-1a": ("        h ^= byte\n        h = (h * FNV_PRIME) & _M64", "        h = (h * FNV_PRIME) & _M64\n        h ^= byte"),
+        "the 32-bit FNV prime": ("FNV_PRIME = 0x100000001B3", "FNV_PRIME = 0x01000193"),
+        "keys do not chain": ('h = fnv1a64(struct.pack("<Q", h) + struct.pack(', 'h = fnv1a64(struct.pack("<Q", parent) + struct.pack('),
+        "a partial block gets a key": ("for i in range(len(tokens) // block_size):", "for i in range(-(-len(tokens) // block_size)):"),
+        "tokens hashed big-endian": ('struct.pack(f"<{block_size}i"', 'struct.pack(f">{block_size}i"'),
+        "lookup skips a miss instead of stopping": ("            if e is None:\n                break", "            if e is None:\n                continue"),
+        "every record at the base address": ("self.entries[k] = [CPU, host_base + j * record_bytes, int(gpu_blocks[j])]", "self.entries[k] = [CPU, host_base, int(gpu_blocks[j])]"),
+        "an upload keeps the old GPU block": ("            self.entries[k][2] = int(b)\n", ""),
+        "an H2D entry can be uploaded again": ("if k not in self.entries or self.entries[k][0] != CPU:\n                raise OracleError(\"INVAL\", f\"key {k:#x} is not CPU-resident\")",
+                                               "if k not in self.entries:\n                raise OracleError(\"INVAL\", f\"key {k:#x} is not CPU-resident\")"),
+        "a finished upload stays in the index": ("        for k in keys:\n            del self.entries[k]\n\n    def remove", "\n    def remove"),
+        "eviction under a running upload": ("if k not in self.entries or self.entries[k][0] != CPU:\n                raise OracleError(\"INVAL\", f\"key {k:#x} is not an idle",
+                                             "if k not in self.entries:\n                raise OracleError(\"INVAL\", f\"key {k:#x} is not an idle"),
+        "a key entered twice replaces the first": ("            if k in self.entries:\n                raise OracleError(\"DUP\", f\"key {k:#x} is already CPU-resident\")", "            pass"),
+        "pending counts CPU-resident entries": ("[ABSENT])[0] == H2D)", "[ABSENT])[0] != ABSENT)"),
     },
 }
 
@@ -64,6 +87,7 @@ def _load(fname, old, new):
     text = open(os.path.join(ODIR, fname)).read()
     assert text.count(old) == 1, f"expected exactly one occurrence of the line to break in {fname}"
     mod = types.ModuleType("oracle_mutant_" + fname[:-3])
+    mod.__package__ = "oracle"          # the sources import their siblings relatively
     exec(compile(text.replace(old, new), fname + " (mutant)", "exec"), mod.__dict__)
     return mod
 
@@ -74,7 +98,7 @@ def _failing(pin_module):
         if name.startswith("test_") and not inspect.signature(fn).parameters:
             try:
                 fn()
-            except (AssertionError, KeyError, IndexError, ValueError, ZeroDivisionError, TypeError, pytest.fail.Exception) as e:
+            except (AssertionError, KeyError, IndexError, ValueError, ZeroDivisionError, TypeError, struct.error, pytest.fail.Exception) as e:
                 failed.append(name)
             except Exception as e:      # noqa: BLE001  the models' own error types
                 if type(e).__name__ in ("OracleError", "Invalid"):
@@ -92,7 +116,7 @@ def test_planted_mistake_is_caught(key, name):
     saved = {s: getattr(pin_module, s) for s in swap}
     try:
         for s in swap:
-            setattr(pin_module, s, mutant if s in ("policy", "L") else getattr(mutant, s))
+            setattr(pin_module, s, mutant if s in ("policy", "L", "R") else getattr(mutant, s))
         failed = _failing(pin_module)
     finally:
         for s, v in saved.items():
