@@ -125,15 +125,23 @@ const char *tc_strerror(int code);
 /* Pops n ids off the LIFO free list (first hand-out is 0,1,2,...); reference count := 1.
  * TC_ERR_NOMEM and no change when fewer than n blocks are free. */
 int tc_alloc(tc_ctx *ctx, uint32_t n, int32_t *out_ids /* HOST, n */);
-/* Claims exactly these ids ("reuses the original GPU block when possible"); all-or-nothing.
+/* Claims exactly these ids (Sec. 6.3: an upload may take its original GPU blocks again); all-or-nothing.
  * TC_ERR_RANGE / TC_ERR_DUP for bad lists, TC_ERR_NOMEM when one of them is held or pending-free. */
 int tc_alloc_at(tc_ctx *ctx, const int32_t *ids, uint32_t n);
+/* Sec. 6.3: an upload takes its original GPU block again where it still can.  n blocks, all or nothing
+ * (TC_ERR_NOMEM, nothing taken): out_ids[i] = preferred[i] wherever that block is still on the free
+ * list, a fresh block from the head of the list otherwise.  Preferred blocks are claimed first, in
+ * order, then the gaps are filled in order.  An id out of range, in use, pending-free or named
+ * earlier in the call is simply no preference (so -1 means "any").  Finished transfers are retired
+ * first.  preferred, out_ids: HOST, n entries each; they may be the same array. */
+int tc_alloc_prefer(tc_ctx *ctx, const int32_t *preferred, uint32_t n, int32_t *out_ids);
+
 /* One more owner for each id (shared prefix blocks).  TC_ERR_RANGE; TC_ERR_INVAL when an id is not
  * allocated.  No change on error. */
 int tc_ref(tc_ctx *ctx, const int32_t *ids, uint32_t n);
 /* Drops one owner per id.  At zero owners the block is free, unless a transfer touching it is
  * still in flight: then it is pending-free and becomes free when tc_poll / tc_sync retire that
- * transfer ("return to the free pool only after the transfer completes"). */
+ * transfer (Sec. 6.3: source blocks re-enter the free pool only once the copy is done). */
 int tc_free(tc_ctx *ctx, const int32_t *ids, uint32_t n);
 /* Copies the ids that have exactly one owner, order kept, into out_ids (HOST, room for n); *m = how
  * many.  TC_ERR_RANGE for a bad id. */
@@ -154,7 +162,7 @@ int tc_host_free(tc_ctx *ctx, void *host_buf);
  * ids must be distinct.  The pool and the block table are not written.  n = 0 is a no-op. */
 int tc_offload(tc_ctx *ctx, const int32_t *block_ids, uint32_t n, void *host_buf, void *stream);
 /* Upload: block new_block_ids[i] <- record i of host_buf, then block_table[i] = new_block_ids[i]
- * for i < n, written on `stream` after the data ("restores the GPU mapping").  block_table may
+ * for i < n, written on `stream` after the data (Sec. 6.3: the upload puts the GPU mapping back).  block_table may
  * be NULL.  Same id rules as tc_offload. */
 int tc_upload(tc_ctx *ctx, const void *host_buf, const int32_t *new_block_ids, uint32_t n,
               int32_t *block_table, void *stream);
@@ -196,7 +204,7 @@ typedef struct {
 } tc_waiting_req;
 
 /* Least-squares fit of both lines from m >= 2 measurements (n_blocks[i], offload_ms[i], upload_ms[i]):
- * "calibrated from measured per-block transfer constants on the target platform".  TC_ERR_INVAL
+ * Eq. 2's per-block constants are meant to come from measurements on the target machine.  TC_ERR_INVAL
  * when m < 2 or all sizes are equal. */
 int tc_cost_fit(const uint32_t *n_blocks, const double *offload_ms, const double *upload_ms, uint32_t m,
                 tc_cost_model *out);
@@ -249,6 +257,56 @@ int tc_forecaster_destroy(tc_forecaster *f);
 int tc_forecaster_observe(tc_forecaster *f, uint32_t fn_type, double elapsed_ms);
 /* Estimate for a type; has_user = 0 when the graph gives no predict_time. */
 double tc_forecaster_estimate(const tc_forecaster *f, uint32_t fn_type, int has_user, double t_user_ms);
+
+/* ---- residency map and CPU prefix-cache index (host only; Sec. 6.3) ---------------------- */
+/* Sec. 6.3: the block pool owns the mapping between GPU blocks, CPU blocks and block hashes.  An
+ * offload links the GPU block to its CPU record, marks it CPU-resident and enters its hash in a CPU
+ * prefix-cache index; a lookup that hits there saves the recomputation but leaves an H2D transfer
+ * entry that must complete before the request runs; the upload puts the GPU mapping back.  The paper
+ * names neither the hash nor the index structure: keys are opaque 64-bit values here, and a lookup
+ * answers for the longest leading run of keys present, since a block's key covers the prefix before
+ * it.  The index stores addresses and ids only; it never touches the records or the pool, and it is
+ * independent of any tc_ctx (the caller keeps it in step with its tc_offload / tc_upload calls).
+ * All key and id arrays are HOST memory, read during the call.  Every call is all-or-nothing: on an
+ * error the index is unchanged.  One internal mutex per index. */
+typedef struct tc_index tc_index;
+enum { TC_RES_ABSENT = 0, TC_RES_CPU = 1, TC_RES_H2D = 2 };
+typedef struct {
+    uint64_t key;
+    void *cpu_record;   /* HOST address of the block's record (inside the buffer given at insert) */
+    int32_t gpu_block;  /* TC_RES_CPU: the block it was offloaded from; TC_RES_H2D: where it is going */
+    int32_t state;      /* TC_RES_CPU or TC_RES_H2D */
+} tc_index_hit;
+
+int tc_index_create(tc_index **out);            /* TC_ERR_INVAL for NULL, TC_ERR_HOST_NOMEM */
+int tc_index_destroy(tc_index *ix);             /* NULL is fine */
+/* After tc_offload(gpu_blocks, n, host_buf): key[j] -> record host_buf + j*record_bytes, CPU-resident,
+ * remembered as coming from gpu_blocks[j].  TC_ERR_DUP if a key repeats or is already present. */
+int tc_index_insert(tc_index *ix, const uint64_t *keys, const int32_t *gpu_blocks, void *host_buf,
+                    uint64_t record_bytes, uint32_t n);
+/* Prefix lookup: fills out[0..*hits) for the longest leading run of keys that are present. */
+int tc_index_lookup(const tc_index *ix, const uint64_t *keys, uint32_t n, tc_index_hit *out /* n */,
+                    uint32_t *hits);
+/* A tc_upload into new_gpu_blocks has been issued for these keys: CPU-resident -> H2D transfer entry.
+ * TC_ERR_INVAL unless every key is present and CPU-resident; TC_ERR_DUP for a repeated key. */
+int tc_index_begin_upload(tc_index *ix, const uint64_t *keys, const int32_t *new_gpu_blocks, uint32_t n);
+/* That upload has completed: the entries leave the index (the GPU holds the mapping again; the
+ * caller may recycle the CPU records).  TC_ERR_INVAL unless every key is an H2D entry. */
+int tc_index_finish_upload(tc_index *ix, const uint64_t *keys, uint32_t n);
+/* Eviction of CPU-resident entries.  TC_ERR_INVAL if a key is absent or an upload is reading it. */
+int tc_index_remove(tc_index *ix, const uint64_t *keys, uint32_t n);
+/* How many of the keys are H2D entries: a request whose hits were uploaded may run when this is 0. */
+uint32_t tc_index_pending(const tc_index *ix, const uint64_t *keys, uint32_t n);
+uint64_t tc_index_size(const tc_index *ix);
+
+/* Convenience keys (this library's choice, the paper gives none): 64-bit FNV-1a, and one key per
+ * WHOLE block of token ids, each covering everything before it:
+ *   key[i] = FNV1a( le64(key[i-1]) || le32(tokens[i*bs .. (i+1)*bs)) ),  key[-1] = parent.
+ * A trailing partial block gets no key.  out needs n_tokens / block_size entries; *n_out = that count. */
+#define TC_FNV_BASIS 0xCBF29CE484222325ull
+uint64_t tc_fnv1a64(const void *data, uint64_t len, uint64_t basis);
+int tc_chain_hashes(const int32_t *tokens, uint64_t n_tokens, uint32_t block_size, uint64_t parent,
+                    uint64_t *out, uint64_t *n_out);
 
 /* ---- measurement helpers: not on the hot path ------------------------------------------- */
 /* dst[i] = src[i]: contiguous DEVICE->DEVICE copy with the gather kernel's access width; the

@@ -78,7 +78,7 @@ class OracleBlockPool:
 
     def alloc_prefer(self, preferred):
         """n blocks, all or nothing: preferred[i] itself wherever it is still free (the original GPU
-        block is claimed again when possible), a fresh block from the free list for the rest.  The
+        block is taken again where it still can be), a fresh block from the free list for the rest.  The
         preferred ids are claimed first, in order; the gaps are then filled in order.  An id that is
         out of range, taken, pending-free or named earlier in the call is simply no preference."""
         preferred = [int(b) for b in preferred]

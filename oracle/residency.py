@@ -4,7 +4,7 @@ Paper Sec. 6.3 ("CPU Migration Infrastructure"): the block pool owns the mapping
 blocks, CPU blocks and block hashes.  An offload links the GPU block to its CPU block, marks the
 KV cache CPU-resident and enters the block's hash in a CPU prefix-cache index; a later lookup that
 hits there saves the recomputation but leaves an H2D transfer entry that has to complete before
-the request runs; the upload restores the GPU mapping.
+the request runs; the upload puts the GPU mapping back.
 
 The paper names no hash function and no index structure.  Readings taken here:
   * hashes are opaque 64-bit keys to the index;

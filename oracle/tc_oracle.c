@@ -8,7 +8,7 @@
  *
  * What it defines (paper Sec. 6.3 "CPU Migration Infrastructure": KV migrates
  * between GPU blocks and CPU blocks, the pool owns the GPU<->CPU block mapping
- * and restores the GPU mapping on upload; Sec. 7.6: a block holds block_size
+ * and puts the GPU mapping back on upload; Sec. 7.6: a block holds block_size
  * tokens of every layer's K and V, e.g. 48 layers x {K,V} x 8 heads x 128 x
  * 16 tokens x 2 B = 3 MiB; Table 2: the Temporal Scheduler works at block
  * granularity).  The paper fixes no memory layout, so the layouts are this
@@ -119,7 +119,7 @@ int tco_upload(const uint8_t *host,
  * Bytes of logical token t of one agent in plane (layer, kv), read through the
  * agent's block table: block table[t / block_size], slot t % block_size, each
  * slot pb / block_size bytes ([block_size][kv_heads][head_dim] inside a page).
- * Used to state "the remapped table addresses the same logical tokens".
+ * Used to state that a table rewritten by an upload still addresses the same logical tokens.
  */
 int tco_read_token(const uint8_t *pool, uint32_t L, uint64_t NB, uint64_t pb,
                    uint32_t block_size, const int32_t *table, uint64_t t,

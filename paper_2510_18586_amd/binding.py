@@ -23,11 +23,17 @@ __all__ = [
     "tc_should_offload", "tc_upload_budget", "tc_gradual_reserve",
     "tc_req_state", "tc_lifecycle_step", "tc_forecaster_create", "tc_forecaster_destroy",
     "tc_forecaster_observe", "tc_forecaster_estimate",
+    "tc_alloc_prefer", "TC_RES_ABSENT", "TC_RES_CPU", "TC_RES_H2D", "TC_FNV_BASIS", "tc_index_hit",
+    "tc_index_create", "tc_index_destroy", "tc_index_insert", "tc_index_lookup", "tc_index_begin_upload",
+    "tc_index_finish_upload", "tc_index_remove", "tc_index_pending", "tc_index_size",
+    "tc_fnv1a64", "tc_chain_hashes",
 ]
 
 TC_OK = 0
 TC_ERR_INVAL, TC_ERR_RANGE, TC_ERR_DUP, TC_ERR_SHARED = -1, -2, -3, -4
 TC_ERR_NOMEM, TC_ERR_HOST_NOMEM, TC_ERR_NOT_PINNED, TC_ERR_HIP = -5, -6, -7, -8
+TC_RES_ABSENT, TC_RES_CPU, TC_RES_H2D = 0, 1, 2
+TC_FNV_BASIS = 0xCBF29CE484222325
 
 
 class tc_pool_desc(ctypes.Structure):
@@ -98,6 +104,14 @@ class tc_req_state(ctypes.Structure):
         return (self.state, bool(self.finish_seen), bool(self.copy_in_flight))
 
 
+class tc_index_hit(ctypes.Structure):
+    _fields_ = [("key", ctypes.c_uint64), ("cpu_record", ctypes.c_void_p),
+                ("gpu_block", ctypes.c_int32), ("state", ctypes.c_int32)]
+
+    def as_tuple(self):
+        return (self.key, self.state, self.cpu_record or 0, self.gpu_block)
+
+
 class TcError(RuntimeError):
     def __init__(self, code):
         super().__init__(f"tokencake_kv error {code}: {tc_strerror(code)}")
@@ -166,6 +180,18 @@ def _load():
         "tc_forecaster_destroy": (ci, [vp]),
         "tc_forecaster_observe": (ci, [vp, u32, ctypes.c_double]),
         "tc_forecaster_estimate": (ctypes.c_double, [vp, u32, ci, ctypes.c_double]),
+        "tc_alloc_prefer": (ci, [vp, vp, u32, vp]),
+        "tc_index_create": (ci, [ctypes.POINTER(vp)]),
+        "tc_index_destroy": (ci, [vp]),
+        "tc_index_insert": (ci, [vp, vp, vp, vp, u64, u32]),
+        "tc_index_lookup": (ci, [vp, vp, u32, ctypes.POINTER(tc_index_hit), ctypes.POINTER(u32)]),
+        "tc_index_begin_upload": (ci, [vp, vp, vp, u32]),
+        "tc_index_finish_upload": (ci, [vp, vp, u32]),
+        "tc_index_remove": (ci, [vp, vp, u32]),
+        "tc_index_pending": (u32, [vp, vp, u32]),
+        "tc_index_size": (u64, [vp]),
+        "tc_fnv1a64": (u64, [vp, u64, u64]),
+        "tc_chain_hashes": (ci, [vp, u64, u32, u64, vp, ctypes.POINTER(u64)]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -237,6 +263,14 @@ def tc_alloc(ctx, n):
 def tc_alloc_at(ctx, ids):
     a, p, n = _ids(ids)
     return _load().tc_alloc_at(ctx, p, n)
+
+
+def tc_alloc_prefer(ctx, preferred):
+    """Returns (rc, ids): preferred[i] where still free, a fresh block otherwise (empty on failure)."""
+    a, p, n = _ids(preferred)
+    out = np.empty(n, dtype=np.int32)
+    rc = _load().tc_alloc_prefer(ctx, p, n, out.ctypes.data if n else None)
+    return rc, (out if rc == TC_OK else out[:0])
 
 
 def tc_ref(ctx, ids):
@@ -406,3 +440,78 @@ def tc_forecaster_observe(f, fn_type, elapsed_ms):
 
 def tc_forecaster_estimate(f, fn_type, t_user_ms=None):
     return float(_load().tc_forecaster_estimate(f, fn_type, int(t_user_ms is not None), t_user_ms or 0.0))
+
+
+def _keys(keys):
+    a = np.ascontiguousarray(keys, dtype=np.uint64)
+    return a, (a.ctypes.data if a.size else None), int(a.size)
+
+
+def tc_index_create():
+    """Returns (rc, handle)."""
+    out = ctypes.c_void_p()
+    rc = _load().tc_index_create(ctypes.byref(out))
+    return rc, out.value
+
+
+def tc_index_destroy(ix):
+    return _load().tc_index_destroy(ix)
+
+
+def tc_index_insert(ix, keys, gpu_blocks, host_buf, record_bytes):
+    k, kp, n = _keys(keys)
+    a, ap, m = _ids(gpu_blocks)
+    if m != n:
+        return TC_ERR_INVAL
+    return _load().tc_index_insert(ix, kp, ap, _ptr(host_buf), record_bytes, n)
+
+
+def tc_index_lookup(ix, keys):
+    """Returns (rc, hits): hits is a list of (key, state, cpu_record, gpu_block) for the leading run present."""
+    k, kp, n = _keys(keys)
+    out = (tc_index_hit * max(n, 1))()
+    hits = ctypes.c_uint32(0)
+    rc = _load().tc_index_lookup(ix, kp, n, out, ctypes.byref(hits))
+    return rc, [out[i].as_tuple() for i in range(hits.value)]
+
+
+def tc_index_begin_upload(ix, keys, new_gpu_blocks):
+    k, kp, n = _keys(keys)
+    a, ap, m = _ids(new_gpu_blocks)
+    if m != n:
+        return TC_ERR_INVAL
+    return _load().tc_index_begin_upload(ix, kp, ap, n)
+
+
+def tc_index_finish_upload(ix, keys):
+    k, kp, n = _keys(keys)
+    return _load().tc_index_finish_upload(ix, kp, n)
+
+
+def tc_index_remove(ix, keys):
+    k, kp, n = _keys(keys)
+    return _load().tc_index_remove(ix, kp, n)
+
+
+def tc_index_pending(ix, keys):
+    k, kp, n = _keys(keys)
+    return int(_load().tc_index_pending(ix, kp, n))
+
+
+def tc_index_size(ix):
+    return int(_load().tc_index_size(ix))
+
+
+def tc_fnv1a64(data, basis=TC_FNV_BASIS):
+    b = bytes(data)
+    return int(_load().tc_fnv1a64(ctypes.cast(ctypes.c_char_p(b), ctypes.c_void_p), len(b), basis))
+
+
+def tc_chain_hashes(tokens, block_size, parent=0):
+    """Returns (rc, keys) with keys a uint64 numpy array, one per whole block."""
+    t = np.ascontiguousarray(tokens, dtype=np.int32)
+    out = np.empty(int(t.size) // block_size if block_size else 0, dtype=np.uint64)
+    n_out = ctypes.c_uint64(0)
+    rc = _load().tc_chain_hashes(t.ctypes.data if t.size else None, int(t.size), block_size, parent,
+                                 out.ctypes.data if out.size else None, ctypes.byref(n_out))
+    return rc, out[: n_out.value]

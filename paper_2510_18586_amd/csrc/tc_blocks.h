@@ -63,6 +63,32 @@ public:
         return TC_OK;
     }
 
+    // n blocks, all or nothing: preferred[i] itself where it is still on the free list (the original
+    // GPU block is taken again where it still can be, Sec. 6.3), a fresh block otherwise.  All claims happen
+    // before the first fresh block is popped, so a pop can never take a block a later entry asks for.
+    int alloc_prefer(const int32_t *preferred, uint32_t n, int32_t *out)
+    {
+        if (n > n_free_) return TC_ERR_NOMEM;
+        for (uint32_t i = 0; i < n; ++i) {
+            int32_t b = preferred[i];
+            if (b >= 0 && uint32_t(b) < nb_ && state_[b] == kFree) {
+                unlink(b);
+                take(b);
+                out[i] = b;
+            } else {
+                out[i] = -1;
+            }
+        }
+        for (uint32_t i = 0; i < n; ++i) {
+            if (out[i] >= 0) continue;
+            int32_t b = head_;
+            unlink(b);
+            take(b);
+            out[i] = b;
+        }
+        return TC_OK;
+    }
+
     int ref(const int32_t *ids, uint32_t n)
     {
         if (int rc = check_range(ids, n)) return rc;

@@ -703,6 +703,15 @@ int tc_alloc_at(tc_ctx *ctx, const int32_t *ids, uint32_t n)
     return rc;
 }
 
+int tc_alloc_prefer(tc_ctx *ctx, const int32_t *preferred, uint32_t n, int32_t *out_ids)
+{
+    if (!ctx || (n && (!preferred || !out_ids))) return TC_ERR_INVAL;
+    std::lock_guard<std::mutex> g(ctx->mu);
+    // retire what has finished first: an original block may be pending-free behind a completed copy
+    if (ctx->blocks->n_pending()) (void)poll_locked(ctx);
+    return ctx->blocks->alloc_prefer(preferred, n, out_ids);
+}
+
 int tc_ref(tc_ctx *ctx, const int32_t *ids, uint32_t n)
 {
     if (!ctx || (n && !ids)) return TC_ERR_INVAL;

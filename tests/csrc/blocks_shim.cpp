@@ -7,6 +7,7 @@ void *tcb_pool_new(uint32_t nb) { return new tc::BlockPool(nb); }
 void tcb_pool_del(void *p) { delete static_cast<tc::BlockPool *>(p); }
 int tcb_alloc(void *p, uint32_t n, int32_t *out) { return static_cast<tc::BlockPool *>(p)->alloc(n, out); }
 int tcb_alloc_at(void *p, const int32_t *ids, uint32_t n) { return static_cast<tc::BlockPool *>(p)->alloc_at(ids, n); }
+int tcb_alloc_prefer(void *p, const int32_t *pref, uint32_t n, int32_t *out) { return static_cast<tc::BlockPool *>(p)->alloc_prefer(pref, n, out); }
 int tcb_ref(void *p, const int32_t *ids, uint32_t n) { return static_cast<tc::BlockPool *>(p)->ref(ids, n); }
 int tcb_free(void *p, const int32_t *ids, uint32_t n) { return static_cast<tc::BlockPool *>(p)->free(ids, n); }
 int tcb_check_transfer(void *p, const int32_t *ids, uint32_t n) { return static_cast<tc::BlockPool *>(p)->check_transfer(ids, n); }

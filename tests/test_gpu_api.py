@@ -93,8 +93,15 @@ def test_pending_free_blocks_are_not_handed_out_while_the_copy_runs():
         # the copy was enqueued microseconds ago and takes milliseconds
         assert K.tc_alloc(gp.ctx, 1)[0] == K.TC_ERR_NOMEM
         assert K.tc_alloc_at(gp.ctx, move[:1]) == K.TC_ERR_NOMEM
+        assert K.tc_alloc_prefer(gp.ctx, move[:1])[0] == K.TC_ERR_NOMEM
         stream.synchronize()
         model.retire_all()
+        # the finished transfer is retired by the call itself, so the original blocks can be claimed again
+        want = [int(move[3]), -1, int(ids[299]), int(move[0])]
+        rc, got = K.tc_alloc_prefer(gp.ctx, want)
+        assert rc == 0 and list(got) == model.alloc_prefer(want) and got[0] == move[3] and got[3] == move[0]
+        K.check(K.tc_free(gp.ctx, got))
+        model.free(list(got))
         rc, again = K.tc_alloc(gp.ctx, n)      # retires the finished transfer itself
         assert rc == 0 and list(again) == model.alloc(n)
         assert _stats(gp).gpu_blocks_pending_free == 0

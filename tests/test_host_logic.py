@@ -35,6 +35,7 @@ def shim(tmp_path_factory):
     for f in ("tcb_alloc_at", "tcb_ref", "tcb_free", "tcb_check_transfer", "tcb_begin", "tcb_end"):
         getattr(lib, f).argtypes = [vp, vp, u32]
     lib.tcb_alloc.argtypes = [vp, u32, vp]
+    lib.tcb_alloc_prefer.argtypes = [vp, vp, u32, vp]
     lib.tcb_filter_private.argtypes = [vp, vp, u32, vp, ctypes.POINTER(u32)]
     lib.tcb_counts.argtypes = [vp, vp]
     lib.tcb_arena_new.restype, lib.tcb_arena_new.argtypes = vp, [u64]
@@ -68,6 +69,12 @@ class NativePool:
         out = np.empty(max(n, 1), dtype=np.int32)
         rc = self.lib.tcb_alloc(self.p, n, out.ctypes.data)
         return rc, list(out[:n]) if rc == 0 else []
+
+    def alloc_prefer(self, pref):
+        a, p, n = self._a(pref)
+        out = np.empty(max(n, 1), dtype=np.int32)
+        rc = self.lib.tcb_alloc_prefer(self.p, p, n, out.ctypes.data)
+        return rc, [int(x) for x in out[:n]] if rc == 0 else []
 
     def counts(self):
         c = np.zeros(4, dtype=np.uint32)
@@ -103,6 +110,19 @@ def test_hand_worked_sequence_matches_oracle(shim):
     orc.free([0, 2])
     assert nat.alloc(3)[1] == orc.alloc(3) == [2, 0, 4]
     assert nat.alloc(4)[0] == CODE["NOMEM"]
+    _same_counts(nat, orc)
+
+
+def test_alloc_prefer_hand_worked_matches_oracle(shim):
+    nat, orc = NativePool(shim, 8), OracleBlockPool(8)
+    nat.alloc(8), orc.alloc(8)
+    nat.call("tcb_free", [5, 2, 7]), orc.free([5, 2, 7])
+    assert nat.alloc_prefer([2, 4, 5]) == (0, orc.alloc_prefer([2, 4, 5])) == (0, [2, 7, 5])
+    assert nat.alloc_prefer([1])[0] == _oracle_rc(orc.alloc_prefer, [1])[0] == CODE["NOMEM"]
+    # a block that is pending-free behind a running copy is not claimed
+    nat.call("tcb_begin", [2, 7]), orc.begin_op([2, 7])
+    nat.call("tcb_free", [2, 7, 5]), orc.free([2, 7, 5])
+    assert nat.alloc_prefer([7])[1] == orc.alloc_prefer([7]) == [5]
     _same_counts(nat, orc)
 
 
@@ -147,7 +167,15 @@ def test_random_op_stream_id_for_id(shim, seed):
             assert rc == rco
             if rc == 0:
                 held.append(ids)
-        elif r < 0.50 and held:
+        elif r < 0.45:
+            k = int(rng.integers(0, 9))
+            pref = [int(x) for x in rng.integers(-1, NB + 1, size=k)]      # repeats, held and bad ids included
+            rc, got = nat.alloc_prefer(pref)
+            rco, want = _oracle_rc(orc.alloc_prefer, pref)
+            assert rc == rco and (rc != 0 or got == want), pref
+            if rc == 0 and got:
+                held.append(got)
+        elif r < 0.52 and held:
             ids = held[int(rng.integers(len(held)))]
             assert nat.call("tcb_ref", ids) == 0
             orc.ref(ids)

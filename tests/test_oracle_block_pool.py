@@ -1,7 +1,7 @@
 """Pins for the oracle's bookkeeping model (no GPU).
 
 What the paper fixes (Sec. 6.3): a block released while a copy that reads it is in flight
-is *pending-free* and returns to the free pool only after the transfer completes; CPU
+is *pending-free* and goes back on the free list no earlier than the end of that copy; CPU
 blocks are recycled through a free list; the original GPU block can be claimed again.
 The rest are conservation laws checked against plain sets under seeded random op streams,
 plus hand-worked examples of the LIFO order this build chose.
@@ -201,7 +201,7 @@ def test_host_arena_random_ops_no_overlap():
         assert ar.used_slots() + sum(l for _, l in ar.free_runs) == N
 
 
-# ---- alloc_prefer: "reuses the original GPU block when possible" (Sec. 6.3) ------------------------
+# ---- alloc_prefer: an upload takes its original GPU blocks again where it still can (Sec. 6.3) ----
 
 def test_alloc_prefer_hand_worked():
     bp = OracleBlockPool(8)
