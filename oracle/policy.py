@@ -7,11 +7,18 @@ Plain Python written from the paper's statements, in the paper's notation:
 * ShouldOffload (Sec. 4.2, Alg. 1): reject when T_fc <= T_transfer; otherwise T_window = T_fc -
   T_transfer, N_capacity = T_window * v_throughput, and the first request in queue order whose
   incremental KV demand fits the freed blocks and whose work fits N_capacity decides;
-* upload budget (Sec. 4.3, Eq. 3) and gradual reservation (Sec. 4.3, Eq. 4).
+* upload budget (Sec. 4.3, Eq. 3) and gradual reservation (Sec. 4.3, Eq. 4);
+* the hard rejections that come before any scoring (Sec. 4.2): not enough CPU capacity, a stall
+  shorter than the transfer, no waiting request that fits, GPU memory pressure under a threshold;
+* one scheduling step of predictive upload (Sec. 4.3): candidates ranked by P_upload = I + U, the
+  step's budget from Eq. 3, each candidate's reservation from Eq. 4 in rank order.
 
 Readings where the paper is silent: the linear terms are fitted by ordinary least squares; a waiting
 request is the pair (kv_blocks, work_tokens); in Eq. 4 B_remain is what is left of this step's budget
-after higher-ranked candidates, B_deficit the candidate's blocks still missing.
+after higher-ranked candidates, B_deficit the candidate's blocks still missing.  The hard rejections
+are tested in the order the paper lists them and the first that applies is the reason; pressure is
+used / total blocks and "below" is strict.  I and U are inputs (the paper gives no formula for U);
+equal P_upload: the more urgent candidate first, then the one named first.
 """
 import math
 
@@ -61,3 +68,37 @@ def upload_budget(b_gpu_free, d_critical, b_shared_free):
 def gradual_reserve(b_remain, b_deficit, b_upload):
     """Eq. 4."""
     return min(b_remain, -(-b_deficit // 2), b_upload)
+
+
+PASS, CPU_FULL, STALL_SHORT, NO_FIT, LOW_PRESSURE = 0, 1, 2, 3, 4
+
+
+def offload_gate(model, req_blocks, cpu_free_blocks, gpu_used_blocks, gpu_total_blocks, pressure_threshold,
+                 t_fc_ms, v_throughput_tokens_per_ms, waiting):
+    """The four hard rejections of Sec. 4.2.  Returns (reason, index of the waiting request that fits or -1);
+    reason PASS means the offload may go on to be scored / issued."""
+    if cpu_free_blocks < req_blocks:
+        return CPU_FULL, -1
+    if t_fc_ms <= estimate_transfer_ms(model, req_blocks):
+        return STALL_SHORT, -1
+    ok, k = should_offload(model, req_blocks, t_fc_ms, v_throughput_tokens_per_ms, waiting)
+    if not ok:
+        return NO_FIT, -1
+    if gpu_used_blocks / gpu_total_blocks < pressure_threshold:
+        return LOW_PRESSURE, -1
+    return PASS, k
+
+
+def upload_plan(candidates, b_gpu_free, d_critical, b_shared_free):
+    """One scheduling step of predictive upload.  candidates = [(importance, urgency, deficit), ...].
+    Returns (order, reserve): candidate indices by falling P_upload = I + U, and the blocks to reserve
+    for each candidate this step (indexed like `candidates`)."""
+    b_upload = upload_budget(b_gpu_free, d_critical, b_shared_free)
+    order = sorted(range(len(candidates)),
+                   key=lambda i: (-(candidates[i][0] + candidates[i][1]), -candidates[i][1], i))
+    reserve = [0] * len(candidates)
+    b_remain = b_upload
+    for i in order:
+        reserve[i] = gradual_reserve(b_remain, candidates[i][2], b_upload)
+        b_remain -= reserve[i]
+    return order, reserve

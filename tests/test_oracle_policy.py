@@ -98,3 +98,79 @@ def test_upload_budget_and_gradual_reserve():
             left -= r
             steps += 1
         assert steps == int(np.ceil(np.log2(d + 1)))
+
+
+# ---- hard rejections (Sec. 4.2) and one step of predictive upload (Sec. 4.3) --------------------------
+
+def test_offload_gate_hand_worked():
+    m = (0.0, 0.1, 0.0, 0.1)                  # 0.2 ms per block both ways: 100 blocks cost 20 ms
+    q = [(150, 10.0), (80, 50.0)]             # the first never fits 100 freed blocks
+    args = dict(req_blocks=100, cpu_free_blocks=100, gpu_used_blocks=90, gpu_total_blocks=100,
+                pressure_threshold=0.8, t_fc_ms=50.0, v_throughput_tokens_per_ms=2.0, waiting=q)
+    assert policy.offload_gate(m, **args) == (policy.PASS, 1)          # window 30 ms -> 60 tokens >= 50
+    assert policy.offload_gate(m, **{**args, "cpu_free_blocks": 99}) == (policy.CPU_FULL, -1)
+    assert policy.offload_gate(m, **{**args, "t_fc_ms": 20.0}) == (policy.STALL_SHORT, -1)
+    assert policy.offload_gate(m, **{**args, "t_fc_ms": 44.0}) == (policy.NO_FIT, -1)     # 48 tokens < 50
+    assert policy.offload_gate(m, **{**args, "gpu_used_blocks": 79}) == (policy.LOW_PRESSURE, -1)
+    assert policy.offload_gate(m, **{**args, "gpu_used_blocks": 80}) == (policy.PASS, 1)  # "below" is strict
+    # several reasons at once: the first in the paper's order is reported
+    assert policy.offload_gate(m, **{**args, "cpu_free_blocks": 0, "t_fc_ms": 1.0, "gpu_used_blocks": 0})[0] == policy.CPU_FULL
+    assert policy.offload_gate(m, **{**args, "t_fc_ms": 1.0, "gpu_used_blocks": 0})[0] == policy.STALL_SHORT
+    assert policy.offload_gate(m, **{**args, "waiting": [], "gpu_used_blocks": 0})[0] == policy.NO_FIT
+
+
+def test_offload_gate_is_alg1_plus_two_independent_conditions():
+    rng = np.random.default_rng(8)
+    for _ in range(2000):
+        m = tuple(float(x) for x in rng.uniform(0, 0.2, size=4))
+        q = [(int(rng.integers(1, 200)), float(rng.uniform(0, 400))) for _ in range(int(rng.integers(0, 5)))]
+        req, cpu = int(rng.integers(1, 200)), int(rng.integers(0, 250))
+        used, thr = int(rng.integers(0, 101)), float(rng.choice([0.0, 0.5, 0.8, 1.0]))
+        t_fc, v = float(rng.uniform(0, 120)), float(rng.uniform(0.5, 4))
+        reason, k = policy.offload_gate(m, req, cpu, used, 100, thr, t_fc, v, q)
+        alg1 = policy.should_offload(m, req, t_fc, v, q)
+        passes = cpu >= req and alg1[0] and used >= thr * 100
+        assert (reason == policy.PASS) == passes
+        assert k == (alg1[1] if passes else -1)
+        if reason in (policy.STALL_SHORT, policy.NO_FIT):
+            assert not alg1[0] and cpu >= req
+
+
+def test_upload_plan_hand_worked():
+    # budget: 40 free, critical demand 30 of which 10 fit the shared pool -> 40 - 20 = 20 blocks
+    cands = [(0.2, 0.1, 16),      # P = 0.3                    rank 2
+             (0.9, 0.5, 10),      # P = 1.4                    rank 0
+             (0.1, 0.9, 31)]      # P = 1.0                    rank 1
+    order, reserve = policy.upload_plan(cands, 40, 30, 10)
+    assert order == [1, 2, 0]
+    # rank 0: min(20, ceil(10/2)=5, 20) = 5; rank 1: min(15, 16, 20) = 15; rank 2: min(0, 8, 20) = 0
+    assert reserve == [0, 5, 15]
+    # equal P: the more urgent first, then the one named first
+    assert policy.upload_plan([(0.5, 0.5, 4), (0.2, 0.8, 4), (0.5, 0.5, 4)], 100, 0, 0)[0] == [1, 0, 2]
+    assert policy.upload_plan([], 10, 0, 0) == ([], [])
+    assert policy.upload_plan([(1.0, 1.0, 9)], 3, 50, 0) == ([0], [0])     # critical demand eats the budget
+
+
+def test_upload_plan_properties():
+    rng = np.random.default_rng(4)
+    for _ in range(1000):
+        n = int(rng.integers(0, 8))
+        cands = [(float(rng.choice([0.0, 0.25, 0.5, 1.0])), float(rng.choice([0.0, 0.25, 0.5, 1.0])), int(rng.integers(0, 40)))
+                 for _ in range(n)]
+        free, crit, shared = (int(x) for x in rng.integers(0, 60, size=3))
+        order, reserve = policy.upload_plan(cands, free, crit, shared)
+        budget = policy.upload_budget(free, crit, shared)
+        assert sorted(order) == list(range(n))
+        p = [cands[i][0] + cands[i][1] for i in order]
+        assert all(a >= b for a, b in zip(p, p[1:]))                       # higher priority first
+        assert sum(reserve) <= budget and all(r <= -(-c[2] // 2) for r, c in zip(reserve, cands))
+        # greedy in rank order: a candidate gets less than half its deficit only when the budget ran out
+        left = budget
+        for i in order:
+            assert reserve[i] == min(left, -(-cands[i][2] // 2))
+            left -= reserve[i]
+        # the answer does not depend on how the candidates are listed, ties aside
+        if len(set(p)) == n:
+            perm = [int(x) for x in rng.permutation(n)]
+            o2, r2 = policy.upload_plan([cands[j] for j in perm], free, crit, shared)
+            assert [perm[j] for j in o2] == order and [r2[perm.index(i)] for i in range(n)] == reserve

@@ -30,6 +30,16 @@ CASES = {
                                                    "return max(0, b_gpu_free - (d_critical - b_shared_free))"),
         "half of the deficit rounds down": ("-(-b_deficit // 2)", "b_deficit // 2"),
         "the fit's slope is inverted": ("b = sxy / sxx", "b = sxx / sxy"),
+        "the gate forgets the CPU capacity": ("    if cpu_free_blocks < req_blocks:\n        return CPU_FULL, -1\n", ""),
+        "the gate reports the pressure before the fit": ("    ok, k = should_offload(model, req_blocks, t_fc_ms, v_throughput_tokens_per_ms, waiting)\n    if not ok:\n        return NO_FIT, -1\n    if gpu_used_blocks / gpu_total_blocks < pressure_threshold:\n        return LOW_PRESSURE, -1\n",
+                                                         "    if gpu_used_blocks / gpu_total_blocks < pressure_threshold:\n        return LOW_PRESSURE, -1\n    ok, k = should_offload(model, req_blocks, t_fc_ms, v_throughput_tokens_per_ms, waiting)\n    if not ok:\n        return NO_FIT, -1\n"),
+        "pressure at the threshold is rejected": ("if gpu_used_blocks / gpu_total_blocks < pressure_threshold:", "if gpu_used_blocks / gpu_total_blocks <= pressure_threshold:"),
+        "a short stall is reported as no fit": ("    if t_fc_ms <= estimate_transfer_ms(model, req_blocks):\n        return STALL_SHORT, -1\n", ""),
+        "uploads ranked by importance alone": ("key=lambda i: (-(candidates[i][0] + candidates[i][1]), -candidates[i][1], i))", "key=lambda i: (-candidates[i][0], -candidates[i][1], i))"),
+        "lowest priority uploads first": ("key=lambda i: (-(candidates[i][0] + candidates[i][1]), -candidates[i][1], i))", "key=lambda i: ((candidates[i][0] + candidates[i][1]), -candidates[i][1], i))"),
+        "ties go to the less urgent": ("key=lambda i: (-(candidates[i][0] + candidates[i][1]), -candidates[i][1], i))", "key=lambda i: (-(candidates[i][0] + candidates[i][1]), candidates[i][1], i))"),
+        "every candidate sees the whole budget": ("        b_remain -= reserve[i]\n", ""),
+        "the plan ignores the critical demand": ("    b_upload = upload_budget(b_gpu_free, d_critical, b_shared_free)\n    order", "    b_upload = b_gpu_free\n    order"),
     },
     ("lifecycle.py", pins_life, ("L",)): {
         "uploaded + call_finish waits instead of resuming": ("return (RUNNING, False, False), RESUME          # already back", "return (UPLOADED, True, False), WAIT  #"),
