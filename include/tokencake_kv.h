@@ -226,6 +226,41 @@ uint32_t tc_upload_budget(uint32_t gpu_free, uint32_t d_critical, uint32_t share
 /* Eq. 4: blocks to reserve for one candidate this step: min(remain, ceil(deficit / 2), budget). */
 uint32_t tc_gradual_reserve(uint32_t remain, uint32_t deficit, uint32_t budget);
 
+/* Sec. 4.2: four hard rejections come before any scoring of an offload: not enough CPU capacity,
+ * a predicted stall no longer than the transfer, no waiting request that fits (Alg. 1), GPU memory
+ * pressure under a configurable threshold.  They are tested in that order and the first that applies
+ * is reported.  Pressure is gpu_used_blocks / gpu_total_blocks; "under" is strict. */
+enum { TC_GATE_PASS = 0, TC_GATE_CPU_FULL = 1, TC_GATE_STALL_SHORT = 2, TC_GATE_NO_FIT = 3, TC_GATE_LOW_PRESSURE = 4 };
+typedef struct {
+    uint32_t req_blocks;        /* blocks the offload would free = CPU records it needs */
+    uint32_t cpu_free_blocks;   /* free CPU records                                     */
+    uint32_t gpu_used_blocks, gpu_total_blocks;
+    double pressure_threshold;
+    double t_fc_ms;             /* predicted stall                                      */
+    double v_throughput_tokens_per_ms;
+} tc_gate_input;
+/* Returns 1 = none applies (*reason = TC_GATE_PASS, *chosen = the waiting request that fits),
+ * 0 = rejected (*reason says why, *chosen = -1), TC_ERR_INVAL for NULL, NaN or gpu_total_blocks = 0.
+ * chosen may be NULL.  The composite score that the paper applies afterwards has no published
+ * weights and is not part of this library. */
+int tc_offload_gate(const tc_cost_model *model, const tc_gate_input *in, const tc_waiting_req *queue,
+                    uint32_t n_queue, int32_t *chosen, int *reason);
+
+/* Sec. 4.3, one scheduling step of predictive upload: candidates are ranked by P_upload = I + U
+ * (importance from the spatial scheduler's metric and urgency towards the predicted end of the call,
+ * both supplied by the caller), the step's budget is Eq. 3, and each candidate in rank order reserves
+ * Eq. 4's min(B_remain, ceil(B_deficit / 2), B_upload), B_remain shrinking as it goes.  Equal
+ * P_upload: the more urgent candidate first, then the one listed first. */
+typedef struct {
+    double importance;   /* I */
+    double urgency;      /* U */
+    uint32_t deficit;    /* destination blocks this candidate still lacks */
+} tc_upload_cand;
+/* order[r] = index of the candidate of rank r; reserve[i] = blocks to reserve now for candidate i.
+ * Both HOST arrays of n entries.  TC_ERR_INVAL for NULL or a NaN; nothing written then. */
+int tc_upload_plan(const tc_upload_cand *cands, uint32_t n, uint32_t gpu_free, uint32_t d_critical,
+                   uint32_t shared_free, uint32_t *order, uint32_t *reserve);
+
 /* ---- request lifecycle and call-duration forecast (host only; Sec. 6.2, Sec. 4.1) -------- */
 /* The five states of Sec. 6.2. */
 enum { TC_RUNNING = 0, TC_PENDING_OFFLOAD = 1, TC_OFFLOADED = 2, TC_PENDING_UPLOAD = 3, TC_UPLOADED = 4 };

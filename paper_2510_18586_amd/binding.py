@@ -27,6 +27,8 @@ __all__ = [
     "tc_index_create", "tc_index_destroy", "tc_index_insert", "tc_index_lookup", "tc_index_begin_upload",
     "tc_index_finish_upload", "tc_index_remove", "tc_index_pending", "tc_index_size",
     "tc_fnv1a64", "tc_chain_hashes",
+    "TC_GATE_PASS", "TC_GATE_CPU_FULL", "TC_GATE_STALL_SHORT", "TC_GATE_NO_FIT", "TC_GATE_LOW_PRESSURE",
+    "tc_gate_input", "tc_upload_cand", "tc_offload_gate", "tc_upload_plan",
 ]
 
 TC_OK = 0
@@ -34,6 +36,7 @@ TC_ERR_INVAL, TC_ERR_RANGE, TC_ERR_DUP, TC_ERR_SHARED = -1, -2, -3, -4
 TC_ERR_NOMEM, TC_ERR_HOST_NOMEM, TC_ERR_NOT_PINNED, TC_ERR_HIP = -5, -6, -7, -8
 TC_RES_ABSENT, TC_RES_CPU, TC_RES_H2D = 0, 1, 2
 TC_FNV_BASIS = 0xCBF29CE484222325
+TC_GATE_PASS, TC_GATE_CPU_FULL, TC_GATE_STALL_SHORT, TC_GATE_NO_FIT, TC_GATE_LOW_PRESSURE = 0, 1, 2, 3, 4
 
 
 class tc_pool_desc(ctypes.Structure):
@@ -102,6 +105,17 @@ class tc_req_state(ctypes.Structure):
 
     def as_tuple(self):
         return (self.state, bool(self.finish_seen), bool(self.copy_in_flight))
+
+
+class tc_gate_input(ctypes.Structure):
+    _fields_ = [("req_blocks", ctypes.c_uint32), ("cpu_free_blocks", ctypes.c_uint32),
+                ("gpu_used_blocks", ctypes.c_uint32), ("gpu_total_blocks", ctypes.c_uint32),
+                ("pressure_threshold", ctypes.c_double), ("t_fc_ms", ctypes.c_double),
+                ("v_throughput_tokens_per_ms", ctypes.c_double)]
+
+
+class tc_upload_cand(ctypes.Structure):
+    _fields_ = [("importance", ctypes.c_double), ("urgency", ctypes.c_double), ("deficit", ctypes.c_uint32)]
 
 
 class tc_index_hit(ctypes.Structure):
@@ -181,6 +195,10 @@ def _load():
         "tc_forecaster_observe": (ci, [vp, u32, ctypes.c_double]),
         "tc_forecaster_estimate": (ctypes.c_double, [vp, u32, ci, ctypes.c_double]),
         "tc_alloc_prefer": (ci, [vp, vp, u32, vp]),
+        "tc_offload_gate": (ci, [ctypes.POINTER(tc_cost_model), ctypes.POINTER(tc_gate_input),
+                                 ctypes.POINTER(tc_waiting_req), u32, ctypes.POINTER(ctypes.c_int32),
+                                 ctypes.POINTER(ci)]),
+        "tc_upload_plan": (ci, [ctypes.POINTER(tc_upload_cand), u32, u32, u32, u32, vp, vp]),
         "tc_index_create": (ci, [ctypes.POINTER(vp)]),
         "tc_index_destroy": (ci, [vp]),
         "tc_index_insert": (ci, [vp, vp, vp, vp, u64, u32]),
@@ -406,6 +424,32 @@ def tc_should_offload(model, req_blocks, t_fc_ms, v_throughput_tokens_per_ms, wa
     rc = _load().tc_should_offload(ctypes.byref(_model(model)), req_blocks, t_fc_ms, v_throughput_tokens_per_ms,
                                    q, len(waiting), ctypes.byref(chosen))
     return rc, chosen.value
+
+
+def tc_offload_gate(model, req_blocks, cpu_free_blocks, gpu_used_blocks, gpu_total_blocks, pressure_threshold,
+                    t_fc_ms, v_throughput_tokens_per_ms, waiting):
+    """Returns (rc, reason, chosen index): rc 1 = no hard rejection applies, 0 = rejected for `reason`."""
+    q = (tc_waiting_req * max(len(waiting), 1))()
+    for i, (b, w) in enumerate(waiting):
+        q[i] = tc_waiting_req(int(b), float(w))
+    gi = tc_gate_input(req_blocks, cpu_free_blocks, gpu_used_blocks, gpu_total_blocks, pressure_threshold,
+                       t_fc_ms, v_throughput_tokens_per_ms)
+    chosen, reason = ctypes.c_int32(-1), ctypes.c_int(-1)
+    rc = _load().tc_offload_gate(ctypes.byref(_model(model)), ctypes.byref(gi), q, len(waiting),
+                                 ctypes.byref(chosen), ctypes.byref(reason))
+    return rc, reason.value, chosen.value
+
+
+def tc_upload_plan(candidates, gpu_free, d_critical, shared_free):
+    """candidates: sequence of (importance, urgency, deficit).  Returns (rc, order, reserve) as lists."""
+    n = len(candidates)
+    c = (tc_upload_cand * max(n, 1))()
+    for i, (imp, urg, d) in enumerate(candidates):
+        c[i] = tc_upload_cand(float(imp), float(urg), int(d))
+    order = np.zeros(max(n, 1), dtype=np.uint32)
+    reserve = np.zeros(max(n, 1), dtype=np.uint32)
+    rc = _load().tc_upload_plan(c, n, gpu_free, d_critical, shared_free, order.ctypes.data, reserve.ctypes.data)
+    return rc, [int(x) for x in order[:n]], [int(x) for x in reserve[:n]]
 
 
 def tc_upload_budget(gpu_free, d_critical, shared_free):

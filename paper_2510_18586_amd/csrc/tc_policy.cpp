@@ -1,7 +1,9 @@
 // Host-side scheduling arithmetic that consumes the copy path's measurements: the linear
 // transfer-cost model (paper Eq. 2), the ShouldOffload gate (Alg. 1), the upload budget (Eq. 3),
-// the gradual reservation (Eq. 4), the five-state request lifecycle (Sec. 6.2) and the call-duration
+// the gradual reservation (Eq. 4), the hard rejections ahead of the offload score (Sec. 4.2), one
+// scheduling step of predictive upload (Sec. 4.3), the five-state request lifecycle (Sec. 6.2) and the call-duration
 // forecast (Eq. 1).  No GPU work here; tc_calibrate lives in the engine.
+#include <algorithm>
 #include <cmath>
 #include <mutex>
 #include <new>
@@ -85,6 +87,60 @@ uint32_t tc_gradual_reserve(uint32_t remain, uint32_t deficit, uint32_t budget)
     if (remain < r) r = remain;
     if (budget < r) r = budget;
     return r;
+}
+
+int tc_offload_gate(const tc_cost_model *model, const tc_gate_input *in, const tc_waiting_req *queue,
+                    uint32_t n_queue, int32_t *chosen, int *reason)
+{
+    if (!model || !in || !reason || (n_queue && !queue) || in->gpu_total_blocks == 0) return TC_ERR_INVAL;
+    if (std::isnan(in->pressure_threshold) || std::isnan(in->t_fc_ms) || std::isnan(in->v_throughput_tokens_per_ms))
+        return TC_ERR_INVAL;
+    if (chosen) *chosen = -1;
+    // the four hard rejections, tested in the order Sec. 4.2 lists them
+    if (in->cpu_free_blocks < in->req_blocks) {
+        *reason = TC_GATE_CPU_FULL;
+        return 0;
+    }
+    if (in->t_fc_ms <= tc_estimate_transfer_ms(model, in->req_blocks)) {
+        *reason = TC_GATE_STALL_SHORT;
+        return 0;
+    }
+    int32_t k = -1;
+    if (tc_should_offload(model, in->req_blocks, in->t_fc_ms, in->v_throughput_tokens_per_ms, queue, n_queue, &k) != 1) {
+        *reason = TC_GATE_NO_FIT;
+        return 0;
+    }
+    if (double(in->gpu_used_blocks) / double(in->gpu_total_blocks) < in->pressure_threshold) {
+        *reason = TC_GATE_LOW_PRESSURE;
+        return 0;
+    }
+    *reason = TC_GATE_PASS;
+    if (chosen) *chosen = k;
+    return 1;
+}
+
+int tc_upload_plan(const tc_upload_cand *cands, uint32_t n, uint32_t gpu_free, uint32_t d_critical,
+                   uint32_t shared_free, uint32_t *order, uint32_t *reserve)
+{
+    if (n && (!cands || !order || !reserve)) return TC_ERR_INVAL;
+    for (uint32_t i = 0; i < n; ++i)
+        if (std::isnan(cands[i].importance) || std::isnan(cands[i].urgency)) return TC_ERR_INVAL;
+    for (uint32_t i = 0; i < n; ++i) order[i] = i;
+    // falling P_upload = I + U; equal P: the more urgent first, then the one named first
+    std::sort(order, order + n, [cands](uint32_t a, uint32_t b) {
+        const double pa = cands[a].importance + cands[a].urgency, pb = cands[b].importance + cands[b].urgency;
+        if (pa != pb) return pa > pb;
+        if (cands[a].urgency != cands[b].urgency) return cands[a].urgency > cands[b].urgency;
+        return a < b;
+    });
+    const uint32_t budget = tc_upload_budget(gpu_free, d_critical, shared_free);
+    uint32_t remain = budget;
+    for (uint32_t r = 0; r < n; ++r) {
+        const uint32_t i = order[r];
+        reserve[i] = tc_gradual_reserve(remain, cands[i].deficit, budget);
+        remain -= reserve[i];
+    }
+    return TC_OK;
 }
 
 int tc_lifecycle_step(tc_req_state *req, int event, int *action)

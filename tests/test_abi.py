@@ -43,6 +43,8 @@ def test_error_strings_and_struct_layout():
     assert ctypes.sizeof(K.tc_pool_desc) == 40
     assert ctypes.sizeof(K.tc_opts) == 40
     assert ctypes.sizeof(K.tc_xfer_desc) == 32
+    assert ctypes.sizeof(K.tc_gate_input) == 40 and ctypes.sizeof(K.tc_upload_cand) == 24
+    assert ctypes.sizeof(K.tc_index_hit) == 24
     assert ctypes.sizeof(K.tc_stats_t) == 24 + 16 + 48 + 32 + 16 + 24 + 48
 
 

@@ -1,5 +1,5 @@
-"""The pieces around the copy path working together on the GPU: forecast (Eq. 1) -> ShouldOffload
-(Alg. 1, with a cost model calibrated on this device, Eq. 2) -> offload -> gradual reservation
+"""The pieces around the copy path working together on the GPU: forecast (Eq. 1) -> hard rejections
+incl. ShouldOffload (Sec. 4.2, Alg. 1, with a cost model calibrated on this device, Eq. 2) -> offload -> gradual reservation
 (Eq. 4) with piecewise uploads -> lifecycle (Sec. 6.2) deciding resume / immediate upload.
 
 Every decision the library takes is compared with the oracle's on the spot; every agent that went
@@ -113,8 +113,12 @@ def test_temporal_loop_on_a_seeded_trace():
                 t_fc = K.tc_forecaster_estimate(fc, ftype, user)
                 assert t_fc == pytest.approx(fc_model.estimate(ftype, user), rel=1e-12)
                 queue = [(int(rng.integers(8, 400)), float(rng.uniform(100, 6000))) for _ in range(3)]
-                ok, pick = K.tc_should_offload(model, n, t_fc, v_tok_per_ms, queue)
-                assert (bool(ok), pick) == policy.should_offload(m, n, t_fc, v_tok_per_ms, queue)
+                st = K.tc_stats(gp.ctx)[1]
+                cpu_free = int(st.host_slots_total - st.host_slots_used)
+                gate = (n, cpu_free, pool_model.n_used(), gp.NB, 0.02, t_fc, v_tok_per_ms, queue)
+                ok, reason, pick = K.tc_offload_gate(model, *gate)
+                assert (reason, pick) == policy.offload_gate(m, *gate) and ok == int(reason == policy.PASS)
+                counts["reason_%d" % reason] = counts.get("reason_%d" % reason, 0) + 1
                 rc, buf = K.tc_host_alloc(gp.ctx, n) if ok else (K.TC_ERR_HOST_NOMEM, None)
                 if not ok or rc != 0:
                     counts["rejected"] += 1

@@ -66,6 +66,47 @@ def test_budget_and_gradual_reserve_match_oracle():
     assert K.tc_upload_budget(big, big, 0) == 0
 
 
+def test_offload_gate_matches_oracle():
+    rng = np.random.default_rng(12)
+    model = (0.05, 0.0374, 0.07, 0.0375)
+    seen = set()
+    for _ in range(4000):
+        req = int(rng.integers(0, 600))
+        cpu = int(rng.integers(0, 800))
+        total = int(rng.integers(1, 20000))
+        used = int(rng.integers(0, total + 1))
+        thr = float(rng.choice([0.0, 0.3, 0.5, used / total, 0.9, 1.0]))
+        queue = [(int(rng.integers(0, 700)), float(rng.uniform(0, 30000))) for _ in range(int(rng.integers(0, 6)))]
+        v = float(rng.uniform(0.1, 40))
+        t_fc = float(rng.choice([0.0, rng.uniform(0, 100), rng.uniform(0, 3000)]))
+        rc, reason, k = K.tc_offload_gate(model, req, cpu, used, total, thr, t_fc, v, queue)
+        want_reason, want_k = policy.offload_gate(model, req, cpu, used, total, thr, t_fc, v, queue)
+        assert (reason, k) == (want_reason, want_k) and rc == int(want_reason == policy.PASS)
+        seen.add(reason)
+    assert seen == {0, 1, 2, 3, 4}, "every outcome should occur"
+    assert (K.TC_GATE_PASS, K.TC_GATE_CPU_FULL, K.TC_GATE_STALL_SHORT, K.TC_GATE_NO_FIT, K.TC_GATE_LOW_PRESSURE) == \
+        (policy.PASS, policy.CPU_FULL, policy.STALL_SHORT, policy.NO_FIT, policy.LOW_PRESSURE)
+    assert K.tc_offload_gate(model, 1, 1, 0, 0, 0.5, 10.0, 1.0, [])[0] == K.TC_ERR_INVAL
+    assert K.tc_offload_gate(model, 1, 1, 0, 10, float("nan"), 10.0, 1.0, [])[0] == K.TC_ERR_INVAL
+
+
+def test_upload_plan_matches_oracle():
+    rng = np.random.default_rng(13)
+    for _ in range(3000):
+        n = int(rng.integers(0, 12))
+        grid = rng.random() < 0.5           # coarse values force equal priorities
+        cands = [((float(rng.integers(0, 5)) / 4 if grid else float(rng.random())),
+                  (float(rng.integers(0, 5)) / 4 if grid else float(rng.random())),
+                  int(rng.integers(0, 2000))) for _ in range(n)]
+        free, crit, shared = (int(x) for x in rng.integers(0, 3000, size=3))
+        rc, order, reserve = K.tc_upload_plan(cands, free, crit, shared)
+        assert rc == K.TC_OK and (order, reserve) == policy.upload_plan(cands, free, crit, shared)
+    big = 2**32 - 1
+    assert K.tc_upload_plan([(0.0, 0.0, big), (1.0, 0.0, big)], big, 0, 0) == (0, [1, 0], [2**31 - 1, 2**31]) == \
+        (0,) + policy.upload_plan([(0.0, 0.0, big), (1.0, 0.0, big)], big, 0, 0)
+    assert K.tc_upload_plan([(float("nan"), 0.0, 1)], 5, 0, 0)[0] == K.TC_ERR_INVAL
+
+
 def test_lifecycle_matches_oracle_on_every_state_and_event():
     from oracle import lifecycle as L
     for state in range(5):
