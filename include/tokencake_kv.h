@@ -22,7 +22,9 @@
  * Conventions
  *   - every function returns TC_OK (0) or a negative TC_ERR_* code; nothing throws
  *     or aborts.  All validation happens before anything is enqueued or any state
- *     changes: an error return means the call had no effect.
+ *     changes: an error return means the call had no effect.  No C++ exception
+ *     leaves the library; the process running out of host memory inside a call is
+ *     reported as TC_ERR_HOST_NOMEM.
  *   - id arrays are HOST pointers (int32) and are copied before the call returns.
  *   - tc_offload / tc_upload are asynchronous: they return after enqueueing on
  *     `stream` (a hipStream_t passed as void*; NULL = the default stream).  Work
@@ -51,7 +53,7 @@ extern "C" {
 #define TC_ERR_DUP (-3)        /* the same block id twice in one transfer            */
 #define TC_ERR_SHARED (-4)     /* block has more than one owner and must not move    */
 #define TC_ERR_NOMEM (-5)      /* not enough free GPU blocks (all-or-nothing)        */
-#define TC_ERR_HOST_NOMEM (-6) /* pinned arena has no run of slots that fits         */
+#define TC_ERR_HOST_NOMEM (-6) /* pinned arena has no run of slots that fits; host OOM */
 #define TC_ERR_NOT_PINNED (-7) /* host buffer is not pinned / device ptr is not device */
 #define TC_ERR_HIP (-8)        /* a HIP runtime call failed                          */
 

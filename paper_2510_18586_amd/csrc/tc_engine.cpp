@@ -561,10 +561,16 @@ void destroy_unlocked(tc_ctx *c)
 }  // namespace
 
 // ================================================================================= C ABI
+// No exception crosses the C boundary: running out of host memory inside a container is reported,
+// anything else unexpected is an invalid call.
+#define TC_CATCH_ALL                                              \
+    catch (const std::bad_alloc &) { return TC_ERR_HOST_NOMEM; } \
+    catch (...) { return TC_ERR_INVAL; }
+
 extern "C" {
 
 int tc_create(const tc_pool_desc *pool, const tc_opts *opts, tc_ctx **out)
-{
+try {
     if (!pool || !out) return TC_ERR_INVAL;
     *out = nullptr;
     if (!pool->kv_base || pool->num_layers == 0 || pool->num_blocks == 0 || pool->page_bytes == 0) return TC_ERR_INVAL;
@@ -579,7 +585,12 @@ int tc_create(const tc_pool_desc *pool, const tc_opts *opts, tc_ctx **out)
     if (!is_device_ptr(pool->kv_base) || (S && !is_device_ptr(pool->scales))) return TC_ERR_NOT_PINNED;
 
     tc_ctx *c = new (std::nothrow) tc_ctx;
-    if (!c) return TC_ERR_INVAL;
+    if (!c) return TC_ERR_HOST_NOMEM;
+    // whatever way this function is left without success, the half-built context goes with it
+    struct Undo {
+        tc_ctx *c;
+        ~Undo() { if (c) destroy_unlocked(c); }
+    } undo{c};
     c->pool = *pool;
     if (opts) c->opts = *opts;
     const uint64_t raw = uint64_t(P) * pool->page_bytes + 4ull * S;
@@ -607,11 +618,8 @@ int tc_create(const tc_pool_desc *pool, const tc_opts *opts, tc_ctx **out)
     c->ring_cap = std::max<uint64_t>(4ull * pool->num_blocks, 1024);
     c->block_ticket.assign(pool->num_blocks, 0);
 
-    auto fail = [&](int code) {
-        destroy_unlocked(c);
-        return code;
-    };
-    if (!c->blocks || !c->arena) return fail(TC_ERR_INVAL);
+    auto fail = [](int code) { return code; };
+    if (!c->blocks || !c->arena) return fail(TC_ERR_HOST_NOMEM);
 #define HIP_OR_FAIL(expr)                                                                     \
     do {                                                                                      \
         hipError_t e_ = (expr);                                                               \
@@ -646,9 +654,10 @@ int tc_create(const tc_pool_desc *pool, const tc_opts *opts, tc_ctx **out)
         c->sync_events.push_back(e);
     }
 #undef HIP_OR_FAIL
+    undo.c = nullptr;
     *out = c;
     return TC_OK;
-}
+} TC_CATCH_ALL
 
 int tc_destroy(tc_ctx *ctx)
 {
@@ -683,16 +692,16 @@ const char *tc_strerror(int code)
 }
 
 int tc_alloc(tc_ctx *ctx, uint32_t n, int32_t *out_ids)
-{
+try {
     if (!ctx || (n && !out_ids)) return TC_ERR_INVAL;
     std::lock_guard<std::mutex> g(ctx->mu);
     // blocks of finished transfers may still be waiting for retirement
     if (n > ctx->blocks->n_free()) (void)poll_locked(ctx);
     return ctx->blocks->alloc(n, out_ids);
-}
+} TC_CATCH_ALL
 
 int tc_alloc_at(tc_ctx *ctx, const int32_t *ids, uint32_t n)
-{
+try {
     if (!ctx || (n && !ids)) return TC_ERR_INVAL;
     std::lock_guard<std::mutex> g(ctx->mu);
     int rc = ctx->blocks->alloc_at(ids, n);
@@ -701,40 +710,40 @@ int tc_alloc_at(tc_ctx *ctx, const int32_t *ids, uint32_t n)
         rc = ctx->blocks->alloc_at(ids, n);
     }
     return rc;
-}
+} TC_CATCH_ALL
 
 int tc_alloc_prefer(tc_ctx *ctx, const int32_t *preferred, uint32_t n, int32_t *out_ids)
-{
+try {
     if (!ctx || (n && (!preferred || !out_ids))) return TC_ERR_INVAL;
     std::lock_guard<std::mutex> g(ctx->mu);
     // retire what has finished first: an original block may be pending-free behind a completed copy
     if (ctx->blocks->n_pending()) (void)poll_locked(ctx);
     return ctx->blocks->alloc_prefer(preferred, n, out_ids);
-}
+} TC_CATCH_ALL
 
 int tc_ref(tc_ctx *ctx, const int32_t *ids, uint32_t n)
-{
+try {
     if (!ctx || (n && !ids)) return TC_ERR_INVAL;
     std::lock_guard<std::mutex> g(ctx->mu);
     return ctx->blocks->ref(ids, n);
-}
+} TC_CATCH_ALL
 
 int tc_free(tc_ctx *ctx, const int32_t *ids, uint32_t n)
-{
+try {
     if (!ctx || (n && !ids)) return TC_ERR_INVAL;
     std::lock_guard<std::mutex> g(ctx->mu);
     return ctx->blocks->free(ids, n);
-}
+} TC_CATCH_ALL
 
 int tc_filter_private(tc_ctx *ctx, const int32_t *ids, uint32_t n, int32_t *out_ids, uint32_t *m)
-{
+try {
     if (!ctx || !m || (n && (!ids || !out_ids))) return TC_ERR_INVAL;
     std::lock_guard<std::mutex> g(ctx->mu);
     return ctx->blocks->filter_private(ids, n, out_ids, m);
-}
+} TC_CATCH_ALL
 
 int tc_host_alloc(tc_ctx *ctx, uint32_t n_blocks, void **host_buf)
-{
+try {
     if (!ctx || !host_buf) return TC_ERR_INVAL;
     *host_buf = nullptr;
     if (n_blocks == 0) return TC_OK;
@@ -748,10 +757,10 @@ int tc_host_alloc(tc_ctx *ctx, uint32_t n_blocks, void **host_buf)
     if (s < 0) return TC_ERR_HOST_NOMEM;
     *host_buf = ctx->arena_base + uint64_t(s) * ctx->rec;
     return TC_OK;
-}
+} TC_CATCH_ALL
 
 int tc_host_free(tc_ctx *ctx, void *host_buf)
-{
+try {
     if (!ctx) return TC_ERR_INVAL;
     if (!host_buf) return TC_OK;
     std::lock_guard<std::mutex> g(ctx->mu);
@@ -760,51 +769,51 @@ int tc_host_free(tc_ctx *ctx, void *host_buf)
     uint64_t off = uint64_t(p - ctx->arena_base);
     if (off % ctx->rec) return TC_ERR_INVAL;
     return ctx->arena->free(off / ctx->rec);
-}
+} TC_CATCH_ALL
 
 int tc_offload_batch(tc_ctx *ctx, const tc_xfer_desc *descs, uint32_t n_descs, void *stream)
-{
+try {
     if (!ctx) return TC_ERR_INVAL;
     std::lock_guard<std::mutex> g(ctx->mu);
     return offload_locked(ctx, descs, n_descs, static_cast<hipStream_t>(stream));
-}
+} TC_CATCH_ALL
 
 int tc_upload_batch(tc_ctx *ctx, const tc_xfer_desc *descs, uint32_t n_descs, void *stream)
-{
+try {
     if (!ctx) return TC_ERR_INVAL;
     std::lock_guard<std::mutex> g(ctx->mu);
     return upload_locked(ctx, descs, n_descs, static_cast<hipStream_t>(stream));
-}
+} TC_CATCH_ALL
 
 int tc_offload(tc_ctx *ctx, const int32_t *block_ids, uint32_t n, void *host_buf, void *stream)
-{
+try {
     tc_xfer_desc d{block_ids, n, host_buf, nullptr};
     return tc_offload_batch(ctx, &d, 1, stream);
-}
+} TC_CATCH_ALL
 
 int tc_upload(tc_ctx *ctx, const void *host_buf, const int32_t *new_block_ids, uint32_t n, int32_t *block_table,
               void *stream)
-{
+try {
     tc_xfer_desc d{new_block_ids, n, const_cast<void *>(host_buf), block_table};
     return tc_upload_batch(ctx, &d, 1, stream);
-}
+} TC_CATCH_ALL
 
 int tc_poll(tc_ctx *ctx)
-{
+try {
     if (!ctx) return TC_ERR_INVAL;
     std::lock_guard<std::mutex> g(ctx->mu);
     return poll_locked(ctx);
-}
+} TC_CATCH_ALL
 
 int tc_sync(tc_ctx *ctx)
-{
+try {
     if (!ctx) return TC_ERR_INVAL;
     std::lock_guard<std::mutex> g(ctx->mu);
     return sync_locked(ctx);
-}
+} TC_CATCH_ALL
 
 int tc_stats(tc_ctx *ctx, tc_stats_t *out)
-{
+try {
     if (!ctx || !out) return TC_ERR_INVAL;
     std::lock_guard<std::mutex> g(ctx->mu);
     tc_stats_t s = ctx->st;
@@ -818,18 +827,18 @@ int tc_stats(tc_ctx *ctx, tc_stats_t *out)
     s.host_slots_used = ctx->arena->used();
     *out = s;
     return TC_OK;
-}
+} TC_CATCH_ALL
 
 int tc_set_profiling(tc_ctx *ctx, int on)
-{
+try {
     if (!ctx) return TC_ERR_INVAL;
     std::lock_guard<std::mutex> g(ctx->mu);
     ctx->profiling = on != 0;
     return TC_OK;
-}
+} TC_CATCH_ALL
 
 int tc_calibrate(tc_ctx *ctx, const uint32_t *sizes, uint32_t m, uint32_t reps, void *stream, tc_cost_model *out)
-{
+try {
     if (!ctx || !sizes || !out || m < 2 || reps == 0) return TC_ERR_INVAL;
     hipStream_t st = static_cast<hipStream_t>(stream);
     uint32_t largest = 0;
@@ -879,28 +888,28 @@ int tc_calibrate(tc_ctx *ctx, const uint32_t *sizes, uint32_t m, uint32_t reps, 
     (void)tc_free(ctx, ids.data(), largest);
     if (rc != TC_OK) return rc;
     return tc_cost_fit(sizes, off_ms.data(), up_ms.data(), m, out);
-}
+} TC_CATCH_ALL
 
 int tc_copy_contiguous(void *dst, const void *src, uint64_t bytes, void *stream)
-{
+try {
     if ((bytes && (!dst || !src)) || bytes % 16) return TC_ERR_INVAL;
     if ((reinterpret_cast<uintptr_t>(dst) | reinterpret_cast<uintptr_t>(src)) % 16) return TC_ERR_INVAL;
     HIP_TRY(tc::launch_copy_contiguous(dst, src, bytes, static_cast<hipStream_t>(stream)));
     return TC_OK;
-}
+} TC_CATCH_ALL
 
 int tc_hbm_stream(float *a, const float *b, const float *c, uint64_t n, float s, uint32_t iters, void *stream)
-{
+try {
     if ((n && (!a || !b || !c)) || n % 4) return TC_ERR_INVAL;
     if ((reinterpret_cast<uintptr_t>(a) | reinterpret_cast<uintptr_t>(b) | reinterpret_cast<uintptr_t>(c)) % 16)
         return TC_ERR_INVAL;
     HIP_TRY(tc::launch_hbm_stream(a, b, c, n, s, iters, static_cast<hipStream_t>(stream)));
     return TC_OK;
-}
+} TC_CATCH_ALL
 
 int tc_naive_transfer(tc_ctx *ctx, const int32_t *block_ids, uint32_t n, void *host_buf, int mode, int direction,
                       void *stream)
-{
+try {
     if (!ctx || (n && (!block_ids || !host_buf)) || mode < 0 || mode > 1 || direction < 0 || direction > 1)
         return TC_ERR_INVAL;
     std::lock_guard<std::mutex> g(ctx->mu);
@@ -929,6 +938,6 @@ int tc_naive_transfer(tc_ctx *ctx, const int32_t *block_ids, uint32_t n, void *h
         }
     }
     return TC_OK;
-}
+} TC_CATCH_ALL
 
 }  // extern "C"

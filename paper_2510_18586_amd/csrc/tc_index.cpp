@@ -8,6 +8,7 @@
 // whole blocks of token ids.
 #include <cstring>
 #include <mutex>
+#include <new>
 #include <unordered_map>
 #include <unordered_set>
 #include <vector>
@@ -49,6 +50,12 @@ struct tc_index {
     }
 };
 
+// No exception crosses the C boundary: running out of host memory inside a container is reported,
+// anything else unexpected is an invalid call.
+#define TC_CATCH_ALL                                              \
+    catch (const std::bad_alloc &) { return TC_ERR_HOST_NOMEM; } \
+    catch (...) { return TC_ERR_INVAL; }
+
 extern "C" {
 
 uint64_t tc_fnv1a64(const void *data, uint64_t len, uint64_t basis)
@@ -64,7 +71,7 @@ uint64_t tc_fnv1a64(const void *data, uint64_t len, uint64_t basis)
 
 int tc_chain_hashes(const int32_t *tokens, uint64_t n_tokens, uint32_t block_size, uint64_t parent,
                     uint64_t *out, uint64_t *n_out)
-{
+try {
     if (!block_size || !n_out || (n_tokens && !tokens)) return TC_ERR_INVAL;
     uint64_t blocks = n_tokens / block_size;
     if (blocks && !out) return TC_ERR_INVAL;
@@ -79,14 +86,14 @@ int tc_chain_hashes(const int32_t *tokens, uint64_t n_tokens, uint32_t block_siz
     }
     *n_out = blocks;
     return TC_OK;
-}
+} TC_CATCH_ALL
 
 int tc_index_create(tc_index **out)
-{
+try {
     if (!out) return TC_ERR_INVAL;
     *out = new (std::nothrow) tc_index();
     return *out ? TC_OK : TC_ERR_HOST_NOMEM;
-}
+} TC_CATCH_ALL
 
 int tc_index_destroy(tc_index *ix)
 {
@@ -96,7 +103,7 @@ int tc_index_destroy(tc_index *ix)
 
 int tc_index_insert(tc_index *ix, const uint64_t *keys, const int32_t *gpu_blocks, void *host_buf,
                     uint64_t record_bytes, uint32_t n)
-{
+try {
     if (!ix || (n && (!keys || !gpu_blocks || !host_buf))) return TC_ERR_INVAL;
     std::lock_guard<std::mutex> g(ix->mu);
     if (!distinct(keys, n)) return TC_ERR_DUP;
@@ -106,10 +113,10 @@ int tc_index_insert(tc_index *ix, const uint64_t *keys, const int32_t *gpu_block
     for (uint32_t i = 0; i < n; ++i)
         ix->map[keys[i]] = Entry{static_cast<char *>(host_buf) + uint64_t(i) * record_bytes, gpu_blocks[i], TC_RES_CPU};
     return TC_OK;
-}
+} TC_CATCH_ALL
 
 int tc_index_lookup(const tc_index *ix, const uint64_t *keys, uint32_t n, tc_index_hit *out, uint32_t *hits)
-{
+try {
     if (!ix || !hits || (n && (!keys || !out))) return TC_ERR_INVAL;
     std::lock_guard<std::mutex> g(ix->mu);
     uint32_t k = 0;
@@ -123,10 +130,10 @@ int tc_index_lookup(const tc_index *ix, const uint64_t *keys, uint32_t n, tc_ind
     }
     *hits = k;
     return TC_OK;
-}
+} TC_CATCH_ALL
 
 int tc_index_begin_upload(tc_index *ix, const uint64_t *keys, const int32_t *new_gpu_blocks, uint32_t n)
-{
+try {
     if (!ix || (n && (!keys || !new_gpu_blocks))) return TC_ERR_INVAL;
     std::lock_guard<std::mutex> g(ix->mu);
     if (!distinct(keys, n)) return TC_ERR_DUP;
@@ -137,27 +144,27 @@ int tc_index_begin_upload(tc_index *ix, const uint64_t *keys, const int32_t *new
         e.gpu_block = new_gpu_blocks[i];
     }
     return TC_OK;
-}
+} TC_CATCH_ALL
 
 int tc_index_finish_upload(tc_index *ix, const uint64_t *keys, uint32_t n)
-{
+try {
     if (!ix || (n && !keys)) return TC_ERR_INVAL;
     std::lock_guard<std::mutex> g(ix->mu);
     if (!distinct(keys, n)) return TC_ERR_DUP;
     if (!ix->all_in(keys, n, TC_RES_H2D)) return TC_ERR_INVAL;
     for (uint32_t i = 0; i < n; ++i) ix->map.erase(keys[i]);
     return TC_OK;
-}
+} TC_CATCH_ALL
 
 int tc_index_remove(tc_index *ix, const uint64_t *keys, uint32_t n)
-{
+try {
     if (!ix || (n && !keys)) return TC_ERR_INVAL;
     std::lock_guard<std::mutex> g(ix->mu);
     if (!distinct(keys, n)) return TC_ERR_DUP;
     if (!ix->all_in(keys, n, TC_RES_CPU)) return TC_ERR_INVAL;
     for (uint32_t i = 0; i < n; ++i) ix->map.erase(keys[i]);
     return TC_OK;
-}
+} TC_CATCH_ALL
 
 uint32_t tc_index_pending(const tc_index *ix, const uint64_t *keys, uint32_t n)
 {

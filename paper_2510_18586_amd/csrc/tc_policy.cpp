@@ -36,18 +36,24 @@ bool fit_line(const uint32_t *n, const double *t, uint32_t m, double *a, double 
 
 }  // namespace
 
+// No exception crosses the C boundary: running out of host memory inside a container is reported,
+// anything else unexpected is an invalid call.
+#define TC_CATCH_ALL                                              \
+    catch (const std::bad_alloc &) { return TC_ERR_HOST_NOMEM; } \
+    catch (...) { return TC_ERR_INVAL; }
+
 extern "C" {
 
 int tc_cost_fit(const uint32_t *n_blocks, const double *offload_ms, const double *upload_ms, uint32_t m,
                 tc_cost_model *out)
-{
+try {
     if (!n_blocks || !offload_ms || !upload_ms || !out || m < 2) return TC_ERR_INVAL;
     tc_cost_model r;
     if (!fit_line(n_blocks, offload_ms, m, &r.off_a_ms, &r.off_b_ms_per_block)) return TC_ERR_INVAL;
     if (!fit_line(n_blocks, upload_ms, m, &r.up_a_ms, &r.up_b_ms_per_block)) return TC_ERR_INVAL;
     *out = r;
     return TC_OK;
-}
+} TC_CATCH_ALL
 
 double tc_estimate_transfer_ms(const tc_cost_model *model, uint32_t n_blocks)
 {
@@ -60,7 +66,7 @@ double tc_estimate_transfer_ms(const tc_cost_model *model, uint32_t n_blocks)
 int tc_should_offload(const tc_cost_model *model, uint32_t req_blocks, double t_fc_ms,
                       double v_throughput_tokens_per_ms, const tc_waiting_req *queue, uint32_t n_queue,
                       int32_t *chosen)
-{
+try {
     if (!model || (n_queue && !queue)) return TC_ERR_INVAL;
     if (chosen) *chosen = -1;
     const double t_transfer = tc_estimate_transfer_ms(model, req_blocks);
@@ -73,7 +79,7 @@ int tc_should_offload(const tc_cost_model *model, uint32_t req_blocks, double t_
         }
     }
     return 0;
-}
+} TC_CATCH_ALL
 
 uint32_t tc_upload_budget(uint32_t gpu_free, uint32_t d_critical, uint32_t shared_free)
 {
@@ -91,7 +97,7 @@ uint32_t tc_gradual_reserve(uint32_t remain, uint32_t deficit, uint32_t budget)
 
 int tc_offload_gate(const tc_cost_model *model, const tc_gate_input *in, const tc_waiting_req *queue,
                     uint32_t n_queue, int32_t *chosen, int *reason)
-{
+try {
     if (!model || !in || !reason || (n_queue && !queue) || in->gpu_total_blocks == 0) return TC_ERR_INVAL;
     if (std::isnan(in->pressure_threshold) || std::isnan(in->t_fc_ms) || std::isnan(in->v_throughput_tokens_per_ms))
         return TC_ERR_INVAL;
@@ -117,11 +123,11 @@ int tc_offload_gate(const tc_cost_model *model, const tc_gate_input *in, const t
     *reason = TC_GATE_PASS;
     if (chosen) *chosen = k;
     return 1;
-}
+} TC_CATCH_ALL
 
 int tc_upload_plan(const tc_upload_cand *cands, uint32_t n, uint32_t gpu_free, uint32_t d_critical,
                    uint32_t shared_free, uint32_t *order, uint32_t *reserve)
-{
+try {
     if (n && (!cands || !order || !reserve)) return TC_ERR_INVAL;
     for (uint32_t i = 0; i < n; ++i)
         if (std::isnan(cands[i].importance) || std::isnan(cands[i].urgency)) return TC_ERR_INVAL;
@@ -141,10 +147,10 @@ int tc_upload_plan(const tc_upload_cand *cands, uint32_t n, uint32_t gpu_free, u
         remain -= reserve[i];
     }
     return TC_OK;
-}
+} TC_CATCH_ALL
 
 int tc_lifecycle_step(tc_req_state *req, int event, int *action)
-{
+try {
     if (!req || req->state > TC_UPLOADED) return TC_ERR_INVAL;
     tc_req_state r = *req;
     int act = TC_ACT_NONE;
@@ -224,7 +230,7 @@ int tc_lifecycle_step(tc_req_state *req, int event, int *action)
     *req = r;
     if (action) *action = act;
     return TC_OK;
-}
+} TC_CATCH_ALL
 
 }  // extern "C"
 
@@ -237,7 +243,7 @@ struct tc_forecaster {
 extern "C" {
 
 int tc_forecaster_create(double alpha, double gamma, double default_ms, tc_forecaster **out)
-{
+try {
     if (!out) return TC_ERR_INVAL;
     *out = nullptr;
     if (!(alpha >= 0.0 && alpha <= 1.0) || !(gamma > 0.0 && gamma <= 1.0) || !(default_ms >= 0.0)) return TC_ERR_INVAL;
@@ -248,7 +254,7 @@ int tc_forecaster_create(double alpha, double gamma, double default_ms, tc_forec
     f->default_ms = default_ms;
     *out = f;
     return TC_OK;
-}
+} TC_CATCH_ALL
 
 int tc_forecaster_destroy(tc_forecaster *f)
 {
@@ -257,14 +263,14 @@ int tc_forecaster_destroy(tc_forecaster *f)
 }
 
 int tc_forecaster_observe(tc_forecaster *f, uint32_t fn_type, double elapsed_ms)
-{
+try {
     if (!f || !(elapsed_ms >= 0.0)) return TC_ERR_INVAL;
     std::lock_guard<std::mutex> g(f->mu);
     auto it = f->history.find(fn_type);
     if (it == f->history.end()) f->history.emplace(fn_type, elapsed_ms);
     else it->second = f->gamma * elapsed_ms + (1.0 - f->gamma) * it->second;
     return TC_OK;
-}
+} TC_CATCH_ALL
 
 double tc_forecaster_estimate(const tc_forecaster *f, uint32_t fn_type, int has_user, double t_user_ms)
 {
