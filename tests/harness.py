@@ -3,6 +3,8 @@
 Nothing here computes any part of the path; it allocates, copies inputs in and results out
 (torch copies), and drives the library and the oracle with the same seeded inputs.
 """
+import os
+
 import numpy as np
 import torch
 
@@ -97,6 +99,23 @@ class GpuPool:
         if self.S:
             cs = torch.cat([cs, self.scales.view(self.S, self.NB)[:, idx].to(torch.int64)], dim=0)
         return cs
+
+
+def host_budget_bytes(want, share=0.25):
+    """Pinned-arena size for a test: `want`, but never more than `share` of the host memory that is
+    available right now (read from /proc/meminfo at run time); prints what it chose."""
+    avail = None
+    try:
+        with open("/proc/meminfo") as f:
+            for line in f:
+                if line.startswith("MemAvailable:"):
+                    avail = int(line.split()[1]) * 1024
+    except OSError:
+        pass
+    got = int(want) if avail is None else int(min(want, share * avail))
+    print(f"[harness] host memory available {'?' if avail is None else f'{avail / 2**30:.0f} GiB'}, "
+          f"{os.cpu_count()} cpus: pinned arena {got / 2**30:.1f} GiB (wanted {want / 2**30:.1f})", flush=True)
+    return got
 
 
 def pinned_bytes(n):
