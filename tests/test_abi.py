@@ -54,3 +54,28 @@ def test_null_arguments_are_rejected_without_a_gpu():
     assert K.tc_sync(None) == K.TC_ERR_INVAL
     assert K.tc_destroy(None) == K.TC_OK
     assert K.tc_record_bytes(None) == 0
+
+
+def test_header_is_plain_c_and_cxx(tmp_path):
+    """The boundary is a C header: it must compile on its own as C11 and as C++17, warnings as errors."""
+    import subprocess
+    inc = os.path.join(ROOT, "include")
+    src = tmp_path / "use_header.c"
+    src.write_text('#include "tokencake_kv.h"\nint main(void) { tc_pool_desc d; tc_opts o; (void)d; (void)o; return TC_OK; }\n')
+    subprocess.run(["gcc", "-std=c11", "-pedantic", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-I", inc, str(src)], check=True)
+    subprocess.run(["g++", "-std=c++17", "-pedantic", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-x", "c++", "-I", inc, str(src)],
+                   check=True)
+
+
+def test_a_plain_c_program_links_and_runs(tmp_path):
+    """tests/csrc/abi_smoke.c, built with gcc against the shared library, runs its host-only calls."""
+    import subprocess
+    lib = K.library_path()
+    exe = str(tmp_path / "abi_smoke")
+    libdir = os.path.dirname(lib)
+    subprocess.run(["gcc", "-std=c11", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(ROOT, "include"),
+                    os.path.join(ROOT, "tests", "csrc", "abi_smoke.c"), "-o", exe,
+                    "-L", libdir, "-ltokencake_kv", "-Wl,-rpath," + libdir, "-Wl,-rpath,/opt/rocm/lib",
+                    "-Wl,--allow-shlib-undefined"], check=True)
+    out = subprocess.run([exe], capture_output=True, text=True, timeout=60)
+    assert out.returncode == 0 and out.stdout.strip() == "ok", (out.returncode, out.stdout, out.stderr)
