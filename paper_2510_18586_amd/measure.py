@@ -1,6 +1,6 @@
 """Measurements beyond the headline benchmark line, for all five configurations.
 
-    python -m paper_2510_18586_amd.measure [--only sweep,naive,config1,config3,config4,config4_replay,forecast_noise,config5] [--out FILE]
+    python -m paper_2510_18586_amd.measure [--only sweep,naive,config1,config3,config4,config4_replay,forecast_noise,config5,host] [--out FILE]
 
 Prints one JSON object per measurement (and writes them to --out).  Needs a GPU.  Times are
 wall-clock around enqueue + synchronisation unless stated; GB = 1e9 bytes.
@@ -17,6 +17,8 @@ wall-clock around enqueue + synchronisation unless stated; GB = 1e9 bytes.
            the tool returns, stall otherwise, per-transfer rates
   forecast_noise  that replay with the forecaster of Eq. 1 and noisy user estimates (sigma 0, 0.25, 0.5)
   config5  70B fp8 shape with scales: one wave of private blocks as a batch
+  host     host-side cost of the calls around a 256-block transfer (bookkeeping, enqueue, index, keys),
+           median and worst of many repetitions, through the ctypes binding (about 2 us of that is Python)
 """
 import argparse
 import json
@@ -485,8 +487,81 @@ def m_config5(torch, K, W, emit):
     c.close()
 
 
+def m_host(torch, K, W, emit):
+    """Sec. 6.3 and 7.6 argue that allocation on the migration path has to stay far below a millisecond."""
+    shape = W.CONFIGS[1]
+    c = Ctx(torch, K, W, shape, 1, 1024, fill=False)
+    n = 256
+    stream = torch.cuda.Stream()
+    out = {}
+
+    def rep(name, fn, reps=2000):
+        ts = []
+        for _ in range(reps):
+            t = time.perf_counter()
+            fn()
+            ts.append(time.perf_counter() - t)
+        ts = np.asarray(ts[reps // 10:]) * 1e6
+        out[name] = dict(median_us=round(float(np.median(ts)), 2), p99_us=round(float(np.percentile(ts, 99)), 2),
+                         worst_us=round(float(ts.max()), 2))
+
+    def alloc_free():
+        rc, ids = K.tc_alloc(c.ctx, n)
+        K.tc_free(c.ctx, ids)
+    rep("tc_alloc(256) + tc_free", alloc_free)
+    rc, ids = K.tc_alloc(c.ctx, n)
+    K.check(K.tc_free(c.ctx, ids))
+
+    def prefer_free():
+        rc, got = K.tc_alloc_prefer(c.ctx, ids)
+        K.tc_free(c.ctx, got)
+    rep("tc_alloc_prefer(256) + tc_free", prefer_free)
+
+    def host_alloc_free():
+        rc, b = K.tc_host_alloc(c.ctx, n)
+        K.tc_host_free(c.ctx, b)
+    rep("tc_host_alloc(256) + tc_host_free", host_alloc_free)
+    rep("tc_poll, nothing in flight", lambda: K.tc_poll(c.ctx))
+
+    perm = np.random.default_rng(3).permutation(shape.num_blocks).astype(np.int32)
+    src, dst = perm[:n].copy(), perm[n:2 * n].copy()
+    K.check(K.tc_alloc_at(c.ctx, src))
+    K.check(K.tc_alloc_at(c.ctx, dst))
+    rc, buf = K.tc_host_alloc(c.ctx, n)
+    table = torch.zeros(n, dtype=torch.int32, device="cuda:0")
+    enq = {"tc_offload(256 blocks): call returns after": [], "tc_upload(256 blocks): call returns after": []}
+    for _ in range(40):
+        t = time.perf_counter()
+        K.tc_offload(c.ctx, src, buf, stream)
+        enq["tc_offload(256 blocks): call returns after"].append(time.perf_counter() - t)
+        K.check(K.tc_sync(c.ctx))
+        t = time.perf_counter()
+        K.tc_upload(c.ctx, buf, dst, table, stream)
+        enq["tc_upload(256 blocks): call returns after"].append(time.perf_counter() - t)
+        K.check(K.tc_sync(c.ctx))
+    for k, v in enq.items():
+        v = np.asarray(v[4:]) * 1e6
+        out[k] = dict(median_us=round(float(np.median(v)), 2), p99_us=round(float(np.percentile(v, 99)), 2),
+                      worst_us=round(float(v.max()), 2))
+
+    tokens = np.random.default_rng(4).integers(0, 128000, size=n * shape.block_size, dtype=np.int32)
+    rep("tc_chain_hashes(4096 tokens)", lambda: K.tc_chain_hashes(tokens, shape.block_size))
+    rc, keys = K.tc_chain_hashes(tokens, shape.block_size)
+    rc, ix = K.tc_index_create()
+
+    def index_cycle():
+        K.tc_index_insert(ix, keys, src, buf, c.rec)
+        K.tc_index_lookup(ix, keys)
+        K.tc_index_begin_upload(ix, keys, dst)
+        K.tc_index_finish_upload(ix, keys)
+    rep("tc_index insert + lookup + begin_upload + finish_upload (256 keys)", index_cycle)
+    K.tc_index_destroy(ix)
+    emit(dict(measurement="host", blocks=n, calls=out))
+    c.close()
+
+
 ALL = dict(sweep=m_sweep, naive=m_naive, config1=m_config1, config3=m_config3, config4=m_config4,
-           config4_replay=m_config4_replay, forecast_noise=m_forecast_noise, config5=m_config5)
+           config4_replay=m_config4_replay, forecast_noise=m_forecast_noise, config5=m_config5, host=m_host)
 
 
 def main():
