@@ -18,7 +18,7 @@ __all__ = [
     "tc_create", "tc_destroy", "tc_record_bytes", "tc_strerror", "tc_alloc", "tc_alloc_at", "tc_ref",
     "tc_free", "tc_filter_private", "tc_host_alloc", "tc_host_free", "tc_offload", "tc_upload",
     "tc_offload_batch", "tc_upload_batch", "tc_poll", "tc_sync", "tc_stats", "tc_set_profiling",
-    "tc_arena_base", "tc_copy_contiguous", "tc_hbm_stream", "tc_naive_transfer",
+    "tc_arena_base", "tc_copy_contiguous", "tc_copy_via_lds", "tc_hbm_stream", "tc_naive_transfer",
     "tc_cost_model", "tc_waiting_req", "tc_cost_fit", "tc_calibrate", "tc_estimate_transfer_ms",
     "tc_should_offload", "tc_upload_budget", "tc_gradual_reserve",
     "tc_req_state", "tc_lifecycle_step", "tc_forecaster_create", "tc_forecaster_destroy",
@@ -180,6 +180,7 @@ def _load():
         "tc_set_profiling": (ci, [vp, ci]),
         "tc_arena_base": (vp, [vp]),
         "tc_copy_contiguous": (ci, [vp, vp, u64, vp]),
+        "tc_copy_via_lds": (ci, [vp, vp, u64, ci, vp]),
         "tc_hbm_stream": (ci, [vp, vp, vp, u64, ctypes.c_float, u32, vp]),
         "tc_naive_transfer": (ci, [vp, vp, u32, vp, ci, ci, vp]),
         "tc_cost_fit": (ci, [vp, vp, vp, u32, ctypes.POINTER(tc_cost_model)]),
@@ -377,6 +378,10 @@ def tc_arena_base(ctx):
 
 def tc_copy_contiguous(dst, src, nbytes, stream=None):
     return _load().tc_copy_contiguous(_ptr(dst), _ptr(src), nbytes, _stream(stream))
+
+
+def tc_copy_via_lds(dst, src, nbytes, lds_direct_loads=0, stream=None):
+    return _load().tc_copy_via_lds(_ptr(dst), _ptr(src), nbytes, int(lds_direct_loads), _stream(stream))
 
 
 def tc_hbm_stream(a, b, c, n, s=0.5, iters=1, stream=None):

@@ -898,6 +898,14 @@ try {
     return TC_OK;
 } TC_CATCH_ALL
 
+int tc_copy_via_lds(void *dst, const void *src, uint64_t bytes, int lds_direct_loads, void *stream)
+try {
+    if ((bytes && (!dst || !src)) || bytes % 16384) return TC_ERR_INVAL;
+    if ((reinterpret_cast<uintptr_t>(dst) | reinterpret_cast<uintptr_t>(src)) % 16) return TC_ERR_INVAL;
+    HIP_TRY(tc::launch_copy_via_lds(dst, src, bytes, lds_direct_loads != 0, static_cast<hipStream_t>(stream)));
+    return TC_OK;
+} TC_CATCH_ALL
+
 int tc_hbm_stream(float *a, const float *b, const float *c, uint64_t n, float s, uint32_t iters, void *stream)
 try {
     if ((n && (!a || !b || !c)) || n % 4) return TC_ERR_INVAL;

@@ -27,6 +27,8 @@ hipError_t launch_scatter_pages(const void *staging, void *pool, uint32_t *scale
 hipError_t launch_rewrite_table(int32_t *table, const int32_t *ids_dev, uint32_t n, hipStream_t stream);
 
 hipError_t launch_copy_contiguous(void *dst, const void *src, uint64_t bytes, hipStream_t stream);
+// The same copy staged through LDS (bytes must be a multiple of 16 KiB); measurement only.
+hipError_t launch_copy_via_lds(void *dst, const void *src, uint64_t bytes, bool lds_direct_loads, hipStream_t stream);
 hipError_t launch_hbm_stream(float *a, const float *b, const float *c, uint64_t n, float s, uint32_t iters,
                              hipStream_t stream);
 

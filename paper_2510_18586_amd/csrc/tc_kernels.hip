@@ -112,6 +112,35 @@ __global__ __launch_bounds__(kThreads) void copy_contiguous_kernel(u32x4 *__rest
     }
 }
 
+// The same contiguous copy with the tile staged in LDS, kept to measure what LDS adds to a copy that
+// has no reuse.  DMA = false: loads into registers, ds_write, barrier, ds_read, stores.  DMA = true:
+// LDS-direct loads (each lane names its own global address; a wave's 64 x 16 bytes land consecutively
+// at a wave-uniform LDS address), then ds_read and stores.  Whole tiles only.
+template <int U, bool DMA>
+__global__ __launch_bounds__(kThreads) void copy_via_lds_kernel(u32x4 *__restrict__ dst, const u32x4 *__restrict__ src)
+{
+    __shared__ u32x4 buf[kThreads * U];
+    const uint64_t base = uint64_t(blockIdx.x) * (kThreads * U) + threadIdx.x;
+    if constexpr (DMA) {
+        const uint32_t wave = threadIdx.x / 64;
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src + base + u * kThreads),
+                                             (__attribute__((address_space(3))) void *)(buf + u * kThreads + wave * 64),
+                                             16, 0, 0);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    } else {
+        u32x4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) v[u] = ld16<true>(src + base + u * kThreads);
+#pragma unroll
+        for (int u = 0; u < U; ++u) buf[u * kThreads + threadIdx.x] = v[u];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < U; ++u) st16<true>(dst + base + u * kThreads, buf[u * kThreads + threadIdx.x]);
+}
+
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 // One pass of a = b + s*c; a workgroup covers 4 consecutive 4 KiB rows and retires, so that
@@ -201,6 +230,23 @@ hipError_t launch_copy_contiguous(void *dst, const void *src, uint64_t bytes, hi
     if (grid > 0x7fffffffull) return hipErrorInvalidValue;
     hipLaunchKernelGGL((copy_contiguous_kernel<8, true>), dim3(uint32_t(grid)), dim3(kThreads), 0, stream,
                        static_cast<u32x4 *>(dst), static_cast<const u32x4 *>(src), n16);
+    return hipGetLastError();
+}
+
+hipError_t launch_copy_via_lds(void *dst, const void *src, uint64_t bytes, bool lds_direct_loads, hipStream_t stream)
+{
+    constexpr int U = 4;                                   // 16 KiB of LDS per workgroup
+    constexpr uint64_t kTileBytes = uint64_t(kThreads) * U * 16;
+    if (bytes == 0) return hipSuccess;
+    if (bytes % kTileBytes) return hipErrorInvalidValue;   // the kernel has no ragged path
+    const uint64_t grid = bytes / kTileBytes;
+    if (grid > 0x7fffffffull) return hipErrorInvalidValue;
+    if (lds_direct_loads)
+        hipLaunchKernelGGL((copy_via_lds_kernel<U, true>), dim3(uint32_t(grid)), dim3(kThreads), 0, stream,
+                           static_cast<u32x4 *>(dst), static_cast<const u32x4 *>(src));
+    else
+        hipLaunchKernelGGL((copy_via_lds_kernel<U, false>), dim3(uint32_t(grid)), dim3(kThreads), 0, stream,
+                           static_cast<u32x4 *>(dst), static_cast<const u32x4 *>(src));
     return hipGetLastError();
 }
 

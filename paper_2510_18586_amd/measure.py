@@ -1,6 +1,6 @@
 """Measurements beyond the headline benchmark line, for all five configurations.
 
-    python -m paper_2510_18586_amd.measure [--only sweep,naive,config1,config3,config4,config4_replay,forecast_noise,config5,host] [--out FILE]
+    python -m paper_2510_18586_amd.measure [--only sweep,naive,config1,config3,config4,config4_replay,forecast_noise,config5,lds,host] [--out FILE]
 
 Prints one JSON object per measurement (and writes them to --out).  Needs a GPU.  Times are
 wall-clock around enqueue + synchronisation unless stated; GB = 1e9 bytes.
@@ -17,6 +17,8 @@ wall-clock around enqueue + synchronisation unless stated; GB = 1e9 bytes.
            the tool returns, stall otherwise, per-transfer rates
   forecast_noise  that replay with the forecaster of Eq. 1 and noisy user estimates (sigma 0, 0.25, 0.5)
   config5  70B fp8 shape with scales: one wave of private blocks as a batch
+  lds      a contiguous 512 MiB device copy through registers (what the copy kernels do), staged in LDS,
+           and with LDS-direct loads: what LDS adds to a copy without reuse
   host     host-side cost of the calls around a 256-block transfer (bookkeeping, enqueue, index, keys),
            median and worst of many repetitions, through the ctypes binding (about 2 us of that is Python)
 """
@@ -487,6 +489,33 @@ def m_config5(torch, K, W, emit):
     c.close()
 
 
+def m_lds(torch, K, W, emit):
+    n = 512 << 20
+    a = torch.empty(n, dtype=torch.uint8, device="cuda:0")
+    a.view(torch.int32).random_(0, 2 ** 31 - 1)
+    b = torch.zeros(n, dtype=torch.uint8, device="cuda:0")
+    stream = torch.cuda.Stream()
+    rows = {}
+    for name, fn in (("registers (tc_copy_contiguous)", lambda: K.tc_copy_contiguous(b, a, n, stream)),
+                     ("registers -> LDS -> registers", lambda: K.tc_copy_via_lds(b, a, n, 0, stream)),
+                     ("LDS-direct loads", lambda: K.tc_copy_via_lds(b, a, n, 1, stream))):
+        ts = []
+        for i in range(14):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            with torch.cuda.stream(stream):
+                e0.record(stream)
+                K.check(fn())
+                e1.record(stream)
+            stream.synchronize()
+            if i >= 2:
+                ts.append(e0.elapsed_time(e1) * 1e3)
+        assert torch.equal(a, b)
+        b.zero_()
+        rows[name] = dict(mean_us=round(float(np.mean(ts)), 1), best_us=round(float(min(ts)), 1),
+                          TBps_of_traffic=round(2 * n / (float(np.mean(ts)) * 1e-6) / 1e12, 2))
+    emit(dict(measurement="lds", MiB=512, rows=rows))
+
+
 def m_host(torch, K, W, emit):
     """Sec. 6.3 and 7.6 argue that allocation on the migration path has to stay far below a millisecond."""
     shape = W.CONFIGS[1]
@@ -561,7 +590,7 @@ def m_host(torch, K, W, emit):
 
 
 ALL = dict(sweep=m_sweep, naive=m_naive, config1=m_config1, config3=m_config3, config4=m_config4,
-           config4_replay=m_config4_replay, forecast_noise=m_forecast_noise, config5=m_config5, host=m_host)
+           config4_replay=m_config4_replay, forecast_noise=m_forecast_noise, config5=m_config5, lds=m_lds, host=m_host)
 
 
 def main():
