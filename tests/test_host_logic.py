@@ -282,3 +282,22 @@ def test_host_arena_matches_oracle(shim):
             assert shim.tcb_arena_used(a) == o.used_slots()
     finally:
         shim.tcb_arena_del(a)
+
+
+@pytest.mark.parametrize("sanitizer", ["address,undefined", "thread"])
+def test_host_code_under_sanitizers(tmp_path, sanitizer):
+    """tests/csrc/host_sanitize.cpp + the library's host-only sources as a plain executable, built with
+    AddressSanitizer + UBSan and with ThreadSanitizer: seeded op streams on the block pool and the arena,
+    four threads on one residency index and one forecaster, random inputs to the scheduling arithmetic."""
+    csrc = os.path.join(ROOT, "paper_2510_18586_amd", "csrc")
+    exe = str(tmp_path / "host_sanitize")
+    subprocess.run(
+        ["g++", "-std=c++17", "-O1", "-g", "-Wall", "-Wextra", "-Werror", "-pthread",
+         "-fsanitize=" + sanitizer, "-fno-sanitize-recover=all",
+         "-static-libasan" if "address" in sanitizer else "-static-libtsan",     # no dependence on library load order
+         "-I", os.path.join(ROOT, "include"), "-I", csrc,
+         os.path.join(HERE, "csrc", "host_sanitize.cpp"), os.path.join(csrc, "tc_index.cpp"),
+         os.path.join(csrc, "tc_policy.cpp"), "-o", exe],
+        check=True)
+    out = subprocess.run([exe], capture_output=True, text=True, timeout=300)
+    assert out.returncode == 0 and out.stdout.strip().endswith("ok"), (out.returncode, out.stdout[-2000:], out.stderr[-4000:])
