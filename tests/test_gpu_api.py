@@ -486,3 +486,38 @@ def test_transfers_on_different_streams_respect_block_and_buffer_hazards():
         if mirror:
             mirror.close()
         gp.close()
+
+
+def test_thousands_of_small_transfers_wrap_the_id_ring():
+    """3 000 one- and two-block transfers on one stream with no host synchronisation in between: the id
+    rings (1 024 entries here) wrap several times and the calls have to wait for old transfers to retire.
+    The KV contents rotate through the pool; the end state must equal the oracle's."""
+    rng = W.rng_for(0, salt=41)
+    pool_host = W.make_pool_host(SMALL, rng)
+    mirror = pool_host.copy()
+    gp = GpuPool(SMALL, pool_host=pool_host, host_arena_bytes=8 * 2 * SMALL.num_layers * SMALL.page_bytes)
+    L, NB, pb = gp.L, gp.NB, gp.pb
+    try:
+        rc, ids = K.tc_alloc(gp.ctx, NB)
+        assert rc == 0
+        order = rng.permutation(NB).astype(np.int32)
+        bufs = [K.tc_host_alloc(gp.ctx, 2)[1] for _ in range(4)]
+        host_o = np.zeros(2 * gp.rec, dtype=np.uint8)
+        stream = torch.cuda.Stream()
+        table = torch.full((4,), -1, dtype=torch.int32, device=DEV)
+        for i in range(1500):
+            n = 1 + i % 2
+            src = np.array([order[(i + k) % NB] for k in range(n)], dtype=np.int32)
+            dst = np.array([order[(i + 7 + 3 * k) % NB] for k in range(n)], dtype=np.int32)
+            buf = bufs[i % 4]
+            K.check(K.tc_offload(gp.ctx, src, buf, stream))
+            K.check(K.tc_upload(gp.ctx, buf, dst, table, stream))
+            oracle.offload(mirror, None, L, NB, pb, 0, src, host_o[:n * gp.rec])
+            oracle.upload(host_o[:n * gp.rec], L, NB, pb, 0, dst, mirror, None)
+        K.check(K.tc_sync(gp.ctx))
+        st = _stats(gp)
+        assert st.n_offloads == st.n_uploads == 1500 and st.ops_in_flight == 0
+        assert np.array_equal(gp.pool_to_host(), mirror)
+        assert table.cpu().numpy()[:2].tolist() == dst.tolist()
+    finally:
+        gp.close()
