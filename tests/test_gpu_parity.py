@@ -114,6 +114,41 @@ def test_direct_paths_move_the_same_bytes(off, up, grid):
     _round_trip_case(W.CONFIGS[0], 0, 8, salt=43, **opts)
 
 
+def _random_case(k):
+    """A seeded random small shape + options: page sizes from 16 B to 48 KiB (whole tiles, ragged tiles,
+    less than one tile), every scale layout, chunked and unchunked staging, capped grids, direct paths."""
+    rng = W.rng_for(0, salt=1000 + k)
+    L = int(rng.integers(1, 6))
+    elem = int(rng.choice([1, 2]))
+    pb = 16 * int(rng.choice([1, 2, 3, 17, 64, 255, 256, 257, 512, 640, 1024, 2048, 3072]))
+    S = int(rng.choice([0, 1, 2 * L]))
+    NB = int(rng.integers(4, 70))
+    n = int(rng.integers(1, NB // 2 + 1))
+    # a shape whose page_bytes is exactly pb: 1 token per block, 1 head, head_dim = pb / elem
+    shape = W.PoolShape(f"rand{k}", L, 1, pb // elem, 1, elem, NB, S, "fp8" if elem == 1 else "normal")
+    assert shape.page_bytes == pb
+    rec = (2 * L * pb + 4 * S + 255) // 256 * 256
+    opts = {}
+    if rng.random() < 0.6:
+        slots = int(rng.integers(1, 4))
+        opts.update(staging_slots=slots, staging_bytes=slots * int(rng.integers(1, 5)) * rec)
+    if rng.random() < 0.4:
+        opts["max_grid"] = int(rng.choice([1, 2, 7, 64]))
+    mode = int(rng.integers(0, 4))
+    if mode == 1:
+        opts.update(direct_offload=1, direct_upload=1, direct_grid=int(rng.choice([0, 1, 5])))
+    elif mode == 2:
+        opts.update(direct_offload=2, direct_upload=int(rng.integers(0, 2)))
+    return shape, n, opts
+
+
+@pytest.mark.parametrize("k", range(24))
+def test_random_small_shapes_and_options(k):
+    shape, n, opts = _random_case(k)
+    print(f"case {k}: L={shape.num_layers} pb={shape.page_bytes} S={shape.scales_per_block} NB={shape.num_blocks} n={n} {opts}", flush=True)
+    _round_trip_case(shape, 0, n, salt=2000 + k, **opts)
+
+
 def test_zero_blocks_is_a_no_op():
     _round_trip_case(W.CONFIGS[0], 0, 0, salt=3)
 
