@@ -113,7 +113,7 @@ typedef struct {
  * `opts` may be NULL for defaults.  The pool and the scales stay the caller's and must outlive the
  * context.  TC_ERR_INVAL for a bad description (zero sizes, page_bytes not a multiple of 16,
  * misaligned base, scales_per_block not in {0, 1, 2*num_layers}, scales given xor announced, an option
- * out of range), TC_ERR_NOT_PINNED when kv_base / scales are not device memory, TC_ERR_HOST_NOMEM /
+ * out of range, num_blocks * 2*num_layers * ceil(page_bytes / 32 KiB) above 2^31 - 1), TC_ERR_NOT_PINNED when kv_base / scales are not device memory, TC_ERR_HOST_NOMEM /
  * TC_ERR_HIP when an allocation fails; *out is NULL on any error. */
 int tc_create(const tc_pool_desc *pool, const tc_opts *opts, tc_ctx **out);
 /* Waits for every transfer in flight, then frees what the context owns (staging, rings, arena:

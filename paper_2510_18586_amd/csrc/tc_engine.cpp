@@ -582,6 +582,10 @@ try {
     if ((S != 0) != (pool->scales != nullptr)) return TC_ERR_INVAL;
     if (S && (reinterpret_cast<uintptr_t>(pool->scales) % 4)) return TC_ERR_INVAL;
     if (opts && (opts->direct_offload > 2 || opts->direct_upload > 1)) return TC_ERR_INVAL;
+    // one launch may cover every block of the pool: its work items (block x plane x tile, a tile being
+    // at most 32 KiB of a page) are counted in 31 bits
+    const uint64_t tiles_per_page = (uint64_t(pool->page_bytes) + 32767) / 32768;
+    if (uint64_t(pool->num_blocks) * P * tiles_per_page > 0x7fffffffull) return TC_ERR_INVAL;
     if (!is_device_ptr(pool->kv_base) || (S && !is_device_ptr(pool->scales))) return TC_ERR_NOT_PINNED;
 
     tc_ctx *c = new (std::nothrow) tc_ctx;

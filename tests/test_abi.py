@@ -52,6 +52,12 @@ def test_null_arguments_are_rejected_without_a_gpu():
     lib = binding._load()
     assert lib.tc_create(None, None, None) == K.TC_ERR_INVAL
     assert K.tc_sync(None) == K.TC_ERR_INVAL
+    # descriptions that are refused before any device call: 2^31 work items in one launch, bad options
+    assert K.tc_create(0x1000, None, 64, 1 << 24, 32768, 16)[0] == K.TC_ERR_INVAL
+    assert K.tc_create(0x1000, None, 1 << 19, 4096, 16, 1)[0] == K.TC_ERR_INVAL
+    assert K.tc_create(0x1000, None, 2, 16, 4096, 16, direct_offload=3)[0] == K.TC_ERR_INVAL
+    assert K.tc_create(0x1010, None, 2, 16, 4096, 16)[0] == K.TC_ERR_INVAL          # base not 256-B aligned
+    assert K.tc_create(0x1000, None, 2, 16, 4100, 16)[0] == K.TC_ERR_INVAL          # page not a multiple of 16
     assert K.tc_destroy(None) == K.TC_OK
     assert K.tc_record_bytes(None) == 0
 
