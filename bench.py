@@ -184,7 +184,7 @@ def cpu_baseline(shape, ids, new_ids, budget_s=12.0):
 def main():
     args = parse()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (no multi-GPU path exists).", file=sys.stderr)
+        print("bench.py: this library runs on ONE GPU; --gpus must be 1 (no multi-GPU path exists).", file=sys.stderr)
         sys.exit(2)
     import torch
     if not torch.cuda.is_available():

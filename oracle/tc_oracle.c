@@ -43,7 +43,7 @@ static int shape_ok(uint32_t L, uint64_t NB, uint64_t pb, uint32_t S)
     return 1;
 }
 
-/* Host bytes per moved block (Sec. 7.6 size formula, plus this build's scale words and pad). */
+/* Host bytes per moved block (Sec. 7.6 size formula, plus this layout's scale words and pad). */
 uint64_t tco_record_bytes(uint32_t L, uint64_t pb, uint32_t S)
 {
     uint64_t raw = (uint64_t)2 * L * pb + (uint64_t)4 * S;

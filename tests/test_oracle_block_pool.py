@@ -4,7 +4,7 @@ What the paper fixes (Sec. 6.3): a block released while a copy that reads it is 
 is *pending-free* and goes back on the free list no earlier than the end of that copy; CPU
 blocks are recycled through a free list; the original GPU block can be claimed again.
 The rest are conservation laws checked against plain sets under seeded random op streams,
-plus hand-worked examples of the LIFO order this build chose.
+plus hand-worked examples of the LIFO order chosen here.
 """
 import numpy as np
 import pytest
