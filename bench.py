@@ -72,14 +72,12 @@ def contiguous_copy_reference(torch, K, nbytes, reps=10):
     return 2 * nbytes / (ms * 1e-3) / 1e12
 
 
-def direct_paths(torch, K, pool, shape, pairs, link, steps=10):
-    """The optional paths without staging, outside the timed region: the gather kernel writes into /
-    the scatter kernel reads from the pinned buffer itself (link-bound kernels, no HBM stage)."""
+def variant(torch, K, pool, shape, pairs, link, note, steps=10, **opts):
+    """The same agent through a context with other options, outside the timed region."""
     L, NB, pb = shape.num_layers, shape.num_blocks, shape.page_bytes
     n = len(pairs[0][0])
     payload = n * 2 * L * pb
-    rc, ctx = K.tc_create(pool, None, L, NB, pb, shape.block_size, 0, host_arena_bytes=payload + 2 * L * pb,
-                          direct_offload=1, direct_upload=1)
+    rc, ctx = K.tc_create(pool, None, L, NB, pb, shape.block_size, 0, host_arena_bytes=payload + 2 * L * pb, **opts)
     K.check(rc)
     rc, host = K.tc_host_alloc(ctx, n)
     K.check(rc)
@@ -89,6 +87,8 @@ def direct_paths(torch, K, pool, shape, pairs, link, steps=10):
         src, dst = pairs[(k + 7) % len(pairs)]
         K.check(K.tc_alloc_at(ctx, src))
         K.check(K.tc_alloc_at(ctx, dst))
+        if k == 2:
+            K.check(K.tc_set_profiling(ctx, 1))
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
         ev[0].record(stream)
         K.check(K.tc_offload(ctx, src, host, stream))
@@ -101,14 +101,19 @@ def direct_paths(torch, K, pool, shape, pairs, link, steps=10):
         if k >= 2:
             off.append(ev[0].elapsed_time(ev[1]))
             up.append(ev[1].elapsed_time(ev[2]))
+    st = K.tc_stats(ctx)[1]
     K.check(K.tc_host_free(ctx, host))
     K.check(K.tc_destroy(ctx))
     o, u = float(np.median(off)), float(np.median(up))
-    return {"note": "tc_opts.direct_offload = 1 (6 workgroups) / direct_upload = 1 (8 workgroups); not the default",
-            "offload_GBps": round(payload / o / 1e6, 3), "upload_GBps": round(payload / u / 1e6, 3),
-            "offload_ms": round(o, 4), "upload_ms": round(u, 4),
-            "pct_of_pinned_link": {"offload": round(100 * payload / o / 1e6 / link["d2h"], 2),
-                                   "upload": round(100 * payload / u / 1e6 / link["h2d"], 2)}}
+    out = {"note": note,
+           "offload_GBps": round(payload / o / 1e6, 3), "upload_GBps": round(payload / u / 1e6, 3),
+           "offload_ms": round(o, 4), "upload_ms": round(u, 4),
+           "pct_of_pinned_link": {"offload": round(100 * payload / o / 1e6 / link["d2h"], 2),
+                                  "upload": round(100 * payload / u / 1e6 / link["h2d"], 2)}}
+    if st.gather_launches and st.scatter_launches:
+        out["avg_launch_us"] = {"gather_pages": round(st.gather_ms / st.gather_launches * 1e3, 1),
+                                "scatter_pages": round(st.scatter_ms / st.scatter_launches * 1e3, 1)}
+    return out
 
 
 def cpu_baseline(shape, ids, new_ids, budget_s=12.0):
@@ -296,7 +301,13 @@ def main():
                                "upload": round(100 * up_gbps / link["h2d"], 2)},
         "roofline": dominant, "roofline_other_kernel": other,
     }
-    out["direct_paths"] = direct_paths(torch, K, pool, shape, pairs, link)
+    out["direct_paths"] = variant(torch, K, pool, shape, pairs, link,
+                                  "tc_opts.direct_offload = 1 (6 workgroups) / direct_upload = 1 (8 workgroups): no staging, "
+                                  "no DMA; not the default", direct_offload=1, direct_upload=1)
+    out["host_tail"] = variant(torch, K, pool, shape, pairs, link,
+                               "tc_opts.host_tail_div = 64: the last 1/64 of the chunk crosses the link inside the copy "
+                               "launch, so the link is not idle while the kernel runs; the launches get longer, the "
+                               "transfer shorter; not the default", host_tail_div=64)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(shape, ids_a, ids_b)
     K.check(K.tc_host_free(ctx, host))

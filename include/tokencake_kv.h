@@ -80,6 +80,11 @@ typedef struct {
     uint32_t direct_upload;     /* 0 = staged (DMA to HBM, then scatter); 1 = the scatter kernel reads the
                                    records straight from the pinned host buffer                      */
     uint32_t direct_grid;       /* workgroups of a direct gather / scatter; 0 = defaults (6 / 8)   */
+    uint32_t host_tail_div;     /* 0 = off; N >= 2: in the staged path the last 1/N of every chunk's blocks
+                                   is moved by a few workgroups of the same copy launch straight to / from
+                                   the pinned buffer, using the link while it would otherwise wait for the
+                                   kernel, and the DMA carries that much less.  Applies to chunks of at
+                                   least N blocks whose tail lies in one host buffer.  1 is invalid.       */
 } tc_opts;
 
 typedef struct {

@@ -411,6 +411,31 @@ int dma_chunk(tc_ctx *c, const Plan &plan, uint64_t c0, uint64_t c1, char *slot_
     return TC_OK;
 }
 
+// The host link is idle while a chunk's copy kernel runs.  With tc_opts.host_tail_div = N the last 1/N of
+// the chunk's blocks skips staging: a few workgroups of the same launch move them straight to / from the
+// pinned buffer while the rest of the grid streams through HBM, and the DMA carries that much less.
+// Returns how many leading blocks of the chunk [c0, c0 + nblk) still go through staging.
+uint32_t host_tail(tc_ctx *c, const Plan &plan, uint64_t c0, uint32_t nblk, void **host_part)
+{
+    const uint32_t denom = c->opts.host_tail_div;
+    *host_part = nullptr;
+    if (denom < 2 || nblk < denom) return nblk;
+    const uint32_t m = nblk / denom;
+    const uint64_t first = c0 + nblk - m;           // first record of the tail
+    for (const Segment &s : plan.segs) {
+        if (first >= s.first && c0 + nblk <= s.first + s.n) {   // the tail lies inside one agent's buffer
+            void *view = nullptr;
+            if (hipHostGetDevicePointer(&view, s.host + (first - s.first) * c->rec, 0) != hipSuccess) {
+                (void)hipGetLastError();
+                return nblk;
+            }
+            *host_part = view;
+            return nblk - m;
+        }
+    }
+    return nblk;
+}
+
 int offload_locked(tc_ctx *c, const tc_xfer_desc *descs, uint32_t n_descs, hipStream_t stream)
 {
     Plan plan;
@@ -440,7 +465,7 @@ int offload_locked(tc_ctx *c, const tc_xfer_desc *descs, uint32_t n_descs, hipSt
             const Segment &s = plan.segs[k];
             if (int rc = time_begin(c, &op, stream, uint64_t(s.n) * c->rec, kDirect)) return rc;
             HIP_TRY(tc::launch_gather_pages(c->pool.kv_base, static_cast<const uint32_t *>(c->pool.scales), dev_view[k],
-                                            c->ids_dev + ring_start + s.first, s.n, c->geom, grid, true, stream));
+                                            c->ids_dev + ring_start + s.first, s.n, c->geom, grid, true, stream, nullptr, s.n, 0));
             if (int rc = time_end(c, &op, stream)) return rc;
         }
         HIP_TRY(hipEventRecord(op.done, stream));
@@ -452,12 +477,15 @@ int offload_locked(tc_ctx *c, const tc_xfer_desc *descs, uint32_t n_descs, hipSt
             Slot *slot = &c->slots[c->next_slot];
             c->next_slot = (c->next_slot + 1) % uint32_t(c->slots.size());
             if (slot->used) HIP_TRY(hipStreamWaitEvent(stream, slot->last, 0));
+            void *host_part = nullptr;
+            const uint32_t split = host_tail(c, plan, c0, nblk, &host_part);
             if (int rc = time_begin(c, &op, stream, uint64_t(nblk) * c->rec, kGather)) return rc;
             HIP_TRY(tc::launch_gather_pages(c->pool.kv_base, static_cast<const uint32_t *>(c->pool.scales), slot->buf,
-                                            c->ids_dev + ring_start + c0, nblk, c->geom, c->opts.max_grid, false, stream));
+                                            c->ids_dev + ring_start + c0, nblk, c->geom, c->opts.max_grid, false, stream,
+                                            host_part, split, kDefaultDirectGatherGrid));
             if (int rc = time_end(c, &op, stream)) return rc;
-            if (int rc = time_begin(c, &op, stream, uint64_t(nblk) * c->rec, kD2H)) return rc;
-            if (int rc = dma_chunk(c, plan, c0, c0 + nblk, slot->buf, true, stream)) return rc;
+            if (int rc = time_begin(c, &op, stream, uint64_t(split) * c->rec, kD2H)) return rc;
+            if (int rc = dma_chunk(c, plan, c0, c0 + split, slot->buf, true, stream)) return rc;
             if (int rc = time_end(c, &op, stream)) return rc;
             HIP_TRY(hipEventRecord(slot->last, stream));
             slot->used = true;
@@ -501,7 +529,7 @@ int upload_locked(tc_ctx *c, const tc_xfer_desc *descs, uint32_t n_descs, hipStr
             const Segment &s = plan.segs[k];
             if (int rc = time_begin(c, &op, stream, uint64_t(s.n) * c->rec, kDirect)) return rc;
             HIP_TRY(tc::launch_scatter_pages(dev_view[k], c->pool.kv_base, static_cast<uint32_t *>(c->pool.scales),
-                                             c->ids_dev + ring_start + s.first, s.n, c->geom, grid, true, stream));
+                                             c->ids_dev + ring_start + s.first, s.n, c->geom, grid, true, stream, nullptr, s.n, 0));
             if (int rc = time_end(c, &op, stream)) return rc;
         }
         for (const Segment &s : plan.segs)
@@ -515,12 +543,15 @@ int upload_locked(tc_ctx *c, const tc_xfer_desc *descs, uint32_t n_descs, hipStr
             Slot *slot = &c->slots[c->next_slot];
             c->next_slot = (c->next_slot + 1) % uint32_t(c->slots.size());
             if (slot->used) HIP_TRY(hipStreamWaitEvent(stream, slot->last, 0));
-            if (int rc = time_begin(c, &op, stream, uint64_t(nblk) * c->rec, kH2D)) return rc;
-            if (int rc = dma_chunk(c, plan, c0, c0 + nblk, slot->buf, false, stream)) return rc;
+            void *host_part = nullptr;
+            const uint32_t split = host_tail(c, plan, c0, nblk, &host_part);
+            if (int rc = time_begin(c, &op, stream, uint64_t(split) * c->rec, kH2D)) return rc;
+            if (int rc = dma_chunk(c, plan, c0, c0 + split, slot->buf, false, stream)) return rc;
             if (int rc = time_end(c, &op, stream)) return rc;
             if (int rc = time_begin(c, &op, stream, uint64_t(nblk) * c->rec, kScatter)) return rc;
             HIP_TRY(tc::launch_scatter_pages(slot->buf, c->pool.kv_base, static_cast<uint32_t *>(c->pool.scales),
-                                             c->ids_dev + ring_start + c0, nblk, c->geom, c->opts.max_grid, false, stream));
+                                             c->ids_dev + ring_start + c0, nblk, c->geom, c->opts.max_grid, false, stream,
+                                             host_part, split, kDefaultDirectScatterGrid));
             if (int rc = time_end(c, &op, stream)) return rc;
             HIP_TRY(hipEventRecord(slot->last, stream));
             slot->used = true;
@@ -581,7 +612,7 @@ try {
     if (S != 0 && S != 1 && S != P) return TC_ERR_INVAL;
     if ((S != 0) != (pool->scales != nullptr)) return TC_ERR_INVAL;
     if (S && (reinterpret_cast<uintptr_t>(pool->scales) % 4)) return TC_ERR_INVAL;
-    if (opts && (opts->direct_offload > 2 || opts->direct_upload > 1)) return TC_ERR_INVAL;
+    if (opts && (opts->direct_offload > 2 || opts->direct_upload > 1 || opts->host_tail_div == 1)) return TC_ERR_INVAL;
     // one launch may cover every block of the pool: its work items (block x plane x tile, a tile being
     // at most 32 KiB of a page) are counted in 31 bits
     const uint64_t tiles_per_page = (uint64_t(pool->page_bytes) + 32767) / 32768;

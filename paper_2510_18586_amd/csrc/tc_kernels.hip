@@ -42,10 +42,18 @@ __device__ __forceinline__ void st16(u32x4 *p, u32x4 v)
 template <int U, bool NTL, bool NTS, bool GATHER, bool DIRECT>
 __global__ __launch_bounds__(kThreads) void page_copy_kernel(
     u32x4 *__restrict__ pool, uint32_t *__restrict__ scales, u32x4 *__restrict__ staging,
-    const int32_t *__restrict__ ids, uint32_t n_items, uint32_t tiles, PageGeom g)
+    const int32_t *__restrict__ ids, uint32_t n_items, uint32_t tiles, PageGeom g,
+    u32x4 *__restrict__ host_part, uint32_t split, uint32_t host_wgs)
 {
     constexpr uint32_t kTile = kThreads * U;  // 16-byte units per tile
-    for (uint32_t item = blockIdx.x; item < n_items; item += gridDim.x) {
+    // Records of blocks [0, split) live in `staging`; records of blocks [split, n) in `host_part` (pinned
+    // host memory seen from the GPU).  The first host_wgs workgroups take the host-side items, so that the
+    // link is busy from the start of the launch; everybody else takes the staging-side items.
+    const uint32_t items_staged = split * g.planes * tiles;
+    uint32_t first, last, step;
+    if (blockIdx.x < host_wgs) { first = items_staged + blockIdx.x; last = n_items; step = host_wgs; }
+    else { first = blockIdx.x - host_wgs; last = items_staged; step = gridDim.x - host_wgs; }
+    for (uint32_t item = first; item < last; item += step) {
         const uint32_t t = item % tiles;
         const uint32_t kp = item / tiles;
         const uint32_t p = kp % g.planes;
@@ -54,7 +62,8 @@ __global__ __launch_bounds__(kThreads) void page_copy_kernel(
 
         // wave-uniform bases; the lane offset stays 32-bit so loads use scalar-base addressing
         u32x4 *in_pool = pool + (uint64_t(p) * g.num_blocks + blk) * g.page16 + t * kTile;
-        u32x4 *in_stag = staging + uint64_t(k) * g.rec16 + uint64_t(p) * g.page16 + t * kTile;
+        u32x4 *record = k < split ? staging + uint64_t(k) * g.rec16 : host_part + uint64_t(k - split) * g.rec16;
+        u32x4 *in_stag = record + uint64_t(p) * g.page16 + t * kTile;
         const u32x4 *src = GATHER ? in_pool : in_stag;
         u32x4 *dst = GATHER ? in_stag : in_pool;
         const uint32_t lane = threadIdx.x;
@@ -74,7 +83,7 @@ __global__ __launch_bounds__(kThreads) void page_copy_kernel(
 
         // the record's tail: S scale words gathered from their planes, then zero pad
         if (g.tail_words && p == 0 && t == 0) {
-            uint32_t *tail = reinterpret_cast<uint32_t *>(staging + uint64_t(k) * g.rec16 + uint64_t(g.planes) * g.page16);
+            uint32_t *tail = reinterpret_cast<uint32_t *>(record + uint64_t(g.planes) * g.page16);
             for (uint32_t w = threadIdx.x; w < g.tail_words; w += kThreads) {
                 if (GATHER) tail[w] = (w < g.scales) ? scales[uint64_t(w) * g.num_blocks + blk] : 0u;
                 else if (w < g.scales) scales[uint64_t(w) * g.num_blocks + blk] = tail[w];
@@ -162,7 +171,8 @@ __global__ __launch_bounds__(kThreads) void hbm_stream_kernel(f32x4 *__restrict_
 // ---------------------------------------------------------------------------------------------
 template <bool GATHER>
 static hipError_t launch_page_copy(void *pool, uint32_t *scales, void *staging, const int32_t *ids_dev, uint32_t n,
-                                   const PageGeom &g, uint32_t max_grid, bool direct, hipStream_t stream)
+                                   const PageGeom &g, uint32_t max_grid, bool direct, hipStream_t stream,
+                                   void *host_part, uint32_t split, uint32_t host_wgs)
 {
     if (n == 0) return hipSuccess;
     // widest tile that a page still fills
@@ -179,13 +189,18 @@ static hipError_t launch_page_copy(void *pool, uint32_t *scales, void *staging, 
     const uint64_t items64 = uint64_t(n) * g.planes * tiles;
     if (items64 > 0x7fffffffull) return hipErrorInvalidValue;
     const uint32_t n_items = uint32_t(items64);
-    uint32_t grid = n_items;
+    if (split > n || (split < n && (!host_part || host_wgs == 0))) return hipErrorInvalidValue;
+    if (split == n) host_wgs = 0;
+    const uint32_t items_staged = split * g.planes * tiles;
+    uint32_t grid = items_staged;
     if (max_grid && grid > max_grid) grid = max_grid;
+    if (grid == 0 && host_wgs == 0) return hipSuccess;
+    grid += host_wgs;
 
 #define TC_LAUNCH(UU, NL, NS, DR)                                                                              \
     hipLaunchKernelGGL((page_copy_kernel<UU, NL, NS, GATHER, DR>), dim3(grid), dim3(kThreads), 0, stream,        \
                        static_cast<u32x4 *>(pool), scales, static_cast<u32x4 *>(staging), ids_dev, n_items, \
-                       tiles, g)
+                       tiles, g, static_cast<u32x4 *>(host_part), split, host_wgs)
 #define TC_LAUNCH_U(NL, NS, DR)                  \
     switch (U) {                                 \
     case 8: TC_LAUNCH(8, NL, NS, DR); break;     \
@@ -202,16 +217,19 @@ static hipError_t launch_page_copy(void *pool, uint32_t *scales, void *staging, 
 }
 
 hipError_t launch_gather_pages(const void *pool, const uint32_t *scales, void *staging, const int32_t *ids_dev,
-                               uint32_t n, const PageGeom &g, uint32_t max_grid, bool direct, hipStream_t stream)
+                               uint32_t n, const PageGeom &g, uint32_t max_grid, bool direct, hipStream_t stream,
+                               void *host_part, uint32_t split, uint32_t host_wgs)
 {
     return launch_page_copy<true>(const_cast<void *>(pool), const_cast<uint32_t *>(scales), staging, ids_dev, n, g,
-                                  max_grid, direct, stream);
+                                  max_grid, direct, stream, host_part, split, host_wgs);
 }
 
 hipError_t launch_scatter_pages(const void *staging, void *pool, uint32_t *scales, const int32_t *ids_dev,
-                                uint32_t n, const PageGeom &g, uint32_t max_grid, bool direct, hipStream_t stream)
+                                uint32_t n, const PageGeom &g, uint32_t max_grid, bool direct, hipStream_t stream,
+                                const void *host_part, uint32_t split, uint32_t host_wgs)
 {
-    return launch_page_copy<false>(pool, scales, const_cast<void *>(staging), ids_dev, n, g, max_grid, direct, stream);
+    return launch_page_copy<false>(pool, scales, const_cast<void *>(staging), ids_dev, n, g, max_grid, direct, stream,
+                                   const_cast<void *>(host_part), split, host_wgs);
 }
 
 hipError_t launch_rewrite_table(int32_t *table, const int32_t *ids_dev, uint32_t n, hipStream_t stream)

@@ -109,8 +109,8 @@ def test_pending_free_blocks_are_not_handed_out_while_the_copy_runs():
         gp.close()
 
 
-@pytest.mark.parametrize("direct", [0, 1])
-def test_batch_of_agents_shares_chunks(direct):
+@pytest.mark.parametrize("direct,tail", [(0, 0), (1, 0), (0, 2), (0, 4)])
+def test_batch_of_agents_shares_chunks(direct, tail):
     rng = W.rng_for(2, salt=3)
     shape = W.CONFIGS[1].with_blocks(128)
     L, NB, pb, P = shape.num_layers, shape.num_blocks, shape.page_bytes, shape.planes
@@ -121,7 +121,8 @@ def test_batch_of_agents_shares_chunks(direct):
     dst = np.split(perm[sum(sizes):], np.cumsum(sizes)[:-1])
     # staging: 3 slots of 4 records, so chunks straddle agents
     gp = GpuPool(shape, pool_h, None, staging_bytes=3 * 4 * 2 * 1024 * 1024, staging_slots=3,
-                 host_arena_bytes=40 * 2 * 1024 * 1024, direct_offload=direct, direct_upload=direct)
+                 host_arena_bytes=40 * 2 * 1024 * 1024, direct_offload=direct, direct_upload=direct,
+                 host_tail_div=tail)      # chunk tails inside one agent's buffer skip staging, the others do not
     try:
         rec = gp.rec
         bufs = []

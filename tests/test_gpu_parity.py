@@ -88,6 +88,19 @@ def test_8b_pages_many_chunks_ragged_tail(slots):
     _round_trip_case(shape, 1, 37, salt=slots, staging_bytes=slots * 5 * 2 * 1024 * 1024, staging_slots=slots)
 
 
+@pytest.mark.parametrize("div,slots", [(2, 1), (4, 2), (5, 3)])
+def test_host_tail_of_every_chunk_skips_staging(div, slots):
+    # chunks of 5 records: with div <= 5 the last 5 // div blocks of each full chunk go straight to / from the
+    # pinned buffer inside the same launch; the ragged last chunk (2 records) is too small for div > 2
+    shape = W.CONFIGS[1].with_blocks(96)
+    _round_trip_case(shape, 1, 37, salt=60 + div, staging_bytes=slots * 5 * 2 * 1024 * 1024, staging_slots=slots,
+                     host_tail_div=div)
+    # scales and a zero pad in the tail records, capped grid, one chunk
+    _round_trip_case(W.PoolShape("fp8-small", 3, 2, 32, 8, 1, 80, 6, "fp8"), 4, 23, salt=61 + div, host_tail_div=div, max_grid=5)
+    # ragged tiles
+    _round_trip_case(W.PoolShape("odd-ragged", 2, 5, 128, 16, 1, 40, 1, "fp8"), 4, 9, salt=62 + div, host_tail_div=div)
+
+
 def test_capped_grid_strides_over_items():
     shape = W.CONFIGS[1].with_blocks(64)
     _round_trip_case(shape, 1, 21, salt=7, max_grid=37)
@@ -139,6 +152,8 @@ def _random_case(k):
         opts.update(direct_offload=1, direct_upload=1, direct_grid=int(rng.choice([0, 1, 5])))
     elif mode == 2:
         opts.update(direct_offload=2, direct_upload=int(rng.integers(0, 2)))
+    if rng.random() < 0.5:
+        opts["host_tail_div"] = int(rng.choice([2, 3, 4, 8]))
     return shape, n, opts
 
 
@@ -153,16 +168,18 @@ def test_zero_blocks_is_a_no_op():
     _round_trip_case(W.CONFIGS[0], 0, 0, salt=3)
 
 
-def test_config2_full_size_llama3_8b():
+@pytest.mark.parametrize("host_tail_div", [0, 64])
+def test_config2_full_size_llama3_8b(host_tail_div):
     """32 layers x 8 heads x 128 x 16 tokens bf16 (2 MiB per block), 16 384 blocks (32 GiB), one agent
-    with a 4 096-token context = 256 blocks scattered uniformly; default launch configuration."""
+    with a 4 096-token context = 256 blocks scattered uniformly; default launch configuration, and the
+    one with the last 1/64 of the chunk moved over the link by the copy launch itself."""
     shape = W.CONFIGS[1]
     rng = W.rng_for(1)
     n = oracle.blocks_for_tokens(4096, shape.block_size)
     L, NB, pb, S, P = shape.num_layers, shape.num_blocks, shape.page_bytes, 0, shape.planes
     ids = W.pick_ids(rng, NB, n)
     new_ids = W.pick_ids(rng, NB, n, exclude=ids)
-    gp = GpuPool(shape, seed=W.seed_for(1))
+    gp = GpuPool(shape, seed=W.seed_for(1), host_tail_div=host_tail_div)
     try:
         rec = gp.rec
         before = gp.page_checksums()
