@@ -39,7 +39,8 @@ __device__ __forceinline__ void st16(u32x4 *p, u32x4 v)
 // consecutive staging addresses.
 // DIRECT marks the launches whose "staging" side is pinned host memory: the same code, but a
 // distinct kernel for the profiler, because those launches are bound by the host link, not by HBM.
-template <int U, bool NTL, bool NTS, bool GATHER, bool DIRECT>
+// TAIL marks the launches that also carry a host part (see below); without it that code is not there.
+template <int U, bool NTL, bool NTS, bool GATHER, bool DIRECT, bool TAIL>
 __global__ __launch_bounds__(kThreads) void page_copy_kernel(
     u32x4 *__restrict__ pool, uint32_t *__restrict__ scales, u32x4 *__restrict__ staging,
     const int32_t *__restrict__ ids, uint32_t n_items, uint32_t tiles, PageGeom g,
@@ -49,10 +50,12 @@ __global__ __launch_bounds__(kThreads) void page_copy_kernel(
     // Records of blocks [0, split) live in `staging`; records of blocks [split, n) in `host_part` (pinned
     // host memory seen from the GPU).  The first host_wgs workgroups take the host-side items, so that the
     // link is busy from the start of the launch; everybody else takes the staging-side items.
-    const uint32_t items_staged = split * g.planes * tiles;
-    uint32_t first, last, step;
-    if (blockIdx.x < host_wgs) { first = items_staged + blockIdx.x; last = n_items; step = host_wgs; }
-    else { first = blockIdx.x - host_wgs; last = items_staged; step = gridDim.x - host_wgs; }
+    uint32_t first = blockIdx.x, last = n_items, step = gridDim.x;
+    if constexpr (TAIL) {
+        const uint32_t items_staged = split * g.planes * tiles;
+        if (blockIdx.x < host_wgs) { first = items_staged + blockIdx.x; last = n_items; step = host_wgs; }
+        else { first = blockIdx.x - host_wgs; last = items_staged; step = gridDim.x - host_wgs; }
+    }
     for (uint32_t item = first; item < last; item += step) {
         const uint32_t t = item % tiles;
         const uint32_t kp = item / tiles;
@@ -62,7 +65,9 @@ __global__ __launch_bounds__(kThreads) void page_copy_kernel(
 
         // wave-uniform bases; the lane offset stays 32-bit so loads use scalar-base addressing
         u32x4 *in_pool = pool + (uint64_t(p) * g.num_blocks + blk) * g.page16 + t * kTile;
-        u32x4 *record = k < split ? staging + uint64_t(k) * g.rec16 : host_part + uint64_t(k - split) * g.rec16;
+        u32x4 *record = staging + uint64_t(k) * g.rec16;
+        if constexpr (TAIL)
+            if (k >= split) record = host_part + uint64_t(k - split) * g.rec16;
         u32x4 *in_stag = record + uint64_t(p) * g.page16 + t * kTile;
         const u32x4 *src = GATHER ? in_pool : in_stag;
         u32x4 *dst = GATHER ? in_stag : in_pool;
@@ -189,7 +194,7 @@ static hipError_t launch_page_copy(void *pool, uint32_t *scales, void *staging, 
     const uint64_t items64 = uint64_t(n) * g.planes * tiles;
     if (items64 > 0x7fffffffull) return hipErrorInvalidValue;
     const uint32_t n_items = uint32_t(items64);
-    if (split > n || (split < n && (!host_part || host_wgs == 0))) return hipErrorInvalidValue;
+    if (split > n || (split < n && (!host_part || host_wgs == 0 || direct))) return hipErrorInvalidValue;
     if (split == n) host_wgs = 0;
     const uint32_t items_staged = split * g.planes * tiles;
     uint32_t grid = items_staged;
@@ -197,20 +202,23 @@ static hipError_t launch_page_copy(void *pool, uint32_t *scales, void *staging, 
     if (grid == 0 && host_wgs == 0) return hipSuccess;
     grid += host_wgs;
 
-#define TC_LAUNCH(UU, NL, NS, DR)                                                                              \
-    hipLaunchKernelGGL((page_copy_kernel<UU, NL, NS, GATHER, DR>), dim3(grid), dim3(kThreads), 0, stream,        \
+#define TC_LAUNCH(UU, NL, NS, DR, TL)                                                                          \
+    hipLaunchKernelGGL((page_copy_kernel<UU, NL, NS, GATHER, DR, TL>), dim3(grid), dim3(kThreads), 0, stream,    \
                        static_cast<u32x4 *>(pool), scales, static_cast<u32x4 *>(staging), ids_dev, n_items, \
                        tiles, g, static_cast<u32x4 *>(host_part), split, host_wgs)
-#define TC_LAUNCH_U(NL, NS, DR)                  \
-    switch (U) {                                 \
-    case 8: TC_LAUNCH(8, NL, NS, DR); break;     \
-    case 4: TC_LAUNCH(4, NL, NS, DR); break;     \
-    case 2: TC_LAUNCH(2, NL, NS, DR); break;     \
-    default: TC_LAUNCH(1, NL, NS, DR); break;    \
+#define TC_LAUNCH_U(NL, NS, DR, TL)                  \
+    switch (U) {                                     \
+    case 8: TC_LAUNCH(8, NL, NS, DR, TL); break;     \
+    case 4: TC_LAUNCH(4, NL, NS, DR, TL); break;     \
+    case 2: TC_LAUNCH(2, NL, NS, DR, TL); break;     \
+    default: TC_LAUNCH(1, NL, NS, DR, TL); break;    \
     }
-    if (direct) { TC_LAUNCH_U(true, true, true) }
-    else if (GATHER) { TC_LAUNCH_U(true, false, false) }
-    else { TC_LAUNCH_U(true, true, false) }
+    const bool tail = host_wgs != 0;
+    if (direct) { TC_LAUNCH_U(true, true, true, false) }
+    else if (GATHER && tail) { TC_LAUNCH_U(true, false, false, true) }
+    else if (GATHER) { TC_LAUNCH_U(true, false, false, false) }
+    else if (tail) { TC_LAUNCH_U(true, true, false, true) }
+    else { TC_LAUNCH_U(true, true, false, false) }
 #undef TC_LAUNCH_U
 #undef TC_LAUNCH
     return hipGetLastError();
