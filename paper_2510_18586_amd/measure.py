@@ -495,6 +495,7 @@ def m_lds(torch, K, W, emit):
     a.view(torch.int32).random_(0, 2 ** 31 - 1)
     b = torch.zeros(n, dtype=torch.uint8, device="cuda:0")
     stream = torch.cuda.Stream()
+    torch.cuda.synchronize()        # a and b were written on torch's stream
     rows = {}
     for name, fn in (("registers (tc_copy_contiguous)", lambda: K.tc_copy_contiguous(b, a, n, stream)),
                      ("registers -> LDS -> registers", lambda: K.tc_copy_via_lds(b, a, n, 0, stream)),
@@ -511,6 +512,7 @@ def m_lds(torch, K, W, emit):
                 ts.append(e0.elapsed_time(e1) * 1e3)
         assert torch.equal(a, b)
         b.zero_()
+        torch.cuda.synchronize()
         rows[name] = dict(mean_us=round(float(np.mean(ts)), 1), best_us=round(float(min(ts)), 1),
                           TBps_of_traffic=round(2 * n / (float(np.mean(ts)) * 1e-6) / 1e12, 2))
     emit(dict(measurement="lds", MiB=512, rows=rows))
@@ -558,6 +560,7 @@ def m_host(torch, K, W, emit):
     K.check(K.tc_alloc_at(c.ctx, dst))
     rc, buf = K.tc_host_alloc(c.ctx, n)
     table = torch.zeros(n, dtype=torch.int32, device="cuda:0")
+    torch.cuda.synchronize()
     enq = {"tc_offload(256 blocks): call returns after": [], "tc_upload(256 blocks): call returns after": []}
     for _ in range(40):
         t = time.perf_counter()

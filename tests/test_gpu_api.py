@@ -30,6 +30,7 @@ def test_validation_errors_have_no_effect():
         host = pinned_bytes(8 * rec)
         host.fill_(0x5A)
         table = torch.full((8,), -9, dtype=torch.int32, device=DEV)
+        torch.cuda.synchronize()       # torch wrote this on its own stream; the library's calls run on others
         K.check(K.tc_alloc_at(gp.ctx, [3, 4, 5, 6]))
         K.check(K.tc_ref(gp.ctx, [6]))
         before = _stats(gp).as_dict()
@@ -147,6 +148,7 @@ def test_batch_of_agents_shares_chunks(direct, tail):
                 assert np.array_equal(got, want[: s * rec])
         # upload the whole batch into other blocks, one table row per agent
         tables = torch.full((len(sizes), 20), -1, dtype=torch.int32, device=DEV)
+        torch.cuda.synchronize()       # torch wrote this on its own stream; the library's calls run on others
         tables_h = np.full((len(sizes), 20), -1, dtype=np.int32)
         K.check(K.tc_alloc_at(gp.ctx, perm[sum(sizes):]))
         K.check(K.tc_upload_batch(gp.ctx, [(dst[i], bufs[i], tables[i]) for i in range(len(sizes))], stream))
@@ -185,6 +187,7 @@ def test_partial_uploads_restore_an_agent_piecewise():
         want = np.empty(n * rec, dtype=np.uint8)
         oracle.offload(pool_h, None, L, NB, pb, 0, ids, want)
         table = torch.full((n,), -1, dtype=torch.int32, device=DEV)
+        torch.cuda.synchronize()       # torch wrote this on its own stream; the library's calls run on others
         table_h = np.full(n, -1, dtype=np.int32)
         oracle.upload(want, L, NB, pb, 0, new_ids, pool_h, None, table_h)
         done = 0
@@ -306,6 +309,7 @@ def test_whole_pool_moves_in_one_call_over_many_chunks():
         assert np.array_equal(host.numpy(), want)
         new_ids = ids[::-1].copy()
         table = torch.full((NB,), -1, dtype=torch.int32, device=DEV)
+        torch.cuda.synchronize()       # torch wrote this on its own stream; the library's calls run on others
         table_h = np.full(NB, -1, dtype=np.int32)
         oracle.upload(want, L, NB, pb, 0, new_ids, pool_h, None, table_h)
         K.check(K.tc_upload(gp.ctx, host, new_ids, table))
@@ -367,6 +371,7 @@ def test_calls_from_several_host_threads():
         K.check(K.tc_alloc_at(gp.ctx, perm))
         errors, bufs = [], [None] * 4
         tables = torch.full((4, 24), -1, dtype=torch.int32, device=DEV)
+        torch.cuda.synchronize()       # torch wrote this on its own stream; the library's calls run on others
 
         def worker(k):
             try:
@@ -506,6 +511,7 @@ def test_thousands_of_small_transfers_wrap_the_id_ring():
         host_o = np.zeros(2 * gp.rec, dtype=np.uint8)
         stream = torch.cuda.Stream()
         table = torch.full((4,), -1, dtype=torch.int32, device=DEV)
+        torch.cuda.synchronize()       # torch wrote this on its own stream; the library's calls run on others
         for i in range(1500):
             n = 1 + i % 2
             src = np.array([order[(i + k) % NB] for k in range(n)], dtype=np.int32)

@@ -115,6 +115,7 @@ def test_config3_64_agents_fragmented_pool_overlapped_with_hbm_stream():
         b = torch.rand(m, device=DEV)
         c = torch.rand(m, device=DEV)
         a = torch.zeros(m, device=DEV)
+        torch.cuda.synchronize()       # torch wrote this on its own stream; the library's calls run on others
         compute, copy = torch.cuda.Stream(), torch.cuda.Stream()
         torch.cuda.synchronize()
         K.check(K.tc_hbm_stream(a, b, c, m, 0.5, 40, compute))
@@ -147,6 +148,7 @@ def test_config3_64_agents_fragmented_pool_overlapped_with_hbm_stream():
         say("config 3: uploading")
         new = [ls.alloc(int(n)) for n in nblk]
         tables = torch.full((64, int(nblk.max()) + 1), -1, dtype=torch.int32, device=DEV)
+        torch.cuda.synchronize()       # torch wrote this on its own stream; the library's calls run on others
         K.check(K.tc_upload_batch(gp.ctx, [(new[i], bufs[i], tables[i]) for i in range(64)], copy))
         ls.begin(np.concatenate(new))
         for i in range(64):
@@ -192,6 +194,7 @@ def test_config4_trace_replay_200_agents():
         arena = oracle.OracleHostArena(4096)
         stream = torch.cuda.Stream()
         tables = torch.full((len(agents), 1024 + 1), -1, dtype=torch.int32, device=DEV)
+        torch.cuda.synchronize()       # torch wrote this on its own stream; the library's calls run on others
         sample = set(int(x) for x in rng.choice(len(agents), 8, replace=False))
         mirror = SparseMirror(gp)
         st8 = [dict(state="new") for _ in agents]
@@ -223,6 +226,7 @@ def test_config4_trace_replay_200_agents():
                 ids = ls.alloc(n)
                 assert ids is not None, "the pool is sized for the trace's peak"
                 tables[i, :n] = torch.from_numpy(ids).to(DEV)
+                torch.cuda.synchronize()       # torch wrote this on its own stream; the library's calls run on others
                 s.update(state="running", ids=ids)
             elif kind == "call_start":
                 ls.sync()                               # finished uploads hand their arena slots back
@@ -306,6 +310,7 @@ def test_config5_fp8_shared_prefix_waves():
         stream = torch.cuda.Stream()
         tables = torch.full((n_agents, 1024), -1, dtype=torch.int32, device=DEV)
         tables[:, :n_prefix] = torch.from_numpy(prefix).to(DEV)
+        torch.cuda.synchronize()       # torch wrote this on its own stream; the library's calls run on others
         sampled = 0
         i = 0
         n_waves = 0
@@ -324,6 +329,7 @@ def test_config5_fp8_shared_prefix_waves():
                 rc, bufs[a] = K.tc_host_alloc(gp.ctx, int(private[a]))
                 assert rc == 0
                 tables[a, n_prefix:n_prefix + private[a]] = torch.from_numpy(ids[a]).to(DEV)
+                torch.cuda.synchronize()       # torch wrote this on its own stream; the library's calls run on others
             # the whole row must be refused, the private part is what moves
             a0 = max(wave, key=lambda a: private[a])
             row = np.concatenate([prefix, ids[a0]])

@@ -22,6 +22,7 @@ def test_copy_contiguous_is_exact_including_a_ragged_tail(nbytes):
     a = _src(nbytes, 1)
     b = torch.full((guard + nbytes + guard,), 0xEE, dtype=torch.uint8, device=DEV)
     stream = torch.cuda.Stream()
+    stream.wait_stream(torch.cuda.current_stream())      # a and b were filled on torch's current stream
     K.check(K.tc_copy_contiguous(b[guard:], a, nbytes, stream))
     stream.synchronize()
     assert torch.equal(b[guard:guard + nbytes], a)
@@ -35,6 +36,7 @@ def test_copy_via_lds_is_exact(direct_loads, nbytes):
     a = _src(nbytes, 2 + direct_loads)
     b = torch.full((guard + nbytes + guard,), 0xEE, dtype=torch.uint8, device=DEV)
     stream = torch.cuda.Stream()
+    stream.wait_stream(torch.cuda.current_stream())
     K.check(K.tc_copy_via_lds(b[guard:], a, nbytes, direct_loads, stream))
     stream.synchronize()
     assert torch.equal(b[guard:guard + nbytes], a)
@@ -62,6 +64,7 @@ def test_hbm_stream_computes_the_triad():
     c = torch.randn(n, device=DEV, generator=g)
     a = torch.zeros(n, device=DEV)
     stream = torch.cuda.Stream()
+    stream.wait_stream(torch.cuda.current_stream())
     K.check(K.tc_hbm_stream(a, b, c, n, 0.5, 2, stream))
     stream.synchronize()
     # a = b + 0.5 * c in fp32: multiplying by 0.5 is exact, so fused or not the result is the rounded sum

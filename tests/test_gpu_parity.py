@@ -53,6 +53,7 @@ def _round_trip_case(shape, seed_idx, n, salt=0, same_ids=False, **opts):
         if n and not same_ids:
             pool_h.reshape(P, NB, pb)[:, ids] = junk
             gp.pool3()[:, torch.as_tensor(ids.astype(np.int64), device=DEV)] = torch.from_numpy(junk).to(DEV)
+            torch.cuda.synchronize()       # torch wrote this on its own stream; the library's calls run on others
 
         table_h = np.full(n + 4, -1, dtype=np.int32)
         table_h[:n] = ids
@@ -197,6 +198,7 @@ def test_config2_full_size_llama3_8b(host_tail_div):
         assert torch.equal(gp.page_checksums(), before), "offload wrote the pool"
 
         table_d = torch.full((n + 2,), -1, dtype=torch.int32, device=DEV)
+        torch.cuda.synchronize()       # torch wrote this on its own stream; the library's calls run on others
         table_h = np.full(n + 2, -1, dtype=np.int32)
         oracle.upload(want_host, L, NB, pb, S, new_ids, mirror.pool, None, table_h)
         K.check(K.tc_alloc_at(gp.ctx, new_ids))

@@ -56,6 +56,7 @@ def test_cpu_hit_reclaims_original_blocks_and_uploads():
         assert set(other) <= set(int(b) for b in ids_a)
         junk = rng.integers(0, 256, size=(gp.P, 4, pb), dtype=np.uint8)
         gp.pool3()[:, torch.as_tensor(other.astype(np.int64), device=DEV)] = torch.from_numpy(junk).to(DEV)
+        torch.cuda.synchronize()       # torch wrote this on its own stream; the library's calls run on others
         mirror.reshape(gp.P, NB, pb)[:, other.astype(np.int64)] = junk
 
         # a request sharing only the first three blocks sees exactly those on the CPU side
@@ -77,6 +78,7 @@ def test_cpu_hit_reclaims_original_blocks_and_uploads():
         assert reclaimed == 10 - len(set(int(b) for b in other) & set(int(b) for b in cached)) and 0 < reclaimed < 10
 
         table = torch.full((16,), -7, dtype=torch.int32, device=DEV)
+        torch.cuda.synchronize()       # torch wrote this on its own stream; the library's calls run on others
         hit_keys = [h[0] for h in hits]
         assert K.tc_upload(gp.ctx, hits[0][2], new_ids[:10], table, stream) == 0
         assert K.tc_index_begin_upload(ix, hit_keys, new_ids[:10]) == 0

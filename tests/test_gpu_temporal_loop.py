@@ -40,6 +40,7 @@ def test_temporal_loop_on_a_seeded_trace():
         pool_model.free(pool_model.alloc(128))     # the calibration claimed and released its largest size
         lead_ms, step_ms, v_tok_per_ms = 200.0, 50.0, 4.0
         tables = torch.full((len(agents), 260), -1, dtype=torch.int32, device=DEV)
+        torch.cuda.synchronize()       # torch wrote this on its own stream; the library's calls run on others
         A = [dict(req=K.tc_req_state(0, 0, 0, 0), model=(L.RUNNING, False, False)) for _ in agents]
         counts = dict(approved=0, rejected=0, resumed_at_once=0, immediate=0, pieces=0)
 
@@ -107,6 +108,7 @@ def test_temporal_loop_on_a_seeded_trace():
             if kind == "start":
                 a["ids"] = alloc(n)
                 tables[i, :n] = torch.from_numpy(a["ids"]).to(DEV)
+                torch.cuda.synchronize()       # torch wrote this on its own stream; the library's calls run on others
             elif kind == "call_start":
                 a["t_call"] = t
                 assert lifecycle(i, L.CALL_START) == L.NONE
