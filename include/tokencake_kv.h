@@ -32,6 +32,9 @@
  *     the pool may be read once the stream (or tc_sync) has completed.  Transfers
  *     of one context that touch the same blocks or the same arena allocation are
  *     ordered among themselves even when they are put on different streams.
+ *     Against anything else the library orders nothing: work the caller has in
+ *     flight on other streams that writes the pool, a host buffer or a block
+ *     table must be ordered before `stream` by the caller (event or synchronise).
  *   - the caller owns the pool, the scales, block tables and any host buffer not
  *     obtained from tc_host_alloc.  The context owns its staging ring and arena.
  *   - one context serves one GPU (the device current at tc_create); calls on one
