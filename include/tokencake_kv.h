@@ -82,7 +82,8 @@ typedef struct {
                                    upload of this context is in flight (the two directions then overlap) */
     uint32_t direct_upload;     /* 0 = staged (DMA to HBM, then scatter); 1 = the scatter kernel reads the
                                    records straight from the pinned host buffer                      */
-    uint32_t direct_grid;       /* workgroups of a direct gather / scatter; 0 = defaults (6 / 8)   */
+    uint32_t direct_grid;       /* workgroups of a direct gather / scatter, and of a chunk's host tail
+                                   (host_tail_div); 0 = defaults (6 / 8)                           */
     uint32_t host_tail_div;     /* 0 = off; N >= 2: in the staged path the last 1/N of every chunk's blocks
                                    is moved by a few workgroups of the same copy launch straight to / from
                                    the pinned buffer, using the link while it would otherwise wait for the

@@ -482,7 +482,8 @@ int offload_locked(tc_ctx *c, const tc_xfer_desc *descs, uint32_t n_descs, hipSt
             if (int rc = time_begin(c, &op, stream, uint64_t(nblk) * c->rec, kGather)) return rc;
             HIP_TRY(tc::launch_gather_pages(c->pool.kv_base, static_cast<const uint32_t *>(c->pool.scales), slot->buf,
                                             c->ids_dev + ring_start + c0, nblk, c->geom, c->opts.max_grid, false, stream,
-                                            host_part, split, kDefaultDirectGatherGrid));
+                                            host_part, split,
+                                            c->opts.direct_grid ? c->opts.direct_grid : kDefaultDirectGatherGrid));
             if (int rc = time_end(c, &op, stream)) return rc;
             if (int rc = time_begin(c, &op, stream, uint64_t(split) * c->rec, kD2H)) return rc;
             if (int rc = dma_chunk(c, plan, c0, c0 + split, slot->buf, true, stream)) return rc;
@@ -551,7 +552,8 @@ int upload_locked(tc_ctx *c, const tc_xfer_desc *descs, uint32_t n_descs, hipStr
             if (int rc = time_begin(c, &op, stream, uint64_t(nblk) * c->rec, kScatter)) return rc;
             HIP_TRY(tc::launch_scatter_pages(slot->buf, c->pool.kv_base, static_cast<uint32_t *>(c->pool.scales),
                                              c->ids_dev + ring_start + c0, nblk, c->geom, c->opts.max_grid, false, stream,
-                                             host_part, split, kDefaultDirectScatterGrid));
+                                             host_part, split,
+                                             c->opts.direct_grid ? c->opts.direct_grid : kDefaultDirectScatterGrid));
             if (int rc = time_end(c, &op, stream)) return rc;
             HIP_TRY(hipEventRecord(slot->last, stream));
             slot->used = true;
