@@ -23,6 +23,7 @@
 #include <hip/hip_runtime_api.h>
 
 #include "tc_blocks.h"
+#include "tc_geom.h"
 #include "tc_kernels.h"
 #include "tokencake_kv.h"
 
@@ -606,19 +607,10 @@ int tc_create(const tc_pool_desc *pool, const tc_opts *opts, tc_ctx **out)
 try {
     if (!pool || !out) return TC_ERR_INVAL;
     *out = nullptr;
-    if (!pool->kv_base || pool->num_layers == 0 || pool->num_blocks == 0 || pool->page_bytes == 0) return TC_ERR_INVAL;
-    if (pool->page_bytes % 16 || (reinterpret_cast<uintptr_t>(pool->kv_base) % 256)) return TC_ERR_INVAL;
-    if (pool->num_blocks > 0x7fffffffu || pool->num_layers > (1u << 20)) return TC_ERR_INVAL;
+    if (int rc = tc::check_pool_desc(pool)) return rc;
     const uint32_t P = 2 * pool->num_layers;
     const uint32_t S = pool->scales_per_block;
-    if (S != 0 && S != 1 && S != P) return TC_ERR_INVAL;
-    if ((S != 0) != (pool->scales != nullptr)) return TC_ERR_INVAL;
-    if (S && (reinterpret_cast<uintptr_t>(pool->scales) % 4)) return TC_ERR_INVAL;
     if (opts && (opts->direct_offload > 2 || opts->direct_upload > 1 || opts->host_tail_div == 1)) return TC_ERR_INVAL;
-    // one launch may cover every block of the pool: its work items (block x plane x tile, a tile being
-    // at most 32 KiB of a page) are counted in 31 bits
-    const uint64_t tiles_per_page = (uint64_t(pool->page_bytes) + 32767) / 32768;
-    if (uint64_t(pool->num_blocks) * P * tiles_per_page > 0x7fffffffull) return TC_ERR_INVAL;
     if (!is_device_ptr(pool->kv_base) || (S && !is_device_ptr(pool->scales))) return TC_ERR_NOT_PINNED;
 
     tc_ctx *c = new (std::nothrow) tc_ctx;
@@ -630,14 +622,8 @@ try {
     } undo{c};
     c->pool = *pool;
     if (opts) c->opts = *opts;
-    const uint64_t raw = uint64_t(P) * pool->page_bytes + 4ull * S;
-    c->rec = (raw + 255) / 256 * 256;
-    c->geom.planes = P;
-    c->geom.page16 = pool->page_bytes / 16;
-    c->geom.num_blocks = pool->num_blocks;
-    c->geom.rec16 = c->rec / 16;
-    c->geom.scales = S;
-    c->geom.tail_words = uint32_t((c->rec - uint64_t(P) * pool->page_bytes) / 4);
+    c->rec = tc::record_bytes_of(P, pool->page_bytes, S);
+    c->geom = tc::make_geom(*pool);
 
     uint32_t n_slots = c->opts.staging_slots ? c->opts.staging_slots : kDefaultSlots;
     if (n_slots < 1) n_slots = 1;

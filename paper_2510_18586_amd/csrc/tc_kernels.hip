@@ -19,7 +19,7 @@ namespace tc {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr uint32_t kThreads = 256;
+constexpr uint32_t kThreads = kCopyThreads;
 
 template <bool NT>
 __device__ __forceinline__ u32x4 ld16(const u32x4 *p)
@@ -180,17 +180,14 @@ static hipError_t launch_page_copy(void *pool, uint32_t *scales, void *staging, 
                                    void *host_part, uint32_t split, uint32_t host_wgs)
 {
     if (n == 0) return hipSuccess;
-    // widest tile that a page still fills
-    int U = 8;
-    while (U > 1 && uint64_t(kThreads) * U > g.page16) U >>= 1;
+    const uint32_t U = tile_units(g.page16);  // widest tile that a page still fills
     // Cache policy, measured on MI355X with cold 512 MiB launches in the offload -> upload sequence:
     // non-temporal loads help both directions.  The gather's staging writes stay ordinary
     // write-back stores: they are absorbed by the memory-side cache and drain to HBM while the
     // slow host-link DMA that follows reads them.  The scatter's page writes are non-temporal, so
     // it leaves no dirty lines for the next kernel to evict (with ordinary stores the scatter looks
     // faster and the following gather pays for it; the sum is worse).
-    const uint32_t tile16 = kThreads * U;
-    const uint32_t tiles = (g.page16 + tile16 - 1) / tile16;
+    const uint32_t tiles = tiles_per_page(g.page16);
     const uint64_t items64 = uint64_t(n) * g.planes * tiles;
     if (items64 > 0x7fffffffull) return hipErrorInvalidValue;
     const uint32_t n_items = uint32_t(items64);
