@@ -59,6 +59,7 @@ extern "C" {
 #define TC_ERR_HOST_NOMEM (-6) /* pinned arena has no run of slots that fits; host OOM */
 #define TC_ERR_NOT_PINNED (-7) /* host buffer is not pinned / device ptr is not device */
 #define TC_ERR_HIP (-8)        /* a HIP runtime call failed                          */
+#define TC_ERR_LIMIT (-9)      /* beyond the fixed capacity of tc_offload_noalloc    */
 
 typedef struct tc_ctx tc_ctx;
 
@@ -186,6 +187,27 @@ int tc_upload(tc_ctx *ctx, const void *host_buf, const int32_t *new_block_ids, u
  * enqueued still runs and the transfer must be treated as failed). */
 int tc_offload_batch(tc_ctx *ctx, const tc_xfer_desc *descs, uint32_t n_descs, void *stream);
 int tc_upload_batch(tc_ctx *ctx, const tc_xfer_desc *descs, uint32_t n_descs, void *stream);
+
+/* For callers that cannot allocate: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  The same offload as tc_offload (record j of host_buf <- block block_ids[j],
+ * gather_pages into a device staging chunk, then one D2H copy, all enqueued on `stream`), but with no
+ * context: the staging chunk and the device copy of the ids live in a fixed device array that is part
+ * of the library's code object (TC_NOALLOC_STAGING_BYTES + 4 KiB on every GPU the library is used on,
+ * held until the process ends), and the call makes no hipMalloc / hipFree / event or heap allocation.
+ *   pool       HOST pointer to the description (kv_base / scales are DEVICE memory, the caller's)
+ *   block_ids  HOST, n distinct ids in [0, num_blocks); read before the call returns
+ *   host_buf   HOST pinned, 16-B aligned, n records; valid once `stream` has completed
+ * Limits: n <= TC_NOALLOC_MAX_BLOCKS and n * record bytes <= TC_NOALLOC_STAGING_BYTES, else TC_ERR_LIMIT
+ * (a message on stderr says which).  Other errors as tc_offload (TC_ERR_INVAL, TC_ERR_RANGE, TC_ERR_DUP,
+ * TC_ERR_NOT_PINNED, TC_ERR_HIP); an error means nothing was enqueued, except TC_ERR_HIP.
+ * There is no bookkeeping: the caller keeps the blocks from being rewritten until `stream` completes.
+ * All calls on one GPU share the one array, which keeps the previous call's bytes (nothing in it needs
+ * clearing: each call writes all it reads): calls on the same stream are ordered, calls that overlap on
+ * different streams of one GPU race and must be ordered by the caller. */
+#define TC_NOALLOC_MAX_BLOCKS 1024u
+#define TC_NOALLOC_STAGING_BYTES (64ull << 20)
+int tc_offload_noalloc(const tc_pool_desc *pool, const int32_t *block_ids, uint32_t n, void *host_buf,
+                       void *stream);
 
 /* Retires completed transfers in issue order (pending-free -> free); never blocks. */
 int tc_poll(tc_ctx *ctx);

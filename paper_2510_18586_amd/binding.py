@@ -13,7 +13,8 @@ from . import build as _build
 
 __all__ = [
     "TC_OK", "TC_ERR_INVAL", "TC_ERR_RANGE", "TC_ERR_DUP", "TC_ERR_SHARED", "TC_ERR_NOMEM",
-    "TC_ERR_HOST_NOMEM", "TC_ERR_NOT_PINNED", "TC_ERR_HIP",
+    "TC_ERR_HOST_NOMEM", "TC_ERR_NOT_PINNED", "TC_ERR_HIP", "TC_ERR_LIMIT",
+    "TC_NOALLOC_MAX_BLOCKS", "TC_NOALLOC_STAGING_BYTES", "tc_offload_noalloc",
     "TcError", "check", "tc_pool_desc", "tc_opts", "tc_xfer_desc", "tc_stats_t", "library_path",
     "tc_create", "tc_destroy", "tc_record_bytes", "tc_strerror", "tc_alloc", "tc_alloc_at", "tc_ref",
     "tc_free", "tc_filter_private", "tc_host_alloc", "tc_host_free", "tc_offload", "tc_upload",
@@ -33,7 +34,8 @@ __all__ = [
 
 TC_OK = 0
 TC_ERR_INVAL, TC_ERR_RANGE, TC_ERR_DUP, TC_ERR_SHARED = -1, -2, -3, -4
-TC_ERR_NOMEM, TC_ERR_HOST_NOMEM, TC_ERR_NOT_PINNED, TC_ERR_HIP = -5, -6, -7, -8
+TC_ERR_NOMEM, TC_ERR_HOST_NOMEM, TC_ERR_NOT_PINNED, TC_ERR_HIP, TC_ERR_LIMIT = -5, -6, -7, -8, -9
+TC_NOALLOC_MAX_BLOCKS, TC_NOALLOC_STAGING_BYTES = 1024, 64 << 20
 TC_RES_ABSENT, TC_RES_CPU, TC_RES_H2D = 0, 1, 2
 TC_FNV_BASIS = 0xCBF29CE484222325
 TC_GATE_PASS, TC_GATE_CPU_FULL, TC_GATE_STALL_SHORT, TC_GATE_NO_FIT, TC_GATE_LOW_PRESSURE = 0, 1, 2, 3, 4
@@ -173,6 +175,7 @@ def _load():
         "tc_host_free": (ci, [vp, vp]),
         "tc_offload": (ci, [vp, vp, u32, vp, vp]),
         "tc_upload": (ci, [vp, vp, vp, u32, vp, vp]),
+        "tc_offload_noalloc": (ci, [ctypes.POINTER(tc_pool_desc), vp, u32, vp, vp]),
         "tc_offload_batch": (ci, [vp, ctypes.POINTER(tc_xfer_desc), u32, vp]),
         "tc_upload_batch": (ci, [vp, ctypes.POINTER(tc_xfer_desc), u32, vp]),
         "tc_poll": (ci, [vp]),
@@ -332,6 +335,14 @@ def tc_offload(ctx, block_ids, host_buf, stream=None):
 def tc_upload(ctx, host_buf, new_block_ids, block_table=None, stream=None):
     a, p, n = _ids(new_block_ids)
     return _load().tc_upload(ctx, _ptr(host_buf), p, n, _ptr(block_table), _stream(stream))
+
+
+def tc_offload_noalloc(kv_base, scales, num_layers, num_blocks, page_bytes, block_size_tokens, scales_per_block,
+                       block_ids, host_buf, stream=None):
+    desc = tc_pool_desc(_ptr(kv_base), _ptr(scales), num_layers, num_blocks, page_bytes, block_size_tokens,
+                        scales_per_block)
+    a, p, n = _ids(block_ids)
+    return _load().tc_offload_noalloc(ctypes.byref(desc), p, n, _ptr(host_buf), _stream(stream))
 
 
 def _descs(items):

@@ -710,6 +710,7 @@ const char *tc_strerror(int code)
     case TC_ERR_HOST_NOMEM: return "pinned host arena exhausted";
     case TC_ERR_NOT_PINNED: return "host buffer is not pinned, or a device pointer is not device memory";
     case TC_ERR_HIP: return "HIP runtime call failed";
+    case TC_ERR_LIMIT: return "transfer exceeds the fixed capacity of the entry point that does not allocate";
     default: return "unknown tokencake_kv error";
     }
 }

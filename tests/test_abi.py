@@ -36,7 +36,7 @@ def test_binding_covers_every_declared_symbol():
 
 def test_error_strings_and_struct_layout():
     assert K.tc_strerror(K.TC_OK) == "ok"
-    for code in range(-8, 0):
+    for code in range(-9, 0):
         assert K.tc_strerror(code) and "unknown" not in K.tc_strerror(code)
     assert "unknown" in K.tc_strerror(-99)
     # the ctypes mirrors must match the C layout (checked against sizes the compiler would give)
