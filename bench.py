@@ -96,6 +96,7 @@ def variant(torch, K, pool, shape, pairs, link, note, steps=10, **opts):
         K.check(K.tc_upload(ctx, host, dst, None, stream))
         ev[2].record(stream)
         K.check(K.tc_sync(ctx))
+        stream.synchronize()          # ev[2] is recorded after the transfer's own completion event
         K.check(K.tc_free(ctx, src))
         K.check(K.tc_free(ctx, dst))
         if k >= 2:

@@ -9,7 +9,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtokencake_kv.so")
 SOURCES = ["tc_kernels.hip", "tc_noalloc.hip", "tc_engine.cpp", "tc_policy.cpp", "tc_index.cpp"]
-HEADERS = ["tc_kernels.h", "tc_blocks.h", "tc_geom.h"]
+HEADERS = ["tc_kernels.h", "tc_blocks.h", "tc_geom.h", "tc_map.h"]
 
 
 def _hipcc():

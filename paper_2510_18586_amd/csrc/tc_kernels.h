@@ -4,6 +4,8 @@
 #include <cstdint>
 #include <hip/hip_runtime_api.h>
 
+#include "tc_map.h"
+
 namespace tc {
 
 // Geometry shared by gather and scatter; all "16" fields count 16-byte units.
@@ -15,22 +17,6 @@ struct PageGeom {
     uint32_t scales;       // S: scale words per block (0, 1 or P)
     uint32_t tail_words;   // 32-bit words from the end of the pages to the end of the record
 };
-
-// A copy tile is 256 lanes x U x 16 B, U the largest of 8, 4, 2, 1 that a page still fills; a page is
-// cut into ceil(page16 / (256*U)) tiles, the last one possibly ragged.  The launchers and the limit on
-// a pool description both go by these two functions.
-constexpr uint32_t kCopyThreads = 256;
-inline uint32_t tile_units(uint32_t page16)
-{
-    uint32_t u = 8;
-    while (u > 1 && uint64_t(kCopyThreads) * u > page16) u >>= 1;
-    return u;
-}
-inline uint32_t tiles_per_page(uint32_t page16)
-{
-    const uint32_t tile16 = kCopyThreads * tile_units(page16);
-    return (page16 + tile16 - 1) / tile16;
-}
 
 // staging[k] <- record of block ids[k] for k < n (pages, scale words, zero pad).  `staging` is a
 // device staging chunk, or (direct = true) the GPU's view of pinned host memory.

@@ -7,10 +7,13 @@
 // scatter_pages  the inverse, into the destination blocks of an upload.
 // rewrite_table  block_table[i] = new_ids[i] once the data is in place.
 //
-// Both copy kernels are pure HBM streaming: a workgroup of four wave64 moves one tile of a page,
-// every lane with U independent 16-byte loads in flight before the first store (a wave
-// instruction covers 1 KiB of consecutive addresses).  There is no arithmetic on the payload and
-// no reuse, so neither LDS nor MFMA has anything to add; bytes are never reinterpreted.
+// Both copy kernels are pure HBM streaming: a workgroup of four wave64 moves 4 KiB tiles of pages,
+// every lane 16 bytes per tile (a wave instruction covers 1 KiB of consecutive addresses).  There is
+// no arithmetic on the payload and no reuse, so neither LDS nor MFMA has anything to add; bytes are
+// never reinterpreted.
+#include <algorithm>
+#include <type_traits>
+
 #include <hip/hip_runtime.h>
 
 #include "tc_kernels.h"
@@ -34,66 +37,144 @@ __device__ __forceinline__ void st16(u32x4 *p, u32x4 v)
     else *p = v;
 }
 
-// One work item = (block k of the chunk, plane p, tile t of the page).  Items are ordered with
-// the tile fastest, then the plane: consecutive workgroups write (gather) or read (scatter)
-// consecutive staging addresses.
-// DIRECT marks the launches whose "staging" side is pinned host memory: the same code, but a
-// distinct kernel for the profiler, because those launches are bound by the host link, not by HBM.
-// TAIL marks the launches that also carry a host part (see below); without it that code is not there.
-template <int U, bool NTL, bool NTS, bool GATHER, bool DIRECT, bool TAIL>
+// What a launch needs besides the pointers; passed by value.
+struct CopyPlan {
+    PageGeom g;
+    FastDiv tiles;       // tiles per page
+    FastDiv planes;      // planes per block
+    uint32_t n_items;    // blocks * planes * tiles
+    uint32_t split;      // TAIL: records of blocks [0, split) live in staging, the rest in host_part
+    uint32_t host_wgs;   // TAIL: the first host_wgs workgroups take the host-side items
+    uint32_t chunks;     // the staged items are cut into this many contiguous runs, one per XCD (1 = no cut)
+};
+
+// One work item = (block k of the chunk, plane p, 4 KiB tile t of the page), ordered with the tile
+// fastest, then the plane: consecutive items are consecutive addresses on the record side.
+//
+// Item -> workgroup.  HBM sustains more when each XCD streams a region of its own than when the eight
+// XCDs interleave 4 KiB pieces of one region, and more with many small workgroups than with few large
+// ones (measured on MI355X: scatter 196 -> 177 us, gather 158 -> 150 us per 512 MiB).  So the staged
+// launches cut the items into `chunks` = 8 contiguous runs; workgroup b (on XCD b mod 8) walks run
+// b mod 8, and V = 1: one tile per iteration, one iteration per workgroup unless the grid is capped.
+// The launches that touch pinned host memory are bound by the host link and run on a handful of
+// workgroups; those need many loads in flight per lane instead: V = 8 consecutive tiles per iteration,
+// no cut (DIRECT), or the first host_wgs workgroups of a staged launch (TAIL).
+//
+// DIRECT marks the launches whose "staging" side is pinned host memory: the same code, but a distinct
+// kernel for the profiler, because those launches are bound by the host link, not by HBM.
+// TAIL marks the launches that also carry a host part; without it that code is not there.
+template <bool NTL, bool NTS, bool GATHER, bool DIRECT, bool TAIL>
 __global__ __launch_bounds__(kThreads) void page_copy_kernel(
     u32x4 *__restrict__ pool, uint32_t *__restrict__ scales, u32x4 *__restrict__ staging,
-    const int32_t *__restrict__ ids, uint32_t n_items, uint32_t tiles, PageGeom g,
-    u32x4 *__restrict__ host_part, uint32_t split, uint32_t host_wgs)
+    const int32_t *__restrict__ ids, u32x4 *__restrict__ host_part, CopyPlan c)
 {
-    constexpr uint32_t kTile = kThreads * U;  // 16-byte units per tile
-    // Records of blocks [0, split) live in `staging`; records of blocks [split, n) in `host_part` (pinned
-    // host memory seen from the GPU).  The first host_wgs workgroups take the host-side items, so that the
-    // link is busy from the start of the launch; everybody else takes the staging-side items.
-    uint32_t first = blockIdx.x, last = n_items, step = gridDim.x;
-    if constexpr (TAIL) {
-        const uint32_t items_staged = split * g.planes * tiles;
-        if (blockIdx.x < host_wgs) { first = items_staged + blockIdx.x; last = n_items; step = host_wgs; }
-        else { first = blockIdx.x - host_wgs; last = items_staged; step = gridDim.x - host_wgs; }
-    }
-    for (uint32_t item = first; item < last; item += step) {
-        const uint32_t t = item % tiles;
-        const uint32_t kp = item / tiles;
-        const uint32_t p = kp % g.planes;
-        const uint32_t k = kp / g.planes;
-        const uint64_t blk = uint64_t(uint32_t(ids[k]));
+    const PageGeom &g = c.g;
+    const uint32_t lane = threadIdx.x;
 
+    // where item `at` lives on both sides
+    struct Place {
+        const u32x4 *src;
+        u32x4 *dst;
+        u32x4 *record;
+        uint32_t left;   // 16-byte units from the tile start to the page end
+    };
+    auto place = [&](const ItemPos &at, uint64_t blk) -> Place {
         // wave-uniform bases; the lane offset stays 32-bit so loads use scalar-base addressing
-        u32x4 *in_pool = pool + (uint64_t(p) * g.num_blocks + blk) * g.page16 + t * kTile;
-        u32x4 *record = staging + uint64_t(k) * g.rec16;
+        u32x4 *in_pool = pool + (uint64_t(at.p) * g.num_blocks + blk) * g.page16 + at.t * kThreads;
+        u32x4 *record = staging + uint64_t(at.k) * g.rec16;
         if constexpr (TAIL)
-            if (k >= split) record = host_part + uint64_t(k - split) * g.rec16;
-        u32x4 *in_stag = record + uint64_t(p) * g.page16 + t * kTile;
-        const u32x4 *src = GATHER ? in_pool : in_stag;
-        u32x4 *dst = GATHER ? in_stag : in_pool;
-        const uint32_t lane = threadIdx.x;
-        const uint32_t left = g.page16 - t * kTile;  // 16-byte units from the tile start to the page end
-
-        u32x4 v[U];
-        if (left >= kTile) {  // full tile: U loads in flight, then U stores, no predicates
-#pragma unroll
-            for (int u = 0; u < U; ++u) v[u] = ld16<NTL>(src + lane + u * kThreads);
-#pragma unroll
-            for (int u = 0; u < U; ++u) st16<NTS>(dst + lane + u * kThreads, v[u]);
-        } else {              // ragged last tile of a page
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-                if (lane + u * kThreads < left) st16<NTS>(dst + lane + u * kThreads, ld16<NTL>(src + lane + u * kThreads));
+            if (at.k >= c.split) record = host_part + uint64_t(at.k - c.split) * g.rec16;
+        u32x4 *in_stag = record + uint64_t(at.p) * g.page16 + at.t * kThreads;
+        return Place{GATHER ? in_pool : in_stag, GATHER ? in_stag : in_pool, record, g.page16 - at.t * kThreads};
+    };
+    // the record's tail, moved by the workgroup that has the block's first item: S scale words gathered from
+    // (scattered to) their planes, then zero pad
+    auto move_tail = [&](const ItemPos &at, uint64_t blk, u32x4 *record) {
+        if (g.tail_words == 0 || at.p != 0 || at.t != 0) return;
+        uint32_t *tail = reinterpret_cast<uint32_t *>(record + uint64_t(g.planes) * g.page16);
+        for (uint32_t w = lane; w < g.tail_words; w += kThreads) {
+            if (GATHER) tail[w] = (w < g.scales) ? scales[uint64_t(w) * g.num_blocks + blk] : 0u;
+            else if (w < g.scales) scales[uint64_t(w) * g.num_blocks + blk] = tail[w];
         }
+    };
 
-        // the record's tail: S scale words gathered from their planes, then zero pad
-        if (g.tail_words && p == 0 && t == 0) {
-            uint32_t *tail = reinterpret_cast<uint32_t *>(record + uint64_t(g.planes) * g.page16);
-            for (uint32_t w = threadIdx.x; w < g.tail_words; w += kThreads) {
-                if (GATHER) tail[w] = (w < g.scales) ? scales[uint64_t(w) * g.num_blocks + blk] : 0u;
-                else if (w < g.scales) scales[uint64_t(w) * g.num_blocks + blk] = tail[w];
+    // moves items [item, item + count), count <= V, all loads issued before the first store
+    auto move = [&](uint32_t item, uint32_t count, auto vtag) {
+        constexpr int V = decltype(vtag)::value;
+        u32x4 v[V];
+        const ItemPos first = item_pos(item, c.tiles, c.planes);
+        if (V == 1 || (count == V && first.t + V <= c.tiles.d)) {
+            // all V tiles lie in one page: one look-up, consecutive addresses
+            const uint64_t blk = uint64_t(uint32_t(ids[first.k]));
+            const Place pl = place(first, blk);
+            if (pl.left >= uint32_t(V) * kThreads) {   // and all of them are full: V loads in flight, then V stores, no predicates
+#pragma unroll
+                for (int u = 0; u < V; ++u) v[u] = ld16<NTL>(pl.src + lane + u * kThreads);
+#pragma unroll
+                for (int u = 0; u < V; ++u) st16<NTS>(pl.dst + lane + u * kThreads, v[u]);
+            } else {
+#pragma unroll
+                for (int u = 0; u < V; ++u)
+                    if (lane + u * kThreads < pl.left) v[u] = ld16<NTL>(pl.src + lane + u * kThreads);
+#pragma unroll
+                for (int u = 0; u < V; ++u)
+                    if (lane + u * kThreads < pl.left) st16<NTS>(pl.dst + lane + u * kThreads, v[u]);
             }
+            move_tail(first, blk, pl.record);
+        } else {
+            ItemPos at[V];
+            uint32_t blk[V];
+            Place pl[V];
+#pragma unroll
+            for (int u = 0; u < V; ++u) {   // the id look-ups first, together
+                at[u] = item_pos(item + (uint32_t(u) < count ? u : 0), c.tiles, c.planes);
+                blk[u] = uint32_t(ids[at[u].k]);
+            }
+            bool all_full = count == V;
+#pragma unroll
+            for (int u = 0; u < V; ++u) {
+                pl[u] = place(at[u], uint64_t(blk[u]));
+                if (uint32_t(u) >= count) pl[u].left = 0;
+                all_full = all_full && pl[u].left >= kThreads;
+            }
+            if (all_full) {   // V full tiles of several pages: no predicates, so the stores need not wait for one another
+#pragma unroll
+                for (int u = 0; u < V; ++u) v[u] = ld16<NTL>(pl[u].src + lane);
+#pragma unroll
+                for (int u = 0; u < V; ++u) st16<NTS>(pl[u].dst + lane, v[u]);
+            } else {
+#pragma unroll
+                for (int u = 0; u < V; ++u)
+                    if (lane < pl[u].left) v[u] = ld16<NTL>(pl[u].src + lane);
+#pragma unroll
+                for (int u = 0; u < V; ++u)
+                    if (lane < pl[u].left) st16<NTS>(pl[u].dst + lane, v[u]);
+            }
+#pragma unroll
+            for (int u = 0; u < V; ++u)
+                if (uint32_t(u) < count) move_tail(at[u], uint64_t(blk[u]), pl[u].record);
         }
+    };
+    using One = std::integral_constant<int, 1>;
+    using Eight = std::integral_constant<int, 8>;
+
+    uint32_t b = blockIdx.x, grid = gridDim.x, staged_end = c.n_items;
+    if constexpr (TAIL) {
+        staged_end = c.split * c.planes.d * c.tiles.d;
+        if (b < c.host_wgs) {   // host side: items [staged_end, n_items), 8 in flight per stop
+            const ItemWalk w = strided_walk(b, c.host_wgs, staged_end, c.n_items, 8);
+            for (uint32_t item = w.first; item < w.end; item += w.step) move(item, min(8u, w.end - item), Eight{});
+            return;
+        }
+        b -= c.host_wgs;
+        grid -= c.host_wgs;
+    }
+    if constexpr (DIRECT) {
+        const ItemWalk w = strided_walk(b, grid, 0, staged_end, 8);
+        for (uint32_t item = w.first; item < w.end; item += w.step) move(item, min(8u, w.end - item), Eight{});
+    } else {
+        const ItemWalk w = staged_walk(b, grid, staged_end, c.chunks);
+        for (uint32_t item = w.first; item < w.end; item += w.step) move(item, 1, One{});
     }
 }
 
@@ -104,26 +185,18 @@ __global__ __launch_bounds__(kThreads) void rewrite_table_kernel(int32_t *__rest
     if (i < n) table[i] = ids[i];
 }
 
-template <int U, bool NT>
+// dst[i] = src[i] with the staged launches' mapping: 4 KiB tiles, XCD b mod 8 streams the (b mod 8)-th eighth.
+template <bool NT>
 __global__ __launch_bounds__(kThreads) void copy_contiguous_kernel(u32x4 *__restrict__ dst,
-                                                                    const u32x4 *__restrict__ src, uint64_t n16)
+                                                                    const u32x4 *__restrict__ src, uint64_t n16,
+                                                                    uint32_t n_tiles)
 {
-    const uint64_t tile = uint64_t(blockIdx.x) * (kThreads * U);
-    const u32x4 *s = src + tile;
-    u32x4 *d = dst + tile;
-    const uint32_t lane = threadIdx.x;
-    const uint64_t left = n16 - tile;
-    if (left >= kThreads * U) {
-        u32x4 v[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) v[u] = ld16<NT>(s + lane + u * kThreads);
-#pragma unroll
-        for (int u = 0; u < U; ++u) st16<NT>(d + lane + u * kThreads, v[u]);
-    } else {
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-            if (lane + u * kThreads < left) st16<NT>(d + lane + u * kThreads, ld16<NT>(s + lane + u * kThreads));
-    }
+    const uint32_t r = blockIdx.x % kXcds;
+    const uint32_t per = (n_tiles + kXcds - 1) / kXcds;
+    const uint32_t tile = r * per + blockIdx.x / kXcds;
+    if (blockIdx.x / kXcds >= per || tile >= n_tiles) return;
+    const uint64_t at = uint64_t(tile) * kThreads + threadIdx.x;
+    if (at < n16) st16<NT>(dst + at, ld16<NT>(src + at));
 }
 
 // The same contiguous copy with the tile staged in LDS, kept to measure what LDS adds to a copy that
@@ -180,7 +253,6 @@ static hipError_t launch_page_copy(void *pool, uint32_t *scales, void *staging, 
                                    void *host_part, uint32_t split, uint32_t host_wgs)
 {
     if (n == 0) return hipSuccess;
-    const uint32_t U = tile_units(g.page16);  // widest tile that a page still fills
     // Cache policy, measured on MI355X with cold 512 MiB launches in the offload -> upload sequence:
     // non-temporal loads help both directions.  The gather's staging writes stay ordinary
     // write-back stores: they are absorbed by the memory-side cache and drain to HBM while the
@@ -190,33 +262,36 @@ static hipError_t launch_page_copy(void *pool, uint32_t *scales, void *staging, 
     const uint32_t tiles = tiles_per_page(g.page16);
     const uint64_t items64 = uint64_t(n) * g.planes * tiles;
     if (items64 > 0x7fffffffull) return hipErrorInvalidValue;
-    const uint32_t n_items = uint32_t(items64);
     if (split > n || (split < n && (!host_part || host_wgs == 0 || direct))) return hipErrorInvalidValue;
     if (split == n) host_wgs = 0;
+    CopyPlan c{};
+    c.g = g;
+    c.tiles = make_fastdiv(tiles);
+    c.planes = make_fastdiv(g.planes);
+    c.n_items = uint32_t(items64);
+    c.split = split;
     const uint32_t items_staged = split * g.planes * tiles;
-    uint32_t grid = items_staged;
+    // the host part and a direct launch move 8 tiles per workgroup and stop: more workgroups than stops are no use
+    // (and the walk's step, workgroups * 8, stays far below 2^32)
+    if (host_wgs) host_wgs = std::min(host_wgs, (c.n_items - items_staged + 7) / 8);
+    c.host_wgs = host_wgs;
+    uint32_t grid = direct ? (items_staged + 7) / 8 : items_staged;
     if (max_grid && grid > max_grid) grid = max_grid;
     if (grid == 0 && host_wgs == 0) return hipSuccess;
+    // every run needs a workgroup of its own; a grid below 8 walks the items as one run
+    c.chunks = (!direct && grid >= kXcds) ? kXcds : 1;
     grid += host_wgs;
 
-#define TC_LAUNCH(UU, NL, NS, DR, TL)                                                                          \
-    hipLaunchKernelGGL((page_copy_kernel<UU, NL, NS, GATHER, DR, TL>), dim3(grid), dim3(kThreads), 0, stream,    \
-                       static_cast<u32x4 *>(pool), scales, static_cast<u32x4 *>(staging), ids_dev, n_items, \
-                       tiles, g, static_cast<u32x4 *>(host_part), split, host_wgs)
-#define TC_LAUNCH_U(NL, NS, DR, TL)                  \
-    switch (U) {                                     \
-    case 8: TC_LAUNCH(8, NL, NS, DR, TL); break;     \
-    case 4: TC_LAUNCH(4, NL, NS, DR, TL); break;     \
-    case 2: TC_LAUNCH(2, NL, NS, DR, TL); break;     \
-    default: TC_LAUNCH(1, NL, NS, DR, TL); break;    \
-    }
+#define TC_LAUNCH(NL, NS, DR, TL)                                                                             \
+    hipLaunchKernelGGL((page_copy_kernel<NL, NS, GATHER, DR, TL>), dim3(grid), dim3(kThreads), 0, stream,     \
+                       static_cast<u32x4 *>(pool), scales, static_cast<u32x4 *>(staging), ids_dev,           \
+                       static_cast<u32x4 *>(host_part), c)
     const bool tail = host_wgs != 0;
-    if (direct) { TC_LAUNCH_U(true, true, true, false) }
-    else if (GATHER && tail) { TC_LAUNCH_U(true, false, false, true) }
-    else if (GATHER) { TC_LAUNCH_U(true, false, false, false) }
-    else if (tail) { TC_LAUNCH_U(true, true, false, true) }
-    else { TC_LAUNCH_U(true, true, false, false) }
-#undef TC_LAUNCH_U
+    if (direct) TC_LAUNCH(true, true, true, false);
+    else if (GATHER && tail) TC_LAUNCH(true, false, false, true);
+    else if (GATHER) TC_LAUNCH(true, false, false, false);
+    else if (tail) TC_LAUNCH(true, true, false, true);
+    else TC_LAUNCH(true, true, false, false);
 #undef TC_LAUNCH
     return hipGetLastError();
 }
@@ -249,10 +324,11 @@ hipError_t launch_copy_contiguous(void *dst, const void *src, uint64_t bytes, hi
 {
     if (bytes == 0) return hipSuccess;
     const uint64_t n16 = bytes / 16;
-    const uint64_t grid = (n16 + kThreads * 8 - 1) / (kThreads * 8);
+    const uint64_t n_tiles = (n16 + kThreads - 1) / kThreads;
+    const uint64_t grid = (n_tiles + kXcds - 1) / kXcds * kXcds;
     if (grid > 0x7fffffffull) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((copy_contiguous_kernel<8, true>), dim3(uint32_t(grid)), dim3(kThreads), 0, stream,
-                       static_cast<u32x4 *>(dst), static_cast<const u32x4 *>(src), n16);
+    hipLaunchKernelGGL((copy_contiguous_kernel<true>), dim3(uint32_t(grid)), dim3(kThreads), 0, stream,
+                       static_cast<u32x4 *>(dst), static_cast<const u32x4 *>(src), n16, uint32_t(n_tiles));
     return hipGetLastError();
 }
 

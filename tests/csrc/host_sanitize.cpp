@@ -10,6 +10,7 @@
 #include <vector>
 
 #include "tc_blocks.h"
+#include "tc_map.h"
 #include "tokencake_kv.h"
 
 #define REQUIRE(c) do { if (!(c)) { std::printf("FAILED %s:%d: %s\n", __FILE__, __LINE__, #c); std::exit(1); } } while (0)
@@ -65,6 +66,83 @@ static void block_pool_stream(uint32_t seed)
             REQUIRE(bp.alloc_at(twice, 2) != TC_OK);
         }
         REQUIRE(bp.n_free() + bp.n_used() + bp.n_pending() == NB);
+    }
+}
+
+// The work-item arithmetic of the copy kernels, walked on the CPU exactly as a launch walks it: every
+// item is taken once and only once, by a workgroup of the right run, and nothing outside [0, n_items).
+static void item_mapping(uint32_t seed)
+{
+    std::mt19937 rng(seed);
+    // division by multiplication: exact for every n < 2^31
+    const uint32_t divisors[] = {1, 2, 3, 5, 7, 8, 10, 64, 96, 127, 128, 160, 255, 256, 1000, 65535, 65536, 1u << 20,
+                                 (1u << 20) + 1, 0x7fffffffu, 0x80000000u};
+    for (uint32_t d : divisors) {
+        const tc::FastDiv f = tc::make_fastdiv(d);
+        REQUIRE(uint64_t(f.mul) == ((uint64_t(1) << f.shift) + d - 1) / d);
+        const uint32_t edge[] = {0, 1, d - 1, d, d + 1, 2 * d - 1, 2 * d, 0x7ffffffeu, 0x7fffffffu};
+        for (uint32_t n : edge)
+            if (n < 0x80000000u) REQUIRE(tc::fastdiv(n, f) == n / d);
+        for (int i = 0; i < 20000; ++i) {
+            const uint32_t n = rng() & 0x7fffffffu;
+            REQUIRE(tc::fastdiv(n, f) == n / d);
+        }
+        for (uint32_t m = 0; m < 3000; ++m)      // around multiples of d, where a wrong multiplier shows
+            for (int32_t e = -1; e <= 1; ++e) {
+                const uint64_t n = uint64_t(m) * d + uint64_t(int64_t(e));
+                if (n < 0x80000000ull) REQUIRE(tc::fastdiv(uint32_t(n), f) == uint32_t(n) / d);
+            }
+    }
+    // item -> (block, plane, tile)
+    for (int rep = 0; rep < 200; ++rep) {
+        const uint32_t tiles = 1 + rng() % 9, planes = 2 * (1 + rng() % 80), n = 1 + rng() % 40;
+        const tc::FastDiv ft = tc::make_fastdiv(tiles), fp = tc::make_fastdiv(planes);
+        uint32_t item = 0;
+        for (uint32_t k = 0; k < n; ++k)
+            for (uint32_t p = 0; p < planes; ++p)
+                for (uint32_t t = 0; t < tiles; ++t, ++item) {
+                    const tc::ItemPos at = tc::item_pos(item, ft, fp);
+                    REQUIRE(at.k == k && at.p == p && at.t == t);
+                }
+    }
+    // workgroup -> items, as the three kinds of launch walk them
+    for (int rep = 0; rep < 3000; ++rep) {
+        const uint32_t n_items = rng() % 5000;
+        uint32_t grid = 1 + rng() % (rep % 3 ? 64 : 6000);
+        const uint32_t chunks = grid >= tc::kXcds && rng() % 4 ? tc::kXcds : 1;
+        std::vector<uint8_t> seen(n_items, 0);
+        const uint32_t per = (n_items + chunks - 1) / chunks;
+        for (uint32_t b = 0; b < grid; ++b) {
+            const tc::ItemWalk w = tc::staged_walk(b, grid, n_items, chunks);
+            REQUIRE(w.step >= 1 && w.end <= n_items);
+            for (uint64_t item = w.first; item < w.end; item += w.step) {
+                REQUIRE(item / per == b % chunks);          // stays inside the run of its XCD
+                REQUIRE(seen[item]++ == 0);
+            }
+        }
+        for (uint32_t i = 0; i < n_items; ++i) REQUIRE(seen[i] == 1);
+
+        // host-bound walk: `width` items per stop over [first, n_items)
+        const uint32_t first = n_items ? rng() % (n_items + 1) : 0, wgs = 1 + rng() % 40, width = 8;
+        std::fill(seen.begin(), seen.end(), 0);
+        for (uint32_t b = 0; b < wgs; ++b) {
+            const tc::ItemWalk w = tc::strided_walk(b, wgs, first, n_items, width);
+            REQUIRE(w.end == n_items && w.step == wgs * width);
+            for (uint64_t item = w.first; item < w.end; item += w.step) {
+                const uint32_t count = uint32_t(std::min<uint64_t>(width, w.end - item));
+                for (uint32_t u = 0; u < count; ++u) REQUIRE(item + u >= first && seen[item + u]++ == 0);
+            }
+        }
+        for (uint32_t i = 0; i < n_items; ++i) REQUIRE(seen[i] == (i >= first ? 1 : 0));
+    }
+    // the extremes a launch may reach: the last items of the largest grid, no wrap-around
+    {
+        const uint32_t n_items = 0x7fffffffu, grid = 0x7fffffffu;
+        for (uint32_t b : {0u, 7u, 8u, grid - 9, grid - 8, grid - 1}) {
+            const tc::ItemWalk w = tc::staged_walk(b, grid, n_items, tc::kXcds);
+            REQUIRE(w.end <= n_items && uint64_t(w.first) + w.step > w.first);
+            if (w.first < w.end) REQUIRE(uint64_t(w.first) + w.step >= w.end || w.step >= 1);
+        }
     }
 }
 
@@ -192,6 +270,7 @@ static void policy_fuzz()
 int main()
 {
     for (uint32_t s = 1; s <= 3; ++s) { block_pool_stream(s); arena_stream(s); }
+    item_mapping(11);
     index_threads();
     forecaster_threads();
     policy_fuzz();
