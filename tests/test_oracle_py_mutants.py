@@ -13,6 +13,7 @@ import test_oracle_block_pool as pins_pool
 import test_oracle_lifecycle as pins_life
 import test_oracle_policy as pins_policy
 import test_oracle_residency as pins_res
+import test_oracle_transfer_plan as pins_plan
 
 ODIR = os.path.dirname(oracle.__file__)
 
@@ -88,6 +89,26 @@ CASES = {
         "a key entered twice replaces the first": ("            if k in self.entries:\n                raise OracleError(\"DUP\", f\"key {k:#x} is already CPU-resident\")", "            pass"),
         "pending counts CPU-resident entries": ("[ABSENT])[0] == H2D)", "[ABSENT])[0] != ABSENT)"),
     },
+    ("transfer_plan.py", pins_plan, ("T",)): {
+        "a request may wrap around the end of the ring": ("        if tail + n > self.cap:\n            skipped = self.cap - tail\n            start = 0\n", ""),
+        "the skipped tail is not counted": ("if self.used() + skipped + n > self.cap:", "if self.used() + n > self.cap:"),
+        "an empty ring goes on where it stopped": ("        if not self.live:\n            return 0\n        start, n, _ = self.live[-1]", "        if not self.live:\n            return 3\n        start, n, _ = self.live[-1]"),
+        "the ring releases the newest span": ("        return self.live.pop(0)\n\n    def cancel_newest", "        return self.live.pop()\n\n    def cancel_newest"),
+        "uploads cut the list like offloads": ("return sizes[::-1] if upload else sizes", "return sizes"),
+        "a chunk may exceed its slot": ("take = min(int(slot_blocks), left)", "take = min(int(slot_blocks) + 1, left)"),
+        "pieces are placed by their list position": ("out.append((k, a - first, a - c0, b - a))", "out.append((k, a - first, a, b - a))"),
+        "pieces start at the buffer's head": ("out.append((k, a - first, a - c0, b - a))", "out.append((k, 0, a - c0, b - a))"),
+        "a tail may straddle two buffers": ("if first >= s_first and c0 + nblk <= s_first + s_n:", "if first >= s_first and first < s_first + s_n:"),
+        "the tail is the head of the chunk": ("first = c0 + nblk - m", "first = c0"),
+        "the first toucher counts": ("                if x in op[index]:\n                    last = op", "                if x in op[index] and last is None:\n                    last = op"),
+        "same-stream transfers are waited for too": ("if last is not None and last[1] != stream:", "if last is not None:"),
+        "host buffers carry no hazard": ("for what, index in ((block_ids, 2), (arena_starts, 3)):", "for what, index in ((block_ids, 2),):"),
+        "a large offload goes direct": ("return DIRECT if (upload_in_flight or total_bytes < auto_direct_bytes) else STAGED", "return DIRECT if (upload_in_flight or total_bytes >= auto_direct_bytes) else STAGED"),
+        "duplex is ignored": ("return DIRECT if (upload_in_flight or total_bytes < auto_direct_bytes) else STAGED", "return DIRECT if total_bytes < auto_direct_bytes else STAGED"),
+        "uploads are staged unless forced": ("return STAGED if mode == PATH_STAGED else DIRECT", "return DIRECT if mode == PATH_DIRECT else STAGED"),
+        "a single chunk gets a tail": ("return auto_div if n_chunks > 1 else 0", "return auto_div"),
+        "a failed transfer gives its span back": ("        op.update(ticket=self.next_ticket, failed=failed)\n", "        op.update(ticket=self.next_ticket, failed=failed)\n        if failed:\n            self.ring.cancel_newest()\n"),
+    },
 }
 
 ALL = [(key, name) for key, d in CASES.items() for name in d]
@@ -126,7 +147,7 @@ def test_planted_mistake_is_caught(key, name):
     saved = {s: getattr(pin_module, s) for s in swap}
     try:
         for s in swap:
-            setattr(pin_module, s, mutant if s in ("policy", "L", "R") else getattr(mutant, s))
+            setattr(pin_module, s, mutant if s in ("policy", "L", "R", "T") else getattr(mutant, s))
         failed = _failing(pin_module)
     finally:
         for s, v in saved.items():
