@@ -73,23 +73,35 @@ typedef struct {
     uint32_t scales_per_block;  /* 0, 1 or 2*num_layers                                            */
 } tc_pool_desc;
 
+enum { TC_PATH_AUTO = 0, TC_PATH_DIRECT = 1, TC_PATH_DIRECT_IF_DUPLEX = 2, TC_PATH_STAGED = 3 };
+
 typedef struct {
     uint64_t host_arena_bytes;  /* pinned arena, allocated once; 0 = none (caller brings buffers)  */
     uint64_t staging_bytes;     /* device staging ring in total; 0 = default                       */
     uint32_t staging_slots;     /* ring depth, >= 1; 0 = default                                   */
     uint32_t max_grid;          /* cap on workgroups per gather/scatter launch; 0 = one per tile   */
-    uint32_t direct_offload;    /* 0 = staged (gather to HBM, then DMA); 1 = the gather kernel writes the
-                                   records straight into the pinned host buffer; 2 = direct only while an
-                                   upload of this context is in flight (the two directions then overlap) */
-    uint32_t direct_upload;     /* 0 = staged (DMA to HBM, then scatter); 1 = the scatter kernel reads the
-                                   records straight from the pinned host buffer                      */
+    uint32_t direct_offload;    /* which path an offload takes: TC_PATH_AUTO (0, the default) = direct when the
+                                   transfer is below auto_direct_bytes or while an upload of this context is
+                                   in flight (kernel-driven D2H traffic overlaps with H2D traffic on the link,
+                                   two DMAs take turns), staged otherwise; TC_PATH_DIRECT = the gather kernel
+                                   writes the records straight into the pinned host buffer, no staging, no
+                                   DMA; TC_PATH_DIRECT_IF_DUPLEX = direct only while an upload is in flight;
+                                   TC_PATH_STAGED = always gather into device staging, then DMA           */
+    uint32_t direct_upload;     /* TC_PATH_AUTO (0) and TC_PATH_DIRECT = the scatter kernel reads the records
+                                   straight from the pinned host buffer (never slower than DMA + scatter, and
+                                   one pass through HBM instead of three); TC_PATH_STAGED = DMA into device
+                                   staging, then scatter.  With TC_PATH_AUTO a host buffer the GPU cannot map
+                                   falls back to staging; with TC_PATH_DIRECT it is TC_ERR_NOT_PINNED          */
     uint32_t direct_grid;       /* workgroups of a direct gather / scatter, and of a chunk's host tail
                                    (host_tail_div); 0 = defaults (6 / 8)                           */
-    uint32_t host_tail_div;     /* 0 = off; N >= 2: in the staged path the last 1/N of every chunk's blocks
-                                   is moved by a few workgroups of the same copy launch straight to / from
-                                   the pinned buffer, using the link while it would otherwise wait for the
-                                   kernel, and the DMA carries that much less.  Applies to chunks of at
-                                   least N blocks whose tail lies in one host buffer.  1 is invalid.       */
+    uint32_t host_tail_div;     /* staged path only: the last 1/N of every chunk's blocks is moved by a few
+                                   workgroups of the same copy launch straight to / from the pinned buffer,
+                                   using the link while it would otherwise wait for the kernel, and the DMA
+                                   carries that much less.  0 = automatic (N = 64 for transfers of more than
+                                   one chunk, none otherwise), 1 = never, N >= 2 = that N.  Applies to chunks
+                                   of at least N blocks whose tail lies in one host buffer.               */
+    uint64_t auto_direct_bytes; /* TC_PATH_AUTO: offloads below this many record bytes go direct; 0 = default
+                                   (128 MiB, the measured crossover on MI355X)                            */
 } tc_opts;
 
 typedef struct {
@@ -115,6 +127,7 @@ typedef struct {
     uint64_t d2h_copies, h2d_copies;          /* timed DMA chunks (all copies of one chunk together) */
     uint64_t d2h_bytes, h2d_bytes;
     double d2h_ms, h2d_ms;                    /* event pairs on the stream around each chunk's DMAs */
+    uint64_t transfers_failed;                /* transfer calls that returned TC_ERR_HIP after validation */
 } tc_stats_t;
 
 /* ---- life cycle ------------------------------------------------------------------------- */
@@ -123,7 +136,7 @@ typedef struct {
  * `opts` may be NULL for defaults.  The pool and the scales stay the caller's and must outlive the
  * context.  TC_ERR_INVAL for a bad description (zero sizes, page_bytes not a multiple of 16,
  * misaligned base, scales_per_block not in {0, 1, 2*num_layers}, scales given xor announced, an option
- * out of range, num_blocks * 2*num_layers * ceil(page_bytes / 32 KiB) above 2^31 - 1), TC_ERR_NOT_PINNED when kv_base / scales are not device memory, TC_ERR_HOST_NOMEM /
+ * out of range, num_blocks * 2*num_layers * ceil(page_bytes / 4 KiB) above 2^31 - 1), TC_ERR_NOT_PINNED when kv_base / scales are not device memory, TC_ERR_HOST_NOMEM /
  * TC_ERR_HIP when an allocation fails; *out is NULL on any error. */
 int tc_create(const tc_pool_desc *pool, const tc_opts *opts, tc_ctx **out);
 /* Waits for every transfer in flight, then frees what the context owns (staging, rings, arena:
@@ -183,8 +196,12 @@ int tc_upload(tc_ctx *ctx, const void *host_buf, const int32_t *new_block_ids, u
  * Errors of all four transfer calls: TC_ERR_INVAL (NULL where data is expected, misaligned host
  * buffer, buffer longer than its arena allocation, unallocated block), TC_ERR_RANGE, TC_ERR_DUP,
  * TC_ERR_SHARED, TC_ERR_NOT_PINNED (host buffer not pinned, block table not device memory),
- * TC_ERR_HIP (a runtime call failed while enqueueing; the bookkeeping is rolled back, work already
- * enqueued still runs and the transfer must be treated as failed). */
+ * TC_ERR_HIP (a runtime call failed while enqueueing).  After TC_ERR_HIP the transfer must be treated as
+ * failed and its destination (host records, or destination blocks and table entries) as undefined: part
+ * of it may already be on the stream and still run.  Nothing that such work can read is reused early:
+ * the transfer stays in flight, its blocks stay in flight (a tc_free on them gives pending-free), its
+ * arena allocation and its span of device ids stay held, all until tc_poll / tc_sync retire it; if not
+ * even its completion event could be recorded, the stream is drained inside the failing call instead. */
 int tc_offload_batch(tc_ctx *ctx, const tc_xfer_desc *descs, uint32_t n_descs, void *stream);
 int tc_upload_batch(tc_ctx *ctx, const tc_xfer_desc *descs, uint32_t n_descs, void *stream);
 
@@ -375,24 +392,6 @@ uint64_t tc_index_size(const tc_index *ix);
 uint64_t tc_fnv1a64(const void *data, uint64_t len, uint64_t basis);
 int tc_chain_hashes(const int32_t *tokens, uint64_t n_tokens, uint32_t block_size, uint64_t parent,
                     uint64_t *out, uint64_t *n_out);
-
-/* ---- measurement helpers: not on the hot path ------------------------------------------- */
-/* dst[i] = src[i]: contiguous DEVICE->DEVICE copy with the gather kernel's access width; the
- * "achievable HBM" reference and the calibration kernel for the traffic counters.
- * bytes must be a multiple of 16. */
-int tc_copy_contiguous(void *dst, const void *src, uint64_t bytes, void *stream);
-/* The same DEVICE->DEVICE copy with every tile staged in LDS: lds_direct_loads = 0 goes through
- * registers into LDS and back, 1 uses LDS-direct loads.  Kept to measure what LDS staging adds to
- * a copy without reuse (on MI355X it is 3 to 10 % slower than the register path).  bytes must be a multiple of 16 384, both
- * pointers 16-B aligned, the ranges must not overlap; TC_ERR_INVAL otherwise. */
-int tc_copy_via_lds(void *dst, const void *src, uint64_t bytes, int lds_direct_loads, void *stream);
-/* `iters` launches of a[i] = b[i] + s*c[i] over n fp32 (DEVICE): the HBM-streaming neighbour that
- * the copy stream is overlapped with.  n must be a multiple of 4. */
-int tc_hbm_stream(float *a, const float *b, const float *c, uint64_t n, float s, uint32_t iters, void *stream);
-/* Comparators without a gather kernel: mode 0 = one hipMemcpyAsync per page, mode 1 = one
- * hipMemcpy2DAsync per block.  direction 0 = offload, 1 = upload.  No bookkeeping. */
-int tc_naive_transfer(tc_ctx *ctx, const int32_t *block_ids, uint32_t n, void *host_buf, int mode,
-                      int direction, void *stream);
 
 #ifdef __cplusplus
 }

@@ -15,6 +15,8 @@ __all__ = [
     "TC_OK", "TC_ERR_INVAL", "TC_ERR_RANGE", "TC_ERR_DUP", "TC_ERR_SHARED", "TC_ERR_NOMEM",
     "TC_ERR_HOST_NOMEM", "TC_ERR_NOT_PINNED", "TC_ERR_HIP", "TC_ERR_LIMIT",
     "TC_NOALLOC_MAX_BLOCKS", "TC_NOALLOC_STAGING_BYTES", "tc_offload_noalloc",
+    "TC_PATH_AUTO", "TC_PATH_DIRECT", "TC_PATH_DIRECT_IF_DUPLEX", "TC_PATH_STAGED",
+    "tc_hbm_write", "tc_hbm_read", "tc_stage_on_device",
     "TcError", "check", "tc_pool_desc", "tc_opts", "tc_xfer_desc", "tc_stats_t", "library_path",
     "tc_create", "tc_destroy", "tc_record_bytes", "tc_strerror", "tc_alloc", "tc_alloc_at", "tc_ref",
     "tc_free", "tc_filter_private", "tc_host_alloc", "tc_host_free", "tc_offload", "tc_upload",
@@ -36,6 +38,7 @@ TC_OK = 0
 TC_ERR_INVAL, TC_ERR_RANGE, TC_ERR_DUP, TC_ERR_SHARED = -1, -2, -3, -4
 TC_ERR_NOMEM, TC_ERR_HOST_NOMEM, TC_ERR_NOT_PINNED, TC_ERR_HIP, TC_ERR_LIMIT = -5, -6, -7, -8, -9
 TC_NOALLOC_MAX_BLOCKS, TC_NOALLOC_STAGING_BYTES = 1024, 64 << 20
+TC_PATH_AUTO, TC_PATH_DIRECT, TC_PATH_DIRECT_IF_DUPLEX, TC_PATH_STAGED = 0, 1, 2, 3
 TC_RES_ABSENT, TC_RES_CPU, TC_RES_H2D = 0, 1, 2
 TC_FNV_BASIS = 0xCBF29CE484222325
 TC_GATE_PASS, TC_GATE_CPU_FULL, TC_GATE_STALL_SHORT, TC_GATE_NO_FIT, TC_GATE_LOW_PRESSURE = 0, 1, 2, 3, 4
@@ -55,7 +58,7 @@ class tc_opts(ctypes.Structure):
         ("host_arena_bytes", ctypes.c_uint64), ("staging_bytes", ctypes.c_uint64),
         ("staging_slots", ctypes.c_uint32), ("max_grid", ctypes.c_uint32),
         ("direct_offload", ctypes.c_uint32), ("direct_upload", ctypes.c_uint32), ("direct_grid", ctypes.c_uint32),
-        ("host_tail_div", ctypes.c_uint32),
+        ("host_tail_div", ctypes.c_uint32), ("auto_direct_bytes", ctypes.c_uint64),
     ]
 
 
@@ -82,6 +85,7 @@ class tc_stats_t(ctypes.Structure):
         ("d2h_copies", ctypes.c_uint64), ("h2d_copies", ctypes.c_uint64),
         ("d2h_bytes", ctypes.c_uint64), ("h2d_bytes", ctypes.c_uint64),
         ("d2h_ms", ctypes.c_double), ("h2d_ms", ctypes.c_double),
+        ("transfers_failed", ctypes.c_uint64),
     ]
 
     def as_dict(self):
@@ -185,6 +189,9 @@ def _load():
         "tc_arena_base": (vp, [vp]),
         "tc_copy_contiguous": (ci, [vp, vp, u64, vp]),
         "tc_copy_via_lds": (ci, [vp, vp, u64, ci, vp]),
+        "tc_hbm_write": (ci, [vp, u64, vp]),
+        "tc_hbm_read": (ci, [vp, u64, vp]),
+        "tc_stage_on_device": (ci, [vp, ci, vp, u32, vp, vp]),
         "tc_hbm_stream": (ci, [vp, vp, vp, u64, ctypes.c_float, u32, vp]),
         "tc_naive_transfer": (ci, [vp, vp, u32, vp, ci, ci, vp]),
         "tc_cost_fit": (ci, [vp, vp, vp, u32, ctypes.POINTER(tc_cost_model)]),
@@ -254,12 +261,12 @@ def _stream(s):
 # ------------------------------------------------------------------ the calls
 def tc_create(kv_base, scales, num_layers, num_blocks, page_bytes, block_size_tokens, scales_per_block=0,
               host_arena_bytes=0, staging_bytes=0, staging_slots=0, max_grid=0, direct_offload=0, direct_upload=0, direct_grid=0,
-              host_tail_div=0):
+              host_tail_div=0, auto_direct_bytes=0):
     """Returns (rc, ctx); ctx is an opaque handle (int) or None."""
     desc = tc_pool_desc(_ptr(kv_base), _ptr(scales), num_layers, num_blocks, page_bytes, block_size_tokens,
                         scales_per_block)
     opts = tc_opts(host_arena_bytes, staging_bytes, staging_slots, max_grid, direct_offload, direct_upload,
-                   direct_grid, host_tail_div)
+                   direct_grid, host_tail_div, auto_direct_bytes)
     out = ctypes.c_void_p()
     rc = _load().tc_create(ctypes.byref(desc), ctypes.byref(opts), ctypes.byref(out))
     return rc, out.value
@@ -395,6 +402,19 @@ def tc_copy_contiguous(dst, src, nbytes, stream=None):
 
 def tc_copy_via_lds(dst, src, nbytes, lds_direct_loads=0, stream=None):
     return _load().tc_copy_via_lds(_ptr(dst), _ptr(src), nbytes, int(lds_direct_loads), _stream(stream))
+
+
+def tc_hbm_write(dst, nbytes, stream=None):
+    return _load().tc_hbm_write(_ptr(dst), nbytes, _stream(stream))
+
+
+def tc_hbm_read(src, nbytes, stream=None):
+    return _load().tc_hbm_read(_ptr(src), nbytes, _stream(stream))
+
+
+def tc_stage_on_device(ctx, direction, block_ids, dev_records, stream=None):
+    a, p, n = _ids(block_ids)
+    return _load().tc_stage_on_device(ctx, direction, p, n, _ptr(dev_records), _stream(stream))
 
 
 def tc_hbm_stream(a, b, c, n, s=0.5, iters=1, stream=None):

@@ -9,7 +9,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtokencake_kv.so")
 SOURCES = ["tc_kernels.hip", "tc_noalloc.hip", "tc_engine.cpp", "tc_policy.cpp", "tc_index.cpp"]
-HEADERS = ["tc_kernels.h", "tc_blocks.h", "tc_geom.h", "tc_map.h"]
+HEADERS = ["tc_kernels.h", "tc_blocks.h", "tc_geom.h", "tc_map.h", "tc_plan.h", "tc_engine_core.h"]
 
 
 def _hipcc():
@@ -20,7 +20,7 @@ def is_stale():
     if not os.path.exists(LIB):
         return True
     t = os.path.getmtime(LIB)
-    deps = [os.path.join(CSRC, f) for f in SOURCES + HEADERS] + [os.path.join(ROOT, "include", "tokencake_kv.h")]
+    deps = [os.path.join(CSRC, f) for f in SOURCES + HEADERS] + [os.path.join(ROOT, "include", h) for h in ("tokencake_kv.h", "tokencake_kv_bench.h")]
     return any(os.path.getmtime(d) > t for d in deps)
 
 

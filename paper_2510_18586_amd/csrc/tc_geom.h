@@ -6,7 +6,7 @@
 
 #include <cstdint>
 
-#include "tc_kernels.h"
+#include "tc_map.h"
 #include "tokencake_kv.h"
 
 namespace tc {

@@ -8,16 +8,6 @@
 
 namespace tc {
 
-// Geometry shared by gather and scatter; all "16" fields count 16-byte units.
-struct PageGeom {
-    uint32_t planes;       // P = 2 * layers
-    uint32_t page16;       // page_bytes / 16
-    uint64_t num_blocks;   // NB
-    uint64_t rec16;        // host-record bytes / 16
-    uint32_t scales;       // S: scale words per block (0, 1 or P)
-    uint32_t tail_words;   // 32-bit words from the end of the pages to the end of the record
-};
-
 // staging[k] <- record of block ids[k] for k < n (pages, scale words, zero pad).  `staging` is a
 // device staging chunk, or (direct = true) the GPU's view of pinned host memory.
 // A launch may be split: records of blocks [0, split) go to `staging`, those of [split, n) to
@@ -35,6 +25,8 @@ hipError_t launch_scatter_pages(const void *staging, void *pool, uint32_t *scale
 hipError_t launch_rewrite_table(int32_t *table, const int32_t *ids_dev, uint32_t n, hipStream_t stream);
 
 hipError_t launch_copy_contiguous(void *dst, const void *src, uint64_t bytes, hipStream_t stream);
+// One-way stream over `bytes` (a multiple of 4 KiB): non-temporal stores of a pattern, or loads alone.
+hipError_t launch_hbm_one_way(void *p, uint64_t bytes, bool write, hipStream_t stream);
 // The same copy staged through LDS (bytes must be a multiple of 16 KiB); measurement only.
 hipError_t launch_copy_via_lds(void *dst, const void *src, uint64_t bytes, bool lds_direct_loads, hipStream_t stream);
 hipError_t launch_hbm_stream(float *a, const float *b, const float *c, uint64_t n, float s, uint32_t iters,

@@ -37,17 +37,6 @@ __device__ __forceinline__ void st16(u32x4 *p, u32x4 v)
     else *p = v;
 }
 
-// What a launch needs besides the pointers; passed by value.
-struct CopyPlan {
-    PageGeom g;
-    FastDiv tiles;       // tiles per page
-    FastDiv planes;      // planes per block
-    uint32_t n_items;    // blocks * planes * tiles
-    uint32_t split;      // TAIL: records of blocks [0, split) live in staging, the rest in host_part
-    uint32_t host_wgs;   // TAIL: the first host_wgs workgroups take the host-side items
-    uint32_t chunks;     // the staged items are cut into this many contiguous runs, one per XCD (1 = no cut)
-};
-
 // One work item = (block k of the chunk, plane p, 4 KiB tile t of the page), ordered with the tile
 // fastest, then the plane: consecutive items are consecutive addresses on the record side.
 //
@@ -80,12 +69,11 @@ __global__ __launch_bounds__(kThreads) void page_copy_kernel(
     };
     auto place = [&](const ItemPos &at, uint64_t blk) -> Place {
         // wave-uniform bases; the lane offset stays 32-bit so loads use scalar-base addressing
-        u32x4 *in_pool = pool + (uint64_t(at.p) * g.num_blocks + blk) * g.page16 + at.t * kThreads;
-        u32x4 *record = staging + uint64_t(at.k) * g.rec16;
-        if constexpr (TAIL)
-            if (at.k >= c.split) record = host_part + uint64_t(at.k - c.split) * g.rec16;
-        u32x4 *in_stag = record + uint64_t(at.p) * g.page16 + at.t * kThreads;
-        return Place{GATHER ? in_pool : in_stag, GATHER ? in_stag : in_pool, record, g.page16 - at.t * kThreads};
+        const ItemPlace w = item_place(at, blk, g, TAIL ? c.split : 0xffffffffu);
+        u32x4 *in_pool = pool + w.pool16;
+        u32x4 *record = (TAIL && w.in_host_part ? host_part : staging) + w.record16;
+        u32x4 *in_stag = record + w.tile16;
+        return Place{GATHER ? in_pool : in_stag, GATHER ? in_stag : in_pool, record, w.left};
     };
     // the record's tail, moved by the workgroup that has the block's first item: S scale words gathered from
     // (scattered to) their planes, then zero pad
@@ -158,24 +146,14 @@ __global__ __launch_bounds__(kThreads) void page_copy_kernel(
     using One = std::integral_constant<int, 1>;
     using Eight = std::integral_constant<int, 8>;
 
-    uint32_t b = blockIdx.x, grid = gridDim.x, staged_end = c.n_items;
-    if constexpr (TAIL) {
-        staged_end = c.split * c.planes.d * c.tiles.d;
-        if (b < c.host_wgs) {   // host side: items [staged_end, n_items), 8 in flight per stop
-            const ItemWalk w = strided_walk(b, c.host_wgs, staged_end, c.n_items, 8);
-            for (uint32_t item = w.first; item < w.end; item += w.step) move(item, min(8u, w.end - item), Eight{});
+    const WgWalk ww = workgroup_walk(c, blockIdx.x);
+    if constexpr (TAIL || DIRECT) {
+        if (ww.width == 8) {
+            for (uint32_t item = ww.w.first; item < ww.w.end; item += ww.w.step) move(item, min(8u, ww.w.end - item), Eight{});
             return;
         }
-        b -= c.host_wgs;
-        grid -= c.host_wgs;
     }
-    if constexpr (DIRECT) {
-        const ItemWalk w = strided_walk(b, grid, 0, staged_end, 8);
-        for (uint32_t item = w.first; item < w.end; item += w.step) move(item, min(8u, w.end - item), Eight{});
-    } else {
-        const ItemWalk w = staged_walk(b, grid, staged_end, c.chunks);
-        for (uint32_t item = w.first; item < w.end; item += w.step) move(item, 1, One{});
-    }
+    for (uint32_t item = ww.w.first; item < ww.w.end; item += ww.w.step) move(item, 1, One{});
 }
 
 __global__ __launch_bounds__(kThreads) void rewrite_table_kernel(int32_t *__restrict__ table,
@@ -197,6 +175,24 @@ __global__ __launch_bounds__(kThreads) void copy_contiguous_kernel(u32x4 *__rest
     if (blockIdx.x / kXcds >= per || tile >= n_tiles) return;
     const uint64_t at = uint64_t(tile) * kThreads + threadIdx.x;
     if (at < n16) st16<NT>(dst + at, ld16<NT>(src + at));
+}
+
+// One-way streams with the same tiles and mapping: what HBM sustains in each direction alone.
+template <bool WRITE>
+__global__ __launch_bounds__(kThreads) void hbm_one_way_kernel(u32x4 *__restrict__ p, uint32_t n_tiles)
+{
+    const uint32_t r = blockIdx.x % kXcds;
+    const uint32_t per = (n_tiles + kXcds - 1) / kXcds;
+    const uint32_t tile = r * per + blockIdx.x / kXcds;
+    if (tile >= n_tiles) return;
+    u32x4 *at = p + uint64_t(tile) * kThreads + threadIdx.x;
+    if constexpr (WRITE) {
+        const u32x4 v = {tile, 0x9E3779B9u, threadIdx.x, ~tile};
+        st16<true>(at, v);
+    } else {
+        const u32x4 v = ld16<true>(at);
+        asm volatile("" ::"v"(v.x), "v"(v.y), "v"(v.z), "v"(v.w));   // the value is used: the load stays
+    }
 }
 
 // The same contiguous copy with the tile staged in LDS, kept to measure what LDS adds to a copy that
@@ -259,28 +255,11 @@ static hipError_t launch_page_copy(void *pool, uint32_t *scales, void *staging, 
     // slow host-link DMA that follows reads them.  The scatter's page writes are non-temporal, so
     // it leaves no dirty lines for the next kernel to evict (with ordinary stores the scatter looks
     // faster and the following gather pays for it; the sum is worse).
-    const uint32_t tiles = tiles_per_page(g.page16);
-    const uint64_t items64 = uint64_t(n) * g.planes * tiles;
-    if (items64 > 0x7fffffffull) return hipErrorInvalidValue;
-    if (split > n || (split < n && (!host_part || host_wgs == 0 || direct))) return hipErrorInvalidValue;
-    if (split == n) host_wgs = 0;
-    CopyPlan c{};
-    c.g = g;
-    c.tiles = make_fastdiv(tiles);
-    c.planes = make_fastdiv(g.planes);
-    c.n_items = uint32_t(items64);
-    c.split = split;
-    const uint32_t items_staged = split * g.planes * tiles;
-    // the host part and a direct launch move 8 tiles per workgroup and stop: more workgroups than stops are no use
-    // (and the walk's step, workgroups * 8, stays far below 2^32)
-    if (host_wgs) host_wgs = std::min(host_wgs, (c.n_items - items_staged + 7) / 8);
-    c.host_wgs = host_wgs;
-    uint32_t grid = direct ? (items_staged + 7) / 8 : items_staged;
-    if (max_grid && grid > max_grid) grid = max_grid;
-    if (grid == 0 && host_wgs == 0) return hipSuccess;
-    // every run needs a workgroup of its own; a grid below 8 walks the items as one run
-    c.chunks = (!direct && grid >= kXcds) ? kXcds : 1;
-    grid += host_wgs;
+    CopyPlan c;
+    if (!make_copy_plan(n, g, max_grid, direct, host_part != nullptr, split, host_wgs, &c)) return hipErrorInvalidValue;
+    if (c.grid == 0) return hipSuccess;
+    const uint32_t grid = c.grid;
+    host_wgs = c.host_wgs;
 
 #define TC_LAUNCH(NL, NS, DR, TL)                                                                             \
     hipLaunchKernelGGL((page_copy_kernel<NL, NS, GATHER, DR, TL>), dim3(grid), dim3(kThreads), 0, stream,     \
@@ -329,6 +308,21 @@ hipError_t launch_copy_contiguous(void *dst, const void *src, uint64_t bytes, hi
     if (grid > 0x7fffffffull) return hipErrorInvalidValue;
     hipLaunchKernelGGL((copy_contiguous_kernel<true>), dim3(uint32_t(grid)), dim3(kThreads), 0, stream,
                        static_cast<u32x4 *>(dst), static_cast<const u32x4 *>(src), n16, uint32_t(n_tiles));
+    return hipGetLastError();
+}
+
+hipError_t launch_hbm_one_way(void *p, uint64_t bytes, bool write, hipStream_t stream)
+{
+    if (bytes == 0) return hipSuccess;
+    const uint64_t n_tiles = bytes / (kThreads * 16);
+    const uint64_t grid = (n_tiles + kXcds - 1) / kXcds * kXcds;
+    if (bytes % (kThreads * 16) || grid > 0x7fffffffull) return hipErrorInvalidValue;
+    if (write)
+        hipLaunchKernelGGL((hbm_one_way_kernel<true>), dim3(uint32_t(grid)), dim3(kThreads), 0, stream,
+                           static_cast<u32x4 *>(p), uint32_t(n_tiles));
+    else
+        hipLaunchKernelGGL((hbm_one_way_kernel<false>), dim3(uint32_t(grid)), dim3(kThreads), 0, stream,
+                           static_cast<u32x4 *>(p), uint32_t(n_tiles));
     return hipGetLastError();
 }
 

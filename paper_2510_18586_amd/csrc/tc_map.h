@@ -14,6 +14,16 @@
 
 namespace tc {
 
+// Geometry shared by gather and scatter; all "16" fields count 16-byte units.
+struct PageGeom {
+    uint32_t planes;       // P = 2 * layers
+    uint32_t page16;       // page_bytes / 16
+    uint64_t num_blocks;   // NB
+    uint64_t rec16;        // host-record bytes / 16
+    uint32_t scales;       // S: scale words per block (0, 1 or P)
+    uint32_t tail_words;   // 32-bit words from the end of the pages to the end of the record
+};
+
 // A copy tile is 256 lanes x 16 B = 4 KiB; a page is cut into ceil(page16 / 256) tiles, the last one
 // possibly ragged.  The launchers and the limit on a pool description both go by this function.
 constexpr uint32_t kCopyThreads = 256;
@@ -50,6 +60,23 @@ TC_HD ItemPos item_pos(uint32_t item, const FastDiv &tiles, const FastDiv &plane
     return ItemPos{k, kp - k * planes.d, item - kp * tiles.d};
 }
 
+// Where an item's tile lies, in 16-byte units: from the pool's base, and from the base of the record side
+// (the staging chunk, or the host part when the launch carries a host tail and the block belongs to it).
+struct ItemPlace {
+    uint64_t pool16;     // offset of the tile in the pool
+    uint64_t record16;   // offset of the block's record in its buffer
+    uint64_t tile16;     // offset of the tile inside the record
+    uint32_t left;       // 16-byte units from the tile start to the page end (the tile covers min(left, 256))
+    bool in_host_part;   // the record lives in the host part, counted from block `split`
+};
+TC_HD ItemPlace item_place(const ItemPos &at, uint64_t blk, const PageGeom &g, uint32_t split)
+{
+    const bool host = at.k >= split;
+    return ItemPlace{(uint64_t(at.p) * g.num_blocks + blk) * g.page16 + uint64_t(at.t) * kCopyThreads,
+                     uint64_t(host ? at.k - split : at.k) * g.rec16,
+                     uint64_t(at.p) * g.page16 + uint64_t(at.t) * kCopyThreads, g.page16 - at.t * kCopyThreads, host};
+}
+
 // The items a workgroup takes: first, first + step, ... below end; `width` consecutive items at each stop.
 struct ItemWalk {
     uint32_t first, end, step;
@@ -73,6 +100,65 @@ TC_HD ItemWalk strided_walk(uint32_t b, uint32_t grid, uint32_t first_item, uint
 {
     const uint64_t first = uint64_t(first_item) + uint64_t(b) * width;
     return ItemWalk{first < end_item ? uint32_t(first) : end_item, end_item, grid * width};
+}
+
+// Everything a page-copy launch is told besides its pointers, and its grid: decided in one place for the
+// launcher and for the CPU tests that walk a launch.
+struct CopyPlan {
+    PageGeom g;
+    FastDiv tiles;       // tiles per page
+    FastDiv planes;      // planes per block
+    uint32_t n_items;    // blocks * planes * tiles
+    uint32_t split;      // records of blocks [0, split) live in staging, the rest in the host part (n = none)
+    uint32_t host_wgs;   // the first host_wgs workgroups take the host-side items, 8 per stop
+    uint32_t chunks;     // the staged items are cut into this many contiguous runs, one per XCD (1 = no cut)
+    uint32_t grid;       // workgroups, host_wgs included; 0 = nothing to launch
+    bool direct;         // the record side is pinned host memory: few workgroups, 8 items per stop, no cut
+};
+// false: the request does not fit a launch (more than 2^31 - 1 items, or a split that makes no sense).
+inline bool make_copy_plan(uint32_t n, const PageGeom &g, uint32_t max_grid, bool direct, bool has_host_part,
+                           uint32_t split, uint32_t host_wgs, CopyPlan *out)
+{
+    const uint32_t tiles = tiles_per_page(g.page16);
+    const uint64_t items64 = uint64_t(n) * g.planes * tiles;
+    if (items64 > 0x7fffffffull) return false;
+    if (split > n || (split < n && (!has_host_part || host_wgs == 0 || direct))) return false;
+    if (split == n) host_wgs = 0;
+    CopyPlan c{};
+    c.g = g;
+    c.tiles = make_fastdiv(tiles);
+    c.planes = make_fastdiv(g.planes);
+    c.n_items = uint32_t(items64);
+    c.split = split;
+    c.direct = direct;
+    const uint32_t items_staged = split * g.planes * tiles;
+    // the host part and a direct launch move 8 tiles per workgroup and stop: more workgroups than stops are no use
+    // (and the walk's step, workgroups * 8, stays far below 2^32)
+    if (host_wgs) host_wgs = host_wgs < (c.n_items - items_staged + 7) / 8 ? host_wgs : (c.n_items - items_staged + 7) / 8;
+    c.host_wgs = host_wgs;
+    uint32_t grid = direct ? (items_staged + 7) / 8 : items_staged;
+    if (max_grid && grid > max_grid) grid = max_grid;
+    // every run needs a workgroup of its own; a grid below 8 walks the items as one run
+    c.chunks = (!direct && grid >= kXcds) ? kXcds : 1;
+    c.grid = grid + host_wgs;
+    *out = c;
+    return true;
+}
+
+// The walk of workgroup b of a launch: the first host_wgs workgroups take the host part, 8 items a stop;
+// the workgroups of a direct launch take everything 8 items a stop; all others walk their XCD's run.
+struct WgWalk {
+    ItemWalk w;
+    uint32_t width;   // items per stop: 1 or 8
+};
+TC_HD WgWalk workgroup_walk(const CopyPlan &c, uint32_t b)
+{
+    const uint32_t staged_end = c.split * c.planes.d * c.tiles.d < c.n_items ? c.split * c.planes.d * c.tiles.d : c.n_items;
+    if (b < c.host_wgs) return WgWalk{strided_walk(b, c.host_wgs, staged_end, c.n_items, 8), 8};
+    b -= c.host_wgs;
+    const uint32_t grid = c.grid - c.host_wgs;
+    if (c.direct) return WgWalk{strided_walk(b, grid, 0, staged_end, 8), 8};
+    return WgWalk{staged_walk(b, grid, staged_end, c.chunks), 1};
 }
 
 }  // namespace tc

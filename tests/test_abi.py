@@ -9,15 +9,24 @@ from paper_2510_18586_amd import binding
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def _declared_functions():
-    text = open(os.path.join(ROOT, "include", "tokencake_kv.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    names = re.findall(r"\b(tc_[a-z_0-9]+)\s*\(", text)
+HEADERS = ("tokencake_kv.h", "tokencake_kv_bench.h")
+
+
+def _declared_functions(headers=HEADERS):
+    names = []
+    for h in headers:
+        text = open(os.path.join(ROOT, "include", h)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names += re.findall(r"\b(tc_[a-z_0-9]+)\s*\(", text)
     return sorted(set(names))
 
 
 def test_header_declares_the_expected_calls():
-    names = _declared_functions()
+    names = _declared_functions(("tokencake_kv.h",))
+    # the serving boundary carries no measurement helper
+    for helper in ("tc_copy_contiguous", "tc_copy_via_lds", "tc_hbm_stream", "tc_naive_transfer", "tc_hbm_write",
+                   "tc_hbm_read", "tc_stage_on_device"):
+        assert helper not in names and helper in _declared_functions(("tokencake_kv_bench.h",))
     for must in ("tc_create", "tc_destroy", "tc_alloc", "tc_free", "tc_offload", "tc_upload",
                  "tc_offload_batch", "tc_upload_batch", "tc_poll", "tc_sync", "tc_stats"):
         assert must in names
@@ -41,11 +50,11 @@ def test_error_strings_and_struct_layout():
     assert "unknown" in K.tc_strerror(-99)
     # the ctypes mirrors must match the C layout (checked against sizes the compiler would give)
     assert ctypes.sizeof(K.tc_pool_desc) == 40
-    assert ctypes.sizeof(K.tc_opts) == 40
+    assert ctypes.sizeof(K.tc_opts) == 48
     assert ctypes.sizeof(K.tc_xfer_desc) == 32
     assert ctypes.sizeof(K.tc_gate_input) == 40 and ctypes.sizeof(K.tc_upload_cand) == 24
     assert ctypes.sizeof(K.tc_index_hit) == 24
-    assert ctypes.sizeof(K.tc_stats_t) == 24 + 16 + 48 + 32 + 16 + 24 + 48
+    assert ctypes.sizeof(K.tc_stats_t) == 24 + 16 + 48 + 32 + 16 + 24 + 48 + 8
 
 
 def test_null_arguments_are_rejected_without_a_gpu():
@@ -55,7 +64,8 @@ def test_null_arguments_are_rejected_without_a_gpu():
     # descriptions that are refused before any device call: 2^31 work items in one launch, bad options
     assert K.tc_create(0x1000, None, 64, 1 << 24, 32768, 16)[0] == K.TC_ERR_INVAL
     assert K.tc_create(0x1000, None, 1 << 19, 4096, 16, 1)[0] == K.TC_ERR_INVAL
-    assert K.tc_create(0x1000, None, 2, 16, 4096, 16, direct_offload=3)[0] == K.TC_ERR_INVAL
+    assert K.tc_create(0x1000, None, 2, 16, 4096, 16, direct_offload=4)[0] == K.TC_ERR_INVAL
+    assert K.tc_create(0x1000, None, 2, 16, 4096, 16, direct_upload=2)[0] == K.TC_ERR_INVAL
     assert K.tc_create(0x1010, None, 2, 16, 4096, 16)[0] == K.TC_ERR_INVAL          # base not 256-B aligned
     assert K.tc_create(0x1000, None, 2, 16, 4100, 16)[0] == K.TC_ERR_INVAL          # page not a multiple of 16
     assert K.tc_destroy(None) == K.TC_OK
@@ -67,7 +77,7 @@ def test_header_is_plain_c_and_cxx(tmp_path):
     import subprocess
     inc = os.path.join(ROOT, "include")
     src = tmp_path / "use_header.c"
-    src.write_text('#include "tokencake_kv.h"\nint main(void) { tc_pool_desc d; tc_opts o; (void)d; (void)o; return TC_OK; }\n')
+    src.write_text('#include "tokencake_kv.h"\n#include "tokencake_kv_bench.h"\nint main(void) { tc_pool_desc d; tc_opts o; (void)d; (void)o; return TC_OK; }\n')
     subprocess.run(["gcc", "-std=c11", "-pedantic", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-I", inc, str(src)], check=True)
     subprocess.run(["g++", "-std=c++17", "-pedantic", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-x", "c++", "-I", inc, str(src)],
                    check=True)

@@ -110,7 +110,8 @@ def test_pending_free_blocks_are_not_handed_out_while_the_copy_runs():
         gp.close()
 
 
-@pytest.mark.parametrize("direct,tail", [(0, 0), (1, 0), (0, 2), (0, 4)])
+@pytest.mark.parametrize("direct,tail", [(3, 1), (1, 0), (3, 2), (3, 4), (0, 0)],
+                         ids=["staged", "direct", "staged-tail2", "staged-tail4", "auto"])
 def test_batch_of_agents_shares_chunks(direct, tail):
     rng = W.rng_for(2, salt=3)
     shape = W.CONFIGS[1].with_blocks(128)
@@ -251,37 +252,43 @@ def test_shared_prefix_blocks_stay_put():
 
 
 def test_calibrated_cost_model_predicts_a_transfer_and_leaves_the_pool_alone():
-    """Eq. 2 closed on this platform: tc_calibrate fits T(N) from its own transfers; the estimate for
-    a size it did not measure is within 8 % of the best of several transfers timed here; the gate of
-    Alg. 1 then uses it."""
-    import time
+    """Eq. 2 closed on this platform: tc_calibrate fits T(N) from its own transfers and leaves the pool as it
+    was; the per-block constants are those of a host link (between 40 and 70 GB/s); the estimate for a size it
+    did not measure agrees with transfers timed here by events on the stream to within 15 % (a bound that
+    catches a wrong unit or a dropped term of Eq. 2, not the link's run-to-run noise); the gate of Alg. 1
+    then uses it."""
     shape = W.CONFIGS[1].with_blocks(400)
     gp = GpuPool(shape, seed=9, host_arena_bytes=330 * 2 * 1024 * 1024)
     try:
-        before = gp.page_checksums()
+        before = gp.page_checksums(weighted=True)
         stream = torch.cuda.Stream()
         rc, model = K.tc_calibrate(gp.ctx, [32, 64, 128, 256], 3, stream)
         assert rc == 0
-        assert torch.equal(gp.page_checksums(), before), "calibration must not change the pool"
+        assert torch.equal(gp.page_checksums(weighted=True), before), "calibration must not change the pool"
         st = _stats(gp)
         assert st.gpu_blocks_free == 400 and st.host_slots_used == 0
-        # 2 MiB per block at roughly 57 GB/s is ~0.037 ms per block and direction
-        assert 0.03 < model.off_b_ms_per_block < 0.06 and 0.03 < model.up_b_ms_per_block < 0.06
+        # 2 MiB per block at 40 .. 70 GB/s is 0.030 .. 0.052 ms per block and direction
+        assert 0.030 < model.off_b_ms_per_block < 0.052 and 0.030 < model.up_b_ms_per_block < 0.052
         assert abs(model.off_a_ms) < 0.5 and abs(model.up_a_ms) < 0.5
+        # linear in the number of blocks (Eq. 2), increasing, and additive over the two directions
+        e = [K.tc_estimate_transfer_ms(model, k) for k in (0, 100, 200, 300)]
+        assert e[1] < e[2] < e[3] and abs((e[3] - e[2]) - (e[2] - e[1])) < 1e-9
+        assert abs(e[0] - (model.off_a_ms + model.up_a_ms)) < 1e-12
         n = 192
         rc, ids = K.tc_alloc(gp.ctx, n)
         rc, host = K.tc_host_alloc(gp.ctx, n)
         ts = []
         for _ in range(6):
-            torch.cuda.synchronize()
-            t = time.perf_counter()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
             K.check(K.tc_offload(gp.ctx, ids, host, stream))
             K.check(K.tc_upload(gp.ctx, host, ids, None, stream))
+            e1.record(stream)
             stream.synchronize()
-            ts.append((time.perf_counter() - t) * 1e3)
-        measured = float(np.min(ts[1:]))       # the link is shared with the rest of the host: take the clean run
+            ts.append(e0.elapsed_time(e1))
+        measured = float(np.median(ts[1:]))
         predicted = K.tc_estimate_transfer_ms(model, n)
-        assert abs(predicted - measured) / measured < 0.08, (predicted, measured)
+        assert abs(predicted - measured) / measured < 0.15, (predicted, measured)
         # a 2 s tool call leaves a window; a 10 ms one does not cover the round trip of 192 blocks
         assert K.tc_should_offload(model, n, 2000.0, 5.0, [(500, 10.0), (100, 4000.0)]) == (1, 1)
         assert K.tc_should_offload(model, n, 10.0, 5.0, [(100, 1.0)]) == (0, -1)
@@ -297,7 +304,8 @@ def test_whole_pool_moves_in_one_call_over_many_chunks():
     L, NB, pb = shape.num_layers, shape.num_blocks, shape.page_bytes
     pool_h = W.make_pool_host(shape, rng)
     ids = rng.permutation(NB).astype(np.int32)
-    gp = GpuPool(shape, pool_h, None, staging_bytes=2 * 7 * 2 * 1024 * 1024, staging_slots=2)   # 7 records per chunk
+    gp = GpuPool(shape, pool_h, None, staging_bytes=2 * 7 * 2 * 1024 * 1024, staging_slots=2,   # 7 records per chunk
+                 direct_offload=K.TC_PATH_STAGED, direct_upload=K.TC_PATH_STAGED)
     try:
         host = pinned_bytes(NB * gp.rec)
         rc, got = K.tc_alloc(gp.ctx, NB)
@@ -331,7 +339,8 @@ def test_two_streams_share_one_staging_slot():
     pool_h = W.make_pool_host(shape, rng)
     perm = W.pick_ids(rng, NB, 90)
     a_src, b_src, b_dst = perm[:30], perm[30:60], perm[60:90]
-    gp = GpuPool(shape, pool_h, None, staging_bytes=4 * 2 * 1024 * 1024, staging_slots=1)       # 4 records per chunk
+    gp = GpuPool(shape, pool_h, None, staging_bytes=4 * 2 * 1024 * 1024, staging_slots=1,       # 4 records per chunk
+                 direct_offload=K.TC_PATH_STAGED, direct_upload=K.TC_PATH_STAGED)
     try:
         rec = gp.rec
         s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
@@ -365,7 +374,7 @@ def test_calls_from_several_host_threads():
     pool_h = W.make_pool_host(shape, rng)
     perm = W.pick_ids(rng, NB, 4 * 2 * 24)
     gp = GpuPool(shape, pool_h, None, staging_bytes=2 * 8 * 2 * 1024 * 1024, staging_slots=2,
-                 host_arena_bytes=100 * 2 * 1024 * 1024)
+                 host_arena_bytes=100 * 2 * 1024 * 1024, direct_offload=K.TC_PATH_STAGED, direct_upload=K.TC_PATH_STAGED)
     try:
         rec = gp.rec
         K.check(K.tc_alloc_at(gp.ctx, perm))
@@ -417,7 +426,7 @@ def test_auto_mode_goes_direct_only_while_an_upload_is_in_flight():
     rng = W.rng_for(1, salt=34)
     shape = W.CONFIGS[1].with_blocks(512)
     L, NB, pb = shape.num_layers, shape.num_blocks, shape.page_bytes
-    gp = GpuPool(shape, seed=34, direct_offload=2)
+    gp = GpuPool(shape, seed=34, direct_offload=K.TC_PATH_DIRECT_IF_DUPLEX, direct_upload=K.TC_PATH_STAGED)
     mirror = None
     try:
         from harness import SparseMirror
@@ -527,4 +536,49 @@ def test_thousands_of_small_transfers_wrap_the_id_ring():
         assert np.array_equal(gp.pool_to_host(), mirror)
         assert table.cpu().numpy()[:2].tolist() == dst.tolist()
     finally:
+        gp.close()
+
+
+def test_the_librarys_own_choice_of_path():
+    """Default options: an upload goes through the scatter kernel that reads pinned memory itself, an offload
+    below 128 MiB through the gather kernel that writes it, a larger one through device staging and DMA; a
+    larger one issued while an upload is in flight goes direct as well.  Same bytes whichever way."""
+    rng = W.rng_for(1, salt=36)
+    shape = W.CONFIGS[1].with_blocks(400)
+    L, NB, pb = shape.num_layers, shape.num_blocks, shape.page_bytes
+    gp = GpuPool(shape, seed=36)
+    mirror = None
+    try:
+        from harness import SparseMirror
+        rec = gp.rec
+        perm = W.pick_ids(rng, NB, 63 + 64 + 100 + 100)
+        small, edge, big, dst = perm[:63], perm[63:127], perm[127:227], perm[227:]
+        K.check(K.tc_alloc_at(gp.ctx, perm))
+        K.check(K.tc_set_profiling(gp.ctx, 1))
+        mirror = SparseMirror(gp, perm)
+        bufs = {k: pinned_bytes(len(v) * rec) for k, v in (("small", small), ("edge", edge), ("big", big))}
+        s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+
+        def counts():
+            K.check(K.tc_sync(gp.ctx))
+            st = _stats(gp)
+            return st.direct_launches, st.gather_launches, st.scatter_launches
+
+        K.check(K.tc_offload(gp.ctx, small, bufs["small"], s1))          # 126 MiB: direct
+        assert counts() == (1, 0, 0)
+        K.check(K.tc_offload(gp.ctx, edge, bufs["edge"], s1))            # 128 MiB, the threshold itself: staged
+        assert counts() == (1, 1, 0)
+        K.check(K.tc_upload(gp.ctx, bufs["edge"], dst[:64], None, s2))   # uploads: direct
+        assert counts() == (2, 1, 0)
+        junk = pinned_bytes(100 * rec)
+        K.check(K.tc_upload(gp.ctx, junk, dst, None, s2))                # 200 MiB coming in (whatever bytes) ...
+        K.check(K.tc_offload(gp.ctx, big, bufs["big"], s1))              # ... while 200 MiB go out: direct
+        assert counts() == (4, 1, 0)
+        for ids, key in ((small, "small"), (edge, "edge"), (big, "big")):
+            want = np.empty(len(ids) * rec, dtype=np.uint8)
+            oracle.offload(mirror.pool, None, L, NB, pb, 0, ids, want)
+            assert np.array_equal(bufs[key].numpy(), want), key
+    finally:
+        if mirror:
+            mirror.close()
         gp.close()

@@ -70,3 +70,61 @@ def test_hbm_stream_computes_the_triad():
     # a = b + 0.5 * c in fp32: multiplying by 0.5 is exact, so fused or not the result is the rounded sum
     assert torch.equal(a, b + 0.5 * c)
     assert K.tc_hbm_stream(a, b, c, n + 1, 0.5, 1, stream) == K.TC_ERR_INVAL
+
+
+def test_one_way_streams_write_everything_and_read_without_side_effects():
+    nbytes = 4096 * 2051                       # not a multiple of 8 tiles: the last run is short
+    guard = 4096
+    buf = torch.full((guard + nbytes + guard,), 0xEE, dtype=torch.uint8, device=DEV)
+    stream = torch.cuda.Stream()
+    stream.wait_stream(torch.cuda.current_stream())
+    K.check(K.tc_hbm_write(buf[guard:], nbytes, stream))
+    stream.synchronize()
+    words = buf[guard:guard + nbytes].view(torch.int32).view(-1, 256, 4)      # [tile][lane][4 words]
+    tiles = torch.arange(words.shape[0], dtype=torch.int32, device=DEV)
+    assert torch.equal(words[:, :, 0], tiles[:, None].expand(-1, 256))        # every tile written, by its own workgroup
+    assert torch.equal(words[:, :, 2], torch.arange(256, dtype=torch.int32, device=DEV)[None, :].expand(words.shape[0], -1))
+    assert bool((buf[:guard] == 0xEE).all()) and bool((buf[guard + nbytes:] == 0xEE).all())
+    before = buf.clone()
+    K.check(K.tc_hbm_read(buf[guard:], nbytes, stream))
+    stream.synchronize()
+    assert torch.equal(buf, before)
+    assert K.tc_hbm_write(buf[guard:], 4096 + 16, stream) == K.TC_ERR_INVAL
+    assert K.tc_hbm_read(buf[guard + 8:], 4096, stream) == K.TC_ERR_INVAL
+    assert K.tc_hbm_read(None, 0, stream) == K.TC_OK
+
+
+def test_stage_on_device_is_the_staged_kernel_on_device_records():
+    """tc_stage_on_device against the oracle: gather into device records, scatter from them into other blocks."""
+    import oracle
+    import tc_workloads as W
+    from harness import GpuPool
+    shape = W.PoolShape("fp8-small", 3, 2, 32, 8, 1, 80, 6, "fp8")
+    rng = W.rng_for(4, salt=91)
+    pool_h, scales_h = W.make_pool_host(shape, rng), W.make_scales_host(shape, rng)
+    gp = GpuPool(shape, pool_h, scales_h)
+    try:
+        n, rec = 23, gp.rec
+        ids = W.pick_ids(rng, shape.num_blocks, n)
+        new_ids = W.pick_ids(rng, shape.num_blocks, n, exclude=ids)
+        records = torch.full((n * rec + 256,), 0x77, dtype=torch.uint8, device=DEV)
+        stream = torch.cuda.Stream()
+        stream.wait_stream(torch.cuda.current_stream())
+        K.check(K.tc_stage_on_device(gp.ctx, 0, ids, records, stream))
+        want = np.empty(n * rec, dtype=np.uint8)
+        oracle.offload(pool_h, scales_h, shape.num_layers, shape.num_blocks, shape.page_bytes, shape.scales_per_block, ids, want)
+        K.check(K.tc_sync(gp.ctx))
+        got = records.cpu().numpy()
+        assert np.array_equal(got[: n * rec], want) and (got[n * rec:] == 0x77).all()
+        K.check(K.tc_stage_on_device(gp.ctx, 1, new_ids, records, stream))
+        K.check(K.tc_sync(gp.ctx))
+        oracle.upload(want, shape.num_layers, shape.num_blocks, shape.page_bytes, shape.scales_per_block, new_ids, pool_h, scales_h, None)
+        assert np.array_equal(gp.pool_to_host(), pool_h) and np.array_equal(gp.scales_all_to_host(), scales_h)
+        assert K.tc_stage_on_device(gp.ctx, 0, [1, 1], records, stream) == K.TC_ERR_DUP
+        assert K.tc_stage_on_device(gp.ctx, 0, [80], records, stream) == K.TC_ERR_RANGE
+        assert K.tc_stage_on_device(gp.ctx, 2, [1], records, stream) == K.TC_ERR_INVAL
+        assert K.tc_stage_on_device(gp.ctx, 0, [1], np.zeros(rec, dtype=np.uint8), stream) == K.TC_ERR_INVAL
+        rc, st = K.tc_stats(gp.ctx)
+        assert st.ops_in_flight == 0 and st.gpu_blocks_free == shape.num_blocks
+    finally:
+        gp.close()

@@ -16,7 +16,12 @@ from harness import DEV, GpuPool, SparseMirror, pinned_bytes
 pytestmark = pytest.mark.gpu
 
 
-def _round_trip_case(shape, seed_idx, n, salt=0, same_ids=False, **opts):
+def _round_trip_case(shape, seed_idx, n, salt=0, same_ids=False, auto=False, **opts):
+    """auto = False: the staged path (gather / scatter through device staging) unless opts name another;
+    auto = True: the library's own choice of path (its default options)."""
+    if not auto:
+        opts.setdefault("direct_offload", K.TC_PATH_STAGED)
+        opts.setdefault("direct_upload", K.TC_PATH_STAGED)
     rng = W.rng_for(seed_idx, salt)
     L, NB, pb, S, P = shape.num_layers, shape.num_blocks, shape.page_bytes, shape.scales_per_block, shape.planes
     pool_h = W.make_pool_host(shape, rng)
@@ -72,9 +77,10 @@ def _round_trip_case(shape, seed_idx, n, salt=0, same_ids=False, **opts):
         gp.close()
 
 
-def test_config1_tiny():
+@pytest.mark.parametrize("auto", [False, True], ids=["staged", "auto"])
+def test_config1_tiny(auto):
     # 2 layers, 4 KV heads, head_dim 64, 16-token blocks, bf16, 256 blocks, one agent with 8 blocks
-    _round_trip_case(W.CONFIGS[0], 0, 8)
+    _round_trip_case(W.CONFIGS[0], 0, 8, auto=auto)
 
 
 def test_config1_tiny_same_ids():
@@ -96,6 +102,9 @@ def test_host_tail_of_every_chunk_skips_staging(div, slots):
     shape = W.CONFIGS[1].with_blocks(96)
     _round_trip_case(shape, 1, 37, salt=60 + div, staging_bytes=slots * 5 * 2 * 1024 * 1024, staging_slots=slots,
                      host_tail_div=div)
+    # the automatic tail: 1/64 of a chunk, so chunks of 70 records carry one record each through the launch itself
+    if div == 2:
+        _round_trip_case(W.CONFIGS[0].with_blocks(512), 0, 200, salt=63, staging_bytes=70 * 32 * 1024, staging_slots=1, host_tail_div=0)
     # scales and a zero pad in the tail records, capped grid, one chunk
     _round_trip_case(W.PoolShape("fp8-small", 3, 2, 32, 8, 1, 80, 6, "fp8"), 4, 23, salt=61 + div, host_tail_div=div, max_grid=5)
     # ragged tiles
@@ -117,7 +126,7 @@ def test_odd_shapes_and_scales(shape, n):
     _round_trip_case(shape, 4, n, salt=n)
 
 
-@pytest.mark.parametrize("off,up,grid", [(1, 0, 0), (1, 1, 3), (0, 1, 0), (2, 1, 0)])
+@pytest.mark.parametrize("off,up,grid", [(1, 3, 0), (1, 1, 3), (3, 1, 0), (2, 1, 0), (0, 0, 0), (2, 0, 0)])
 def test_direct_paths_move_the_same_bytes(off, up, grid):
     # the gather kernel stores straight into the pinned host buffer / the scatter kernel reads straight
     # from it (no staging, no DMA)
@@ -152,7 +161,7 @@ def _random_case(k):
     if mode == 1:
         opts.update(direct_offload=1, direct_upload=1, direct_grid=int(rng.choice([0, 1, 5])))
     elif mode == 2:
-        opts.update(direct_offload=2, direct_upload=int(rng.integers(0, 2)))
+        opts.update(direct_offload=2, direct_upload=int(rng.choice([1, 3])))
     if rng.random() < 0.5:
         opts["host_tail_div"] = int(rng.choice([2, 3, 4, 8]))
     return shape, n, opts
@@ -165,12 +174,27 @@ def test_random_small_shapes_and_options(k):
     _round_trip_case(shape, 0, n, salt=2000 + k, **opts)
 
 
+@pytest.mark.parametrize("k", range(24))
+def test_random_small_shapes_with_the_librarys_choice_of_path(k):
+    """The same 24 shapes with the path left to the library (the default): small offloads and all uploads go
+    through the kernels that touch pinned memory themselves; auto_direct_bytes = 1 in every third case makes the
+    offload staged, with the automatic host tail on transfers of several chunks."""
+    shape, n, opts = _random_case(k)
+    for key in ("direct_offload", "direct_upload"):
+        opts.pop(key, None)
+    if k % 3 == 0:
+        opts["auto_direct_bytes"] = 1
+        opts.pop("host_tail_div", None)
+    print(f"case {k} (auto): L={shape.num_layers} pb={shape.page_bytes} S={shape.scales_per_block} NB={shape.num_blocks} n={n} {opts}", flush=True)
+    _round_trip_case(shape, 0, n, salt=2000 + k, auto=True, **opts)
+
+
 def test_zero_blocks_is_a_no_op():
     _round_trip_case(W.CONFIGS[0], 0, 0, salt=3)
 
 
-@pytest.mark.parametrize("host_tail_div", [0, 64])
-def test_config2_full_size_llama3_8b(host_tail_div):
+@pytest.mark.parametrize("host_tail_div,paths", [(1, "staged"), (64, "staged"), (0, "auto")])
+def test_config2_full_size_llama3_8b(host_tail_div, paths):
     """32 layers x 8 heads x 128 x 16 tokens bf16 (2 MiB per block), 16 384 blocks (32 GiB), one agent
     with a 4 096-token context = 256 blocks scattered uniformly; default launch configuration, and the
     one with the last 1/64 of the chunk moved over the link by the copy launch itself."""
@@ -180,10 +204,11 @@ def test_config2_full_size_llama3_8b(host_tail_div):
     L, NB, pb, S, P = shape.num_layers, shape.num_blocks, shape.page_bytes, 0, shape.planes
     ids = W.pick_ids(rng, NB, n)
     new_ids = W.pick_ids(rng, NB, n, exclude=ids)
-    gp = GpuPool(shape, seed=W.seed_for(1), host_tail_div=host_tail_div)
+    path = {} if paths == "auto" else dict(direct_offload=K.TC_PATH_STAGED, direct_upload=K.TC_PATH_STAGED)
+    gp = GpuPool(shape, seed=W.seed_for(1), host_tail_div=host_tail_div, **path)
     try:
         rec = gp.rec
-        before = gp.page_checksums()
+        before = gp.page_checksums(weighted=True)       # position-sensitive: a word that moved inside a page shows
         mirror = SparseMirror(gp, np.concatenate([ids, new_ids]))
         want_host = np.empty(n * rec, dtype=np.uint8)
         oracle.offload(mirror.pool, None, L, NB, pb, S, ids, want_host)
@@ -195,7 +220,7 @@ def test_config2_full_size_llama3_8b(host_tail_div):
         K.check(K.tc_free(gp.ctx, ids))
         K.check(K.tc_sync(gp.ctx))
         assert np.array_equal(host.numpy(), want_host)
-        assert torch.equal(gp.page_checksums(), before), "offload wrote the pool"
+        assert torch.equal(gp.page_checksums(weighted=True), before), "offload wrote the pool"
 
         table_d = torch.full((n + 2,), -1, dtype=torch.int32, device=DEV)
         torch.cuda.synchronize()       # torch wrote this on its own stream; the library's calls run on others
@@ -207,7 +232,7 @@ def test_config2_full_size_llama3_8b(host_tail_div):
         assert np.array_equal(gp.blocks_to_host(new_ids), mirror.blocks(new_ids)), "uploaded blocks differ"
         assert np.array_equal(table_d.cpu().numpy(), table_h)
         # every block outside new_ids: untouched (per-page checksums by torch, not by the library)
-        after = gp.page_checksums()
+        after = gp.page_checksums(weighted=True)
         keep = torch.ones(NB, dtype=torch.bool, device=DEV)
         keep[torch.as_tensor(new_ids.astype(np.int64), device=DEV)] = False
         assert torch.equal(after[:, keep], before[:, keep])

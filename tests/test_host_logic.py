@@ -301,3 +301,115 @@ def test_host_code_under_sanitizers(tmp_path, sanitizer):
         check=True)
     out = subprocess.run([exe], capture_output=True, text=True, timeout=300)
     assert out.returncode == 0 and out.stdout.strip().endswith("ok"), (out.returncode, out.stdout[-2000:], out.stderr[-4000:])
+
+
+# ---------------------------------------------------------------------------------- transfer planning
+def _plan_sigs(lib):
+    vp, u32, u64, i64, ci = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint64, ctypes.c_int64, ctypes.c_int
+    lib.tcp_book_new.restype, lib.tcp_book_new.argtypes = vp, [u64, u32]
+    lib.tcp_book_del.argtypes = [vp]
+    lib.tcp_book_begin.restype = i64
+    lib.tcp_book_begin.argtypes = [vp, u64, vp, u32, vp, u32, ci, vp, ctypes.POINTER(u32), vp]
+    lib.tcp_book_publish.restype = u64
+    lib.tcp_book_publish.argtypes = [vp, u64, vp, u32, vp, u32, ci, ci, vp]
+    lib.tcp_book_cancel.argtypes = [vp, vp]
+    lib.tcp_book_retire.restype, lib.tcp_book_retire.argtypes = u64, [vp]
+    lib.tcp_book_ring_used.restype, lib.tcp_book_ring_used.argtypes = u64, [vp]
+    lib.tcp_book_upload_in_flight.argtypes = [vp]
+    lib.tcp_plan_chunks.restype, lib.tcp_plan_chunks.argtypes = u32, [u64, u32, ci, vp, u32]
+    lib.tcp_chunk_pieces.restype, lib.tcp_chunk_pieces.argtypes = u32, [vp, vp, u32, u64, u64, vp, u32]
+    lib.tcp_host_tail.argtypes = [u32, u64, u32, vp, vp, u32, vp]
+    lib.tcp_offload_direct.argtypes = [u32, u64, ci, u64]
+    lib.tcp_upload_direct.argtypes = [u32]
+    lib.tcp_tail_divisor.restype, lib.tcp_tail_divisor.argtypes = u32, [u32, u64]
+    return lib
+
+
+def test_transfer_book_matches_the_model_step_for_step(shim):
+    """Id ring, hazards and what a failed transfer holds (csrc/tc_plan.h) against oracle/transfer_plan.py on
+    seeded streams of begin / publish / publish-failed / cancel / retire: every ring start, every set of
+    transfers to wait for, every ticket and the ring's fill level agree."""
+    import oracle.transfer_plan as T
+    lib = _plan_sigs(shim)
+    rng = np.random.default_rng(W.seed_for(0, 91))
+    for cap, nb in ((16, 12), (64, 40), (1000, 300)):
+        book = lib.tcp_book_new(cap, nb)
+        model = T.OracleTransferBook(cap)
+        for _ in range(3000):
+            r = rng.random()
+            if r < 0.6:
+                n = int(rng.integers(1, max(2, min(nb, cap // 3))))
+                ids = rng.choice(nb, size=n, replace=False).astype(np.int32)
+                arena = rng.choice(8, size=int(rng.integers(0, 3)), replace=False).astype(np.uint64)
+                stream, up = int(rng.integers(1, 4)), int(rng.integers(0, 2))
+                waits = np.zeros(64, dtype=np.uint64)
+                n_waits, span = ctypes.c_uint32(0), np.zeros(3, dtype=np.uint64)
+                got = lib.tcp_book_begin(book, stream, ids.ctypes.data, n, arena.ctypes.data if arena.size else None,
+                                         int(arena.size), up, waits.ctypes.data, ctypes.byref(n_waits), span.ctypes.data)
+                want_start, want_waits = model.begin(stream, ids.tolist(), arena.tolist(), upload=bool(up))
+                assert set(int(x) for x in waits[: n_waits.value]) == want_waits
+                assert got == (-1 if want_start is None else want_start)
+                if want_start is None:
+                    continue
+                if rng.random() < 0.1:
+                    lib.tcp_book_cancel(book, span.ctypes.data)
+                    model.cancel()
+                else:
+                    failed = int(rng.random() < 0.2)
+                    t = lib.tcp_book_publish(book, stream, ids.ctypes.data, n, arena.ctypes.data if arena.size else None,
+                                             int(arena.size), up, failed, span.ctypes.data)
+                    assert t == model.publish(failed=bool(failed))
+            elif model.ops:
+                assert lib.tcp_book_retire(book) == model.retire_oldest()["ticket"]
+            assert lib.tcp_book_ring_used(book) == model.ring.used()
+            assert bool(lib.tcp_book_upload_in_flight(book)) == model.upload_in_flight()
+        lib.tcp_book_del(book)
+
+
+def test_chunks_pieces_tail_and_paths_match_the_model(shim):
+    import oracle.transfer_plan as T
+    lib = _plan_sigs(shim)
+    rng = np.random.default_rng(W.seed_for(0, 92))
+    for _ in range(2000):
+        lens = rng.integers(1, 300, size=int(rng.integers(1, 8))).astype(np.uint32)
+        firsts = np.concatenate([[0], np.cumsum(lens)[:-1]]).astype(np.uint64)
+        segs = [(int(f), int(n)) for f, n in zip(firsts, lens)]
+        total, slot, up = int(lens.sum()), int(rng.integers(1, 400)), int(rng.integers(0, 2))
+        out = np.zeros(2048, dtype=np.uint32)
+        k = lib.tcp_plan_chunks(total, slot, up, out.ctypes.data, out.size)
+        sizes = T.plan_chunks(total, slot, bool(up))
+        assert out[:k].tolist() == sizes
+        c0 = 0
+        for size in sizes[:6]:
+            buf = np.zeros(4 * 16, dtype=np.uint64)
+            m = lib.tcp_chunk_pieces(firsts.ctypes.data, lens.ctypes.data, len(segs), c0, c0 + size, buf.ctypes.data, 16)
+            assert [tuple(int(x) for x in buf[4 * i:4 * i + 4]) for i in range(m)] == T.chunk_pieces(segs, c0, c0 + size)
+            div = int(rng.choice([0, 1, 2, 3, 64, 1000]))
+            o3 = np.zeros(3, dtype=np.int64)
+            lib.tcp_host_tail(div, c0, size, firsts.ctypes.data, lens.ctypes.data, len(segs), o3.ctypes.data)
+            staged, seg, in_seg = T.host_tail_split(div, c0, size, segs)
+            assert (int(o3[0]), int(o3[1]), int(o3[2])) == (staged, -1 if seg is None else seg, 0 if in_seg is None else in_seg)
+            c0 += size
+        mode, nbytes, dup, auto = int(rng.integers(0, 4)), int(rng.integers(0, 1 << 30)), int(rng.integers(0, 2)), int(rng.integers(1, 1 << 30))
+        assert bool(lib.tcp_offload_direct(mode, nbytes, dup, auto)) == (T.offload_path(mode, nbytes, bool(dup), auto) == T.DIRECT)
+        assert bool(lib.tcp_upload_direct(mode)) == (T.upload_path(mode) == T.DIRECT)
+        opt, nch = int(rng.choice([0, 1, 2, 48])), int(rng.integers(1, 5))
+        assert lib.tcp_tail_divisor(opt, nch) == T.tail_divisor(opt, nch)
+
+
+def test_engine_on_a_cpu_stand_in_under_sanitizers(tmp_path):
+    """tests/csrc/engine_emul.cpp: the whole transfer engine (csrc/tc_engine_core.h) with a stand-in device that
+    runs every copy and every kernel launch at once on exact-size heap buffers, walking a launch through the
+    kernels' own index arithmetic.  Built with AddressSanitizer + UBSan, compared byte for byte with the oracle's
+    C file, with every fallible device call failing in turn."""
+    import oracle
+    csrc = os.path.join(ROOT, "paper_2510_18586_amd", "csrc")
+    exe, obj = str(tmp_path / "engine_emul"), str(tmp_path / "tc_oracle.o")
+    san = ["-fsanitize=address,undefined", "-fno-sanitize-recover=all"]
+    subprocess.run(["gcc", "-std=c11", "-O1", "-g", *san, "-c", os.path.join(os.path.dirname(oracle.__file__), "tc_oracle.c"),
+                    "-o", obj], check=True)
+    subprocess.run(["g++", "-std=c++17", "-O1", "-g", "-Wall", "-Wextra", "-Werror", *san, "-static-libasan",
+                    "-I", os.path.join(ROOT, "include"), "-I", csrc, os.path.join(HERE, "csrc", "engine_emul.cpp"), obj,
+                    "-o", exe], check=True)
+    out = subprocess.run([exe], capture_output=True, text=True, timeout=600)
+    assert out.returncode == 0 and out.stdout.strip().endswith("ok"), (out.returncode, out.stdout[-2000:], out.stderr[-4000:])
