@@ -80,28 +80,31 @@ typedef struct {
     uint64_t staging_bytes;     /* device staging ring in total; 0 = default                       */
     uint32_t staging_slots;     /* ring depth, >= 1; 0 = default                                   */
     uint32_t max_grid;          /* cap on workgroups per gather/scatter launch; 0 = one per tile   */
-    uint32_t direct_offload;    /* which path an offload takes: TC_PATH_AUTO (0, the default) = direct when the
-                                   transfer is below auto_direct_bytes or while an upload of this context is
-                                   in flight (kernel-driven D2H traffic overlaps with H2D traffic on the link,
-                                   two DMAs take turns), staged otherwise; TC_PATH_DIRECT = the gather kernel
-                                   writes the records straight into the pinned host buffer, no staging, no
-                                   DMA; TC_PATH_DIRECT_IF_DUPLEX = direct only while an upload is in flight;
+    uint32_t direct_offload;    /* which path an offload takes: TC_PATH_AUTO (0, the default) = through device
+                                   staging and the copy engine, except while an upload of this context is in
+                                   flight, when it goes direct (kernel-driven D2H traffic overlaps with H2D
+                                   traffic on the link, two DMAs take turns), and except below
+                                   auto_direct_bytes; TC_PATH_DIRECT = the gather kernel writes the records
+                                   straight into the pinned host buffer, no staging, no DMA;
+                                   TC_PATH_DIRECT_IF_DUPLEX = direct only while an upload is in flight;
                                    TC_PATH_STAGED = always gather into device staging, then DMA           */
     uint32_t direct_upload;     /* TC_PATH_AUTO (0) and TC_PATH_DIRECT = the scatter kernel reads the records
-                                   straight from the pinned host buffer (never slower than DMA + scatter, and
-                                   one pass through HBM instead of three); TC_PATH_STAGED = DMA into device
-                                   staging, then scatter.  With TC_PATH_AUTO a host buffer the GPU cannot map
-                                   falls back to staging; with TC_PATH_DIRECT it is TC_ERR_NOT_PINNED          */
+                                   straight from the pinned host buffer (at the link rate on an idle GPU, the
+                                   least disturbed next to memory-bound kernels, and one pass through HBM
+                                   instead of three); TC_PATH_STAGED = DMA into device staging, then scatter.
+                                   With TC_PATH_AUTO a host buffer the GPU cannot map falls back to staging;
+                                   with TC_PATH_DIRECT it is TC_ERR_NOT_PINNED                              */
     uint32_t direct_grid;       /* workgroups of a direct gather / scatter, and of a chunk's host tail
-                                   (host_tail_div); 0 = defaults (6 / 8)                           */
+                                   (host_tail_div); 0 = defaults (gather 6, scatter 16, tails 6 / 8)   */
     uint32_t host_tail_div;     /* staged path only: the last 1/N of every chunk's blocks is moved by a few
                                    workgroups of the same copy launch straight to / from the pinned buffer,
                                    using the link while it would otherwise wait for the kernel, and the DMA
                                    carries that much less.  0 = automatic (N = 64 for transfers of more than
                                    one chunk, none otherwise), 1 = never, N >= 2 = that N.  Applies to chunks
                                    of at least N blocks whose tail lies in one host buffer.               */
-    uint64_t auto_direct_bytes; /* TC_PATH_AUTO: offloads below this many record bytes go direct; 0 = default
-                                   (128 MiB, the measured crossover on MI355X)                            */
+    uint64_t auto_direct_bytes; /* TC_PATH_AUTO: offloads below this many record bytes go direct as well (one
+                                   kernel instead of kernel + DMA saves ~19 us on an otherwise idle GPU; next to
+                                   memory-bound kernels the staged path is the faster one); 0 = no such rule   */
 } tc_opts;
 
 typedef struct {

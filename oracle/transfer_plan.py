@@ -15,8 +15,9 @@ Readings where the paper is silent (it describes no mechanism at this level):
 * hazards: a transfer waits for the LAST earlier transfer, still in flight, that touched one of its
   blocks or its host allocation, if that one was put on another stream (same-stream order is implicit).
 * paths: an upload goes through the copy kernel that reads pinned memory itself unless told otherwise;
-  an offload does so when it is small or while an upload of the same context is in flight (the two then
-  share the link instead of taking turns), and through device staging plus DMA otherwise.
+  an offload does so while an upload of the same context is in flight (the two then share the link
+  instead of taking turns) or when it is below a size the caller may set (none by default), and through
+  device staging plus DMA otherwise.
 * a transfer whose enqueue failed after part of it was handed to the stream keeps everything it holds
   (ring span, in-flight marks, host allocation) until it is retired like any other transfer.
 """

@@ -37,10 +37,13 @@
 
 namespace tc {
 
-// A handful of workgroups saturate the host link; more only deepen the queue of host-bound requests
-// that other kernels' memory traffic has to wait behind.
+// A handful of workgroups saturate the host link.  More host-bound stores (gather) only deepen the queue that
+// other kernels' memory traffic has to wait behind; host-bound loads (scatter) are harmless up to about 24
+// workgroups, and 16 keep a direct upload at the link rate next to a kernel that saturates HBM.  A chunk's host
+// tail shares its launch with thousands of staged workgroups and stays small either way.
 constexpr uint32_t kDefaultDirectGatherGrid = 6;
-constexpr uint32_t kDefaultDirectScatterGrid = 8;
+constexpr uint32_t kDefaultDirectScatterGrid = 16;
+constexpr uint32_t kDefaultTailScatterGrid = 8;
 
 enum TimedKind { kGather = 0, kScatter = 1, kD2H = 2, kH2D = 3, kDirect = 4 };
 
@@ -345,10 +348,9 @@ public:
         (void)poll();
 
         // Direct path: the gather kernel writes each agent's records straight into its pinned host buffer.
-        // Slightly slower alone than gather + DMA on large transfers, but kernel-driven D2H traffic overlaps
-        // with H2D traffic, which two DMAs of opposite direction do not, and small transfers save a DMA.
-        const uint64_t auto_bytes = opts.auto_direct_bytes ? opts.auto_direct_bytes : kAutoDirectOffloadBytes;
-        bool direct = offload_goes_direct(opts.direct_offload, plan.total * rec, book->upload_in_flight(), auto_bytes);
+        // Kernel-driven D2H traffic overlaps with H2D traffic, which two DMAs of opposite direction do not;
+        // otherwise the staged path is the polite one (see offload_goes_direct).
+        bool direct = offload_goes_direct(opts.direct_offload, plan.total * rec, book->upload_in_flight(), opts.auto_direct_bytes);
         std::vector<void *> dev_view;
         if (direct && !device_views(plan, &dev_view)) {
             if (opts.direct_offload == kPathDirect) return TC_ERR_NOT_PINNED;
@@ -462,7 +464,7 @@ public:
                 TC_RC(time_begin(&op, stream, uint64_t(nblk) * rec, kScatter));
                 TC_DEV(dev.scatter(slot->buf, pool.kv_base, static_cast<uint32_t *>(pool.scales),
                                    ids_dev + ring_start + c0, nblk, geom, opts.max_grid, false, stream, host_part, split,
-                                   opts.direct_grid ? opts.direct_grid : kDefaultDirectScatterGrid));
+                                   opts.direct_grid ? opts.direct_grid : kDefaultTailScatterGrid));
                 TC_RC(time_end(&op, stream));
                 TC_DEV(dev.event_record(slot->last, stream));
                 slot->used = true;

@@ -121,15 +121,22 @@ inline TailSplit host_tail_split(uint32_t div, uint64_t c0, uint32_t nblk, const
 // ------------------------------------------------------------------------------------------ paths
 // Values of tc_opts.direct_offload / direct_upload.
 enum : uint32_t { kPathAuto = 0, kPathDirect = 1, kPathDirectIfDuplex = 2, kPathStaged = 3 };
-// An offload below this many bytes takes the direct path when the choice is left to the library
-// (measured on MI355X: one kernel beats kernel + DMA by ~19 us on small pieces; from about 128 MiB on
-// the staged path is faster).
-constexpr uint64_t kAutoDirectOffloadBytes = 128ull << 20;
 constexpr uint32_t kAutoTailDivisor = 64;
 
-// Direct = the copy kernel writes / reads the pinned host buffer itself.  Kernel-driven D2H traffic
-// overlaps with H2D traffic on the link, two DMAs of opposite direction take turns: so an offload goes
-// direct while an upload of the same context is in flight, and when it is small.
+// Direct = the copy kernel writes / reads the pinned host buffer itself.  Measured on MI355X, 512 MiB next to a
+// kernel that saturates HBM on another stream (transfer time / that kernel's rate, against each alone):
+//   staged                      offload +14 %, upload +22 %     neighbour -2 %
+//   direct, 6 / 8 workgroups    offload +80 %, upload +63 %     neighbour -4 % / -1 %
+//   direct, 16 workgroups       offload +31 %, upload  +4 %     neighbour -42 % / -4 %
+//   direct, 32 workgroups       offload  +5 %, upload  +2 %     neighbour -66 % / -22 %
+// Host-bound stores (direct offload) clog the memory pipeline for everybody once there are enough of them to
+// keep the link busy under load; host-bound loads (direct upload) do not.  So, left to the library:
+// an upload goes direct (16 workgroups: as fast as the link when the GPU is idle, the least disturbed when it
+// is busy, one pass through HBM instead of three); an offload goes through device staging and the copy engine,
+// except while an upload of the same context is in flight: kernel-driven D2H traffic overlaps with H2D traffic
+// on the link, two DMAs of opposite direction take turns.  auto_direct_bytes > 0 adds a size rule for callers
+// whose GPU is otherwise idle: an offload below that many bytes goes direct too (one kernel beats kernel + DMA
+// by ~19 us).
 inline bool offload_goes_direct(uint32_t mode, uint64_t total_bytes, bool upload_in_flight, uint64_t auto_direct_bytes)
 {
     if (mode == kPathDirect) return true;
@@ -137,8 +144,6 @@ inline bool offload_goes_direct(uint32_t mode, uint64_t total_bytes, bool upload
     if (mode == kPathDirectIfDuplex) return upload_in_flight;
     return upload_in_flight || total_bytes < auto_direct_bytes;
 }
-// The direct upload is never slower than DMA + scatter (99 % of the link rate with 8 workgroups) and
-// moves every byte through HBM once instead of three times.
 inline bool upload_goes_direct(uint32_t mode) { return mode != kPathStaged; }
 // tc_opts.host_tail_div: 0 = automatic (a tail only when the transfer has more than one chunk, where the
 // link would otherwise idle once per chunk), 1 = never, N >= 2 = 1/N of every chunk.

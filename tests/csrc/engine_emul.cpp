@@ -517,7 +517,7 @@ int main()
                 opts.max_grid = variant == 1 ? 5 : (variant == 2 ? 19 : 0);       // capped grids: one run, and 8 runs
                 opts.host_tail_div = variant == 3 ? 2 : (variant == 2 ? 1 : 0);
                 opts.direct_grid = variant == 2 ? 3 : 0;
-                opts.auto_direct_bytes = variant == 1 ? 1 : 0;                    // automatic, but nothing is "small"
+                opts.auto_direct_bytes = variant == 1 ? (1ull << 40) : 0;         // automatic, and everything is "small"
                 const uint32_t slot_blocks = variant == 0 ? 64 : 3 + variant;     // one chunk, or several
                 round_trip(sh, opts, 1 + variant % 3, std::min(slot_blocks, sh.NB), ++seed);
             }

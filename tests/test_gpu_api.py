@@ -541,44 +541,47 @@ def test_thousands_of_small_transfers_wrap_the_id_ring():
 
 def test_the_librarys_own_choice_of_path():
     """Default options: an upload goes through the scatter kernel that reads pinned memory itself, an offload
-    below 128 MiB through the gather kernel that writes it, a larger one through device staging and DMA; a
-    larger one issued while an upload is in flight goes direct as well.  Same bytes whichever way."""
+    through device staging and DMA, unless an upload is in flight: then it goes direct as well.  With
+    auto_direct_bytes set, offloads below it go direct, the threshold itself does not.  Same bytes whichever way."""
     rng = W.rng_for(1, salt=36)
     shape = W.CONFIGS[1].with_blocks(400)
     L, NB, pb = shape.num_layers, shape.num_blocks, shape.page_bytes
-    gp = GpuPool(shape, seed=36)
     mirror = None
-    try:
-        from harness import SparseMirror
-        rec = gp.rec
-        perm = W.pick_ids(rng, NB, 63 + 64 + 100 + 100)
-        small, edge, big, dst = perm[:63], perm[63:127], perm[127:227], perm[227:]
-        K.check(K.tc_alloc_at(gp.ctx, perm))
-        K.check(K.tc_set_profiling(gp.ctx, 1))
-        mirror = SparseMirror(gp, perm)
-        bufs = {k: pinned_bytes(len(v) * rec) for k, v in (("small", small), ("edge", edge), ("big", big))}
-        s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    for auto_bytes in (0, 128 << 20):
+        gp = GpuPool(shape, seed=36, auto_direct_bytes=auto_bytes)
+        try:
+            from harness import SparseMirror
+            rec = gp.rec
+            perm = W.pick_ids(rng, NB, 63 + 64 + 100 + 100)
+            small, edge, big, dst = perm[:63], perm[63:127], perm[127:227], perm[227:]
+            K.check(K.tc_alloc_at(gp.ctx, perm))
+            K.check(K.tc_set_profiling(gp.ctx, 1))
+            mirror = SparseMirror(gp, perm)
+            bufs = {k: pinned_bytes(len(v) * rec) for k, v in (("small", small), ("edge", edge), ("big", big))}
+            s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
 
-        def counts():
-            K.check(K.tc_sync(gp.ctx))
-            st = _stats(gp)
-            return st.direct_launches, st.gather_launches, st.scatter_launches
+            def counts():
+                K.check(K.tc_sync(gp.ctx))
+                st = _stats(gp)
+                return st.direct_launches, st.gather_launches, st.scatter_launches
 
-        K.check(K.tc_offload(gp.ctx, small, bufs["small"], s1))          # 126 MiB: direct
-        assert counts() == (1, 0, 0)
-        K.check(K.tc_offload(gp.ctx, edge, bufs["edge"], s1))            # 128 MiB, the threshold itself: staged
-        assert counts() == (1, 1, 0)
-        K.check(K.tc_upload(gp.ctx, bufs["edge"], dst[:64], None, s2))   # uploads: direct
-        assert counts() == (2, 1, 0)
-        junk = pinned_bytes(100 * rec)
-        K.check(K.tc_upload(gp.ctx, junk, dst, None, s2))                # 200 MiB coming in (whatever bytes) ...
-        K.check(K.tc_offload(gp.ctx, big, bufs["big"], s1))              # ... while 200 MiB go out: direct
-        assert counts() == (4, 1, 0)
-        for ids, key in ((small, "small"), (edge, "edge"), (big, "big")):
-            want = np.empty(len(ids) * rec, dtype=np.uint8)
-            oracle.offload(mirror.pool, None, L, NB, pb, 0, ids, want)
-            assert np.array_equal(bufs[key].numpy(), want), key
-    finally:
-        if mirror:
-            mirror.close()
-        gp.close()
+            K.check(K.tc_offload(gp.ctx, small, bufs["small"], s1))          # 126 MiB
+            assert counts() == ((1, 0, 0) if auto_bytes else (0, 1, 0))
+            d, g = counts()[:2]
+            K.check(K.tc_offload(gp.ctx, edge, bufs["edge"], s1))            # 128 MiB, the threshold itself: staged
+            assert counts() == (d, g + 1, 0)
+            K.check(K.tc_upload(gp.ctx, bufs["edge"], dst[:64], None, s2))   # uploads: direct
+            assert counts() == (d + 1, g + 1, 0)
+            junk = pinned_bytes(100 * rec)
+            K.check(K.tc_upload(gp.ctx, junk, dst, None, s2))                # 200 MiB coming in (whatever bytes) ...
+            K.check(K.tc_offload(gp.ctx, big, bufs["big"], s1))              # ... while 200 MiB go out: direct
+            assert counts() == (d + 3, g + 1, 0)
+            for ids, key in ((small, "small"), (edge, "edge"), (big, "big")):
+                want = np.empty(len(ids) * rec, dtype=np.uint8)
+                oracle.offload(mirror.pool, None, L, NB, pb, 0, ids, want)
+                assert np.array_equal(bufs[key].numpy(), want), key
+        finally:
+            if mirror:
+                mirror.close()
+                mirror = None
+            gp.close()

@@ -176,14 +176,15 @@ def test_random_small_shapes_and_options(k):
 
 @pytest.mark.parametrize("k", range(24))
 def test_random_small_shapes_with_the_librarys_choice_of_path(k):
-    """The same 24 shapes with the path left to the library (the default): small offloads and all uploads go
-    through the kernels that touch pinned memory themselves; auto_direct_bytes = 1 in every third case makes the
-    offload staged, with the automatic host tail on transfers of several chunks."""
+    """The same 24 shapes with the path left to the library (the default): uploads go through the scatter kernel
+    that reads pinned memory itself, offloads through staging with the automatic host tail on transfers of several
+    chunks; a large auto_direct_bytes in every third case sends the offload through the direct gather as well."""
     shape, n, opts = _random_case(k)
     for key in ("direct_offload", "direct_upload"):
         opts.pop(key, None)
     if k % 3 == 0:
-        opts["auto_direct_bytes"] = 1
+        opts["auto_direct_bytes"] = 1 << 40
+    else:
         opts.pop("host_tail_div", None)
     print(f"case {k} (auto): L={shape.num_layers} pb={shape.page_bytes} S={shape.scales_per_block} NB={shape.num_blocks} n={n} {opts}", flush=True)
     _round_trip_case(shape, 0, n, salt=2000 + k, auto=True, **opts)
