@@ -171,3 +171,163 @@ def host_view(addr, nbytes):
     """numpy view of pinned memory the library handed out (tc_host_alloc)."""
     import ctypes
     return np.ctypeslib.as_array((ctypes.c_uint8 * int(nbytes)).from_address(int(addr)))
+
+
+class OracleStream:
+    """Byte-for-byte comparison of whole configurations with the oracle, streamed: the blocks an agent owns are
+    pulled into a sparse host mirror at their true strides (through pinned memory, in pieces of at most `piece`
+    blocks), the oracle offloads them from the mirror and its records are compared with the library's; the oracle
+    uploads the library's records into the mirror and the destination blocks are pulled and compared; then the
+    mirror's pages are given back.  The CPU work of each piece runs on a small thread pool (the oracle's C code,
+    numpy copies and comparisons all release the interpreter lock), the GPU copies on the calling thread."""
+
+    def __init__(self, gp, workers=None, piece=192, max_pending=10):
+        from concurrent.futures import ThreadPoolExecutor
+        self.gp, self.piece, self.max_pending = gp, piece, max_pending
+        self.mirror = SparseMirror(gp)
+        self.pool = ThreadPoolExecutor(workers or max(2, min(12, (os.cpu_count() or 4) - 2)))
+        self.pending = []
+        self.stream = torch.cuda.Stream()
+        self.bytes_compared = 0
+
+    # ---- plumbing
+    def _submit(self, fn, *a):
+        self.pending.append(self.pool.submit(fn, *a))
+        while len(self.pending) > self.max_pending:
+            self.pending.pop(0).result()
+
+    def wait(self):
+        while self.pending:
+            self.pending.pop(0).result()
+
+    def _pieces(self, n):
+        return [(a, min(n, a + self.piece)) for a in range(0, n, self.piece)]
+
+    def _pull(self, ids):
+        """(pages [P][n][pb], scale words [S][n] or None) of these blocks in pinned host memory + the event that
+        says the copies have landed.  Runs on its own stream after everything enqueued so far on the device."""
+        gp = self.gp
+        host = torch.empty((gp.P, len(ids), gp.pb), dtype=torch.uint8, pin_memory=True)
+        sc = torch.empty((gp.S, len(ids)), dtype=torch.int32, pin_memory=True) if gp.S else None
+        torch.cuda.synchronize()
+        with torch.cuda.stream(self.stream):
+            # every temporary is made on this stream: a tensor made on another stream could be recycled, and
+            # overwritten, while the gather enqueued here still reads it
+            idx = torch.as_tensor(np.asarray(ids, dtype=np.int64)).to(DEV, non_blocking=False)
+            host.copy_(gp.pool3()[:, idx], non_blocking=True)
+            if gp.S:
+                sc.copy_(gp.scales.view(gp.S, gp.NB)[:, idx], non_blocking=True)
+            ev = torch.cuda.Event()
+            ev.record(self.stream)
+        return host, sc, ev
+
+    @staticmethod
+    def _same(a, b):
+        a, b = np.ascontiguousarray(a).reshape(-1), np.ascontiguousarray(b).reshape(-1)
+        if a.size != b.size:
+            return False
+        k = a.size // 8 * 8
+        return bool((a[:k].view(np.uint64) == b[:k].view(np.uint64)).all()) and bool((a[k:] == b[k:]).all())
+
+    # ---- the three steps
+    def snapshot(self, ids):
+        """Before the offload: the agent's blocks, as they are on the device now, go into the mirror."""
+        ids = np.asarray(ids, dtype=np.int32)
+        for a, b in self._pieces(len(ids)):
+            host, sc, ev = self._pull(ids[a:b])
+
+            def work(sub=ids[a:b].astype(np.int64), host=host, sc=sc, ev=ev):
+                ev.synchronize()
+                gp = self.gp
+                self.mirror.pool.reshape(gp.P, gp.NB, gp.pb)[:, sub] = host.numpy()
+                if gp.S:
+                    self.mirror.scales.reshape(gp.S, gp.NB)[:, sub] = sc.numpy().view(np.uint32)
+            self._submit(work)
+
+    def check_records(self, ids, records, what=""):
+        """After the offload has completed: the oracle's records of these blocks against the library's
+        (`records`: numpy view of the host buffer).  The caller has waited for the snapshot (wait())."""
+        gp = self.gp
+        ids = np.asarray(ids, dtype=np.int32)
+        for a, b in self._pieces(len(ids)):
+            def work(a=a, b=b):
+                want = np.empty((b - a) * gp.rec, dtype=np.uint8)
+                oracle.offload(self.mirror.pool, self.mirror.scales, gp.L, gp.NB, gp.pb, gp.S, ids[a:b], want)
+                assert self._same(want, records[a * gp.rec:b * gp.rec]), f"{what}: records of blocks {a}..{b} differ from the oracle"
+            self._submit(work)
+            self.bytes_compared += (b - a) * gp.rec
+
+    def expected_records(self, ids):
+        """The oracle's records of these blocks, from the mirror as it is now (complete on return)."""
+        gp = self.gp
+        ids = np.asarray(ids, dtype=np.int32)
+        want = np.empty(len(ids) * gp.rec, dtype=np.uint8)
+        for a, b in self._pieces(len(ids)):
+            self._submit(lambda a=a, b=b: oracle.offload(self.mirror.pool, self.mirror.scales, gp.L, gp.NB, gp.pb, gp.S,
+                                                         ids[a:b], want[a * gp.rec:b * gp.rec]))
+        self.wait()
+        return want
+
+    def compare(self, want, got, what=""):
+        """Two byte arrays of whole records, piece by piece on the pool (complete after wait())."""
+        gp = self.gp
+        assert want.size == got.size, f"{what}: {want.size} bytes expected, {got.size} there"
+        for a, b in self._pieces(want.size // gp.rec):
+            def work(a=a, b=b):
+                assert self._same(want[a * gp.rec:b * gp.rec], got[a * gp.rec:b * gp.rec]), \
+                    f"{what}: records of blocks {a}..{b} differ from the oracle"
+            self._submit(work)
+            self.bytes_compared += (b - a) * gp.rec
+
+    def check_upload(self, records, new_ids, what="", table=None):
+        """After the upload has completed: the oracle uploads the same records into the mirror, and the
+        destination blocks on the device must equal the mirror's, pages and scale words.  Returns the table
+        row the oracle wrote, complete after wait() (if `table`, an int32 array of len(new_ids), is given it is
+        filled).  The caller has waited for the steps before."""
+        gp = self.gp
+        new_ids = np.asarray(new_ids, dtype=np.int32)
+        if table is None:
+            table = np.full(len(new_ids), -1, dtype=np.int32)
+        for a, b in self._pieces(len(new_ids)):
+            host, sc, ev = self._pull(new_ids[a:b])
+
+            def work(a=a, b=b, host=host, sc=sc, ev=ev):
+                oracle.upload(records[a * gp.rec:b * gp.rec], gp.L, gp.NB, gp.pb, gp.S, new_ids[a:b], self.mirror.pool,
+                              self.mirror.scales, table[a:b])
+                ev.synchronize()
+                sub = new_ids[a:b].astype(np.int64)
+                assert self._same(host.numpy(), self.mirror.pool.reshape(gp.P, gp.NB, gp.pb)[:, sub]), \
+                    f"{what}: uploaded blocks {a}..{b} differ from the oracle"
+                if gp.S:
+                    assert self._same(sc.numpy().view(np.uint32), self.mirror.scales.reshape(gp.S, gp.NB)[:, sub]), \
+                        f"{what}: scale words of blocks {a}..{b} differ from the oracle"
+            self._submit(work)
+            self.bytes_compared += (b - a) * gp.rec
+        return table
+
+    def drop(self, ids=None):
+        """Gives the mirror's pages of these blocks (all of them without `ids`) back to the system; they read
+        as zeros afterwards."""
+        import mmap
+        self.wait()
+        gp = self.gp
+        mm = self.mirror._mm[0]
+        if gp.pb % mmap.PAGESIZE or not hasattr(mm, "madvise"):
+            return
+        if ids is None:
+            mm.madvise(mmap.MADV_DONTNEED)
+            return
+        blocks = np.sort(np.asarray(ids, dtype=np.int64))
+        if blocks.size == 0:
+            return
+        cuts = np.flatnonzero(np.diff(blocks) != 1) + 1            # runs of consecutive ids: one call per run and plane
+        for run in np.split(blocks, cuts):
+            for p in range(gp.P):
+                mm.madvise(mmap.MADV_DONTNEED, int((p * gp.NB + run[0]) * gp.pb), int(run.size) * gp.pb)
+
+    def close(self):
+        try:
+            self.wait()
+        finally:
+            self.pool.shutdown(wait=True)
+            self.mirror.close()
