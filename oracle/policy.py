@@ -4,9 +4,10 @@ Plain Python written from the paper's statements, in the paper's notation:
 
 * transfer cost (Sec. 4.2, Eq. 2): T_transfer = T_offload(N_blocks) + T_upload(N_blocks), each term
   linear in N_blocks with constants calibrated from per-block measurements on the target platform;
-* ShouldOffload (Sec. 4.2, Alg. 1): reject when T_fc <= T_transfer; otherwise T_window = T_fc -
-  T_transfer, N_capacity = T_window * v_throughput, and the first request in queue order whose
-  incremental KV demand fits the freed blocks and whose work fits N_capacity decides;
+* ShouldOffload (Sec. 4.2, Alg. 1): the scheduling window is the predicted stall minus the transfer time
+  and a window that is not positive rejects; the window times the observed decode throughput is a
+  token capacity; the first request in queue order whose incremental KV demand fits the freed blocks
+  and whose total work fits that capacity decides;
 * upload budget (Sec. 4.3, Eq. 3) and gradual reservation (Sec. 4.3, Eq. 4);
 * the hard rejections that come before any scoring (Sec. 4.2): not enough CPU capacity, a stall
   shorter than the transfer, no waiting request that fits, GPU memory pressure under a threshold;
@@ -47,17 +48,20 @@ def estimate_transfer_ms(model, n_blocks):
 
 
 def should_offload(model, req_blocks, t_fc_ms, v_throughput_tokens_per_ms, waiting):
-    """Alg. 1.  waiting = [(kv_blocks, work_tokens), ...] in queue order.
+    """The gate of Sec. 4.2, from its three paragraphs (transfer overhead, scheduling window, waiting-request
+    fit).  waiting = [(kv_blocks, work_tokens), ...] in queue order.
     Returns (decision, index of the chosen waiting request or -1)."""
-    t_transfer = estimate_transfer_ms(model, req_blocks)
-    if t_fc_ms <= t_transfer:
-        return False, -1                      # stall too short
-    t_window = t_fc_ms - t_transfer
-    n_capacity = t_window * v_throughput_tokens_per_ms
-    for k, (kv_blocks, work_tokens) in enumerate(waiting):   # first fit, queue order
-        if kv_blocks <= req_blocks and work_tokens <= n_capacity:
-            return True, k
-    return False, -1
+    # scheduling window: what is left of the predicted stall once the round trip is paid for
+    window_ms = t_fc_ms - estimate_transfer_ms(model, req_blocks)
+    if not window_ms > 0:
+        return False, -1
+    # the window as decode work, at the throughput the system has been observed to reach
+    tokens_that_fit = window_ms * v_throughput_tokens_per_ms
+    eligible = [k for k, (kv_blocks, work_tokens) in enumerate(waiting)
+                if kv_blocks <= req_blocks and work_tokens <= tokens_that_fit]
+    if not eligible:
+        return False, -1
+    return True, eligible[0]                 # first_fit: the first eligible request in queue order
 
 
 def upload_budget(b_gpu_free, d_critical, b_shared_free):

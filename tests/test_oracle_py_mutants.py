@@ -20,12 +20,12 @@ ODIR = os.path.dirname(oracle.__file__)
 CASES = {
     # (source file, pin module, names to swap in the pin module): {description: (old, new)}
     ("policy.py", pins_policy, ("policy",)): {
-        "a stall equal to the transfer time is accepted": ("if t_fc_ms <= t_transfer:", "if t_fc_ms < t_transfer:"),
-        "last fit instead of first fit": ("for k, (kv_blocks, work_tokens) in enumerate(waiting):",
-                                          "for k, (kv_blocks, work_tokens) in reversed(list(enumerate(waiting))):"),
+        "a stall equal to the transfer time is accepted": ("if not window_ms > 0:", "if not window_ms >= 0:"),
+        "last fit instead of first fit": ("return True, eligible[0]", "return True, eligible[-1]"),
         "a request needing exactly the freed blocks does not fit": ("if kv_blocks <= req_blocks and", "if kv_blocks < req_blocks and"),
-        "capacity divides by the throughput": ("n_capacity = t_window * v_throughput_tokens_per_ms", "n_capacity = t_window / v_throughput_tokens_per_ms"),
-        "the window forgets the transfer time": ("t_window = t_fc_ms - t_transfer", "t_window = t_fc_ms"),
+        "capacity divides by the throughput": ("tokens_that_fit = window_ms * v_throughput_tokens_per_ms", "tokens_that_fit = window_ms / v_throughput_tokens_per_ms"),
+        "the window forgets the transfer time": ("window_ms = t_fc_ms - estimate_transfer_ms(model, req_blocks)", "window_ms = t_fc_ms"),
+        "work is compared with the window in ms": ("and work_tokens <= tokens_that_fit]", "and work_tokens <= window_ms]"),
         "transfer cost drops the upload": ("return t_offload + t_upload", "return t_offload"),
         "budget lets the inner term go negative": ("return max(0, b_gpu_free - max(0, d_critical - b_shared_free))",
                                                    "return max(0, b_gpu_free - (d_critical - b_shared_free))"),
