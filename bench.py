@@ -36,6 +36,8 @@ def parse():
     ap.add_argument("--tokens", type=int, default=4096, help="context length of the agent")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-configs", action="store_true", help="skip the other four configurations")
+    ap.add_argument("--config", type=int, default=0, choices=[0, 1, 3, 4, 5],
+                    help="run only this one of the other configurations and print its object (for profiler runs)")
     return ap.parse_args()
 
 
@@ -223,10 +225,11 @@ class TwoContexts:
     def __init__(self, torch, K, shape, pool, scales, arena_blocks):
         self.K, self.shape = K, shape
         a = (shape.num_layers, shape.num_blocks, shape.page_bytes, shape.block_size, shape.scales_per_block)
-        self.rec = (2 * shape.num_layers * shape.page_bytes + 4 * shape.scales_per_block + 255) // 256 * 256
-        rc, self.auto = K.tc_create(pool, scales, *a, host_arena_bytes=arena_blocks * self.rec)
+        # the arena is sized by an upper bound of the record size; what a record is, the library says
+        bound = 2 * shape.num_layers * shape.page_bytes + 4 * shape.scales_per_block + 256
+        rc, self.auto = K.tc_create(pool, scales, *a, host_arena_bytes=arena_blocks * bound)
         K.check(rc)
-        assert K.tc_record_bytes(self.auto) == self.rec
+        self.rec = K.tc_record_bytes(self.auto)
         rc, self.staged = K.tc_create(pool, scales, *a, direct_offload=K.TC_PATH_STAGED, direct_upload=K.TC_PATH_STAGED,
                                       host_tail_div=1)
         K.check(rc)
@@ -450,16 +453,15 @@ def config5(torch, K, W, link):
     budget = min(16 << 30, int(0.2 * avail)) if avail else 8 << 30
     tokens = W.uniform_contexts(rng, 128)
     private = (W.blocks_of(tokens, shape.block_size) - 32).astype(int)
-    rec = 160 * 32768 + 768
-    wave, used = [], 0
+    bound = shape.planes * shape.page_bytes + 4 * shape.scales_per_block + 256      # what a record can take at most
+    arena_blocks = budget // bound
+    two = TwoContexts(torch, K, shape, pool, scales.view(torch.int32), arena_blocks)
+    wave = []
     for n in private:                 # agents in index order while the arena has room
-        if used + n * rec > budget:
+        if sum(wave) + n + 8 > arena_blocks:
             break
         wave.append(int(n))
-        used += n * rec
     total = sum(wave)
-    two = TwoContexts(torch, K, shape, pool, scales.view(torch.int32), total + 8)
-    assert two.rec == rec
     perm = rng.permutation(shape.num_blocks).astype(np.int32)
     rest = perm[32:]                  # the first 32 stand for the shared prefix blocks, which stay
     cuts = np.cumsum(wave)[:-1]
@@ -470,7 +472,7 @@ def config5(torch, K, W, link):
     stream = torch.cuda.Stream()
     out, _ = batch_both_ways(torch, K, two, link, src, dst, [tables[i].data_ptr() + 128 for i in range(len(wave))], stream,
                              total * shape.block_size)
-    out["workload"] = (f"70B fp8 shape: 80 layers, 32-token blocks, 32 KiB pages + 160 fp32 scale words (record 5 MiB + 768 B), "
+    out["workload"] = (f"70B fp8 shape: 80 layers, 32-token blocks, 32 KiB pages + 160 fp32 scale words (record {two.rec} B), "
                        f"32 768 blocks (160 GiB); one wave of {len(wave)} of the 128 agents (contexts uniform 1k..32k tokens, "
                        f"32 shared prefix blocks stay), sized to a pinned arena of {budget / 2 ** 30:.0f} GiB")
     two.close()
@@ -560,6 +562,16 @@ def main():
         sys.exit(2)
     import paper_2510_18586_amd as K
     import tc_workloads as W
+
+    if args.config:
+        stream = torch.cuda.Stream()
+        link = pinned_link_peak(torch, 512 << 20, stream)
+        if args.config == 3:
+            one = config3(torch, K, W, link, fresh_pool(torch, W.CONFIGS[2])[0])
+        else:
+            one = {1: config1, 4: config4, 5: config5}[args.config](torch, K, W, link)
+        print(json.dumps({"config": str(args.config), **one}))
+        return
 
     cfg_index = 1
     shape = W.CONFIGS[cfg_index]

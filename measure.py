@@ -1,22 +1,25 @@
-"""Measurements beyond the headline benchmark line, for all five configurations.
+#!/usr/bin/env python3
+"""Measurements beyond the benchmark line (bench.py covers configurations 1, 2, 3 and 5 and the overlap).
 
-    python -m paper_2510_18586_amd.measure [--only sweep,naive,config1,config3,config4,config4_replay,forecast_noise,config5,lds,host] [--out FILE]
+    python3 measure.py [--only hbm_limits,contention,dma_spread,sweep,naive,config4,config4_replay,forecast_noise,lds,host]
+                       [--out FILE]
 
-Prints one JSON object per measurement (and writes them to --out).  Needs a GPU.  Times are
-wall-clock around enqueue + synchronisation unless stated; GB = 1e9 bytes.
-  sweep    offload / upload time against the number of blocks (64..320, the paper's Sec. 7.6 range),
-           for the 8B shape and the paper's 14B shape, with the per-block constants of the linear
-           cost model (Eq. 2): T(N) = a + b N
+Prints one JSON object per measurement (and writes them to --out).  Needs a GPU.  Kernel and transfer
+times are HIP events on the stream of the work unless stated; GB = 1e9 bytes.
+  hbm_limits  what HBM gives a streaming kernel on 512 MiB that no cache holds: reading only, writing only
+           (non-temporal), a contiguous copy, and the two page kernels on device-resident records.  This is
+           the program the counter passes under profiles/ run.
+  contention  a 512 MiB transfer of every path and launch width next to a kernel that saturates HBM on
+           another stream: how much the transfer slows down, how much the neighbour does
+  dma_spread  repeated two-chunk staged transfers of 4 MiB records: spread of the copy engine's per-chunk rate
+  sweep    offload / upload time against the number of blocks (64..320, the range of Sec. 7.6), for the 8B
+           shape and the paper's 14B shape, with the per-block constants of the linear cost model (Eq. 2)
   naive    the same 256-block transfer done with one hipMemcpyAsync per page and with one
            hipMemcpy2DAsync per block, no gather kernel (comparators)
-  config1  the tiny configuration: latency of an 8-block transfer
-  config3  64 agents offloaded / uploaded as a batch, alone and while an HBM-streaming kernel
-           runs on another stream; the neighbour's own bandwidth alone and overlapped
   config4  32B shape (4 MiB per block): per-agent transfer rates over the trace's agent sizes
   config4_replay  the 200-agent trace in real time (about 27 s): share of uploads that are complete when
            the tool returns, stall otherwise, per-transfer rates
   forecast_noise  that replay with the forecaster of Eq. 1 and noisy user estimates (sigma 0, 0.25, 0.5)
-  config5  70B fp8 shape with scales: one wave of private blocks as a batch
   lds      a contiguous 512 MiB device copy through registers (what the copy kernels do), staged in LDS,
            and with LDS-direct loads: what LDS adds to a copy without reuse
   host     host-side cost of the calls around a 256-block transfer (bookkeeping, enqueue, index, keys),
@@ -24,6 +27,7 @@ wall-clock around enqueue + synchronisation unless stated; GB = 1e9 bytes.
 """
 import argparse
 import json
+import os
 import sys
 import time
 
@@ -31,7 +35,7 @@ import numpy as np
 
 
 def _sync_time(torch, fn, reps=5, warm=1):
-    """Median wall time of fn() + device synchronisation."""
+    """Median wall time of fn() + device synchronisation (host-side view of a whole call)."""
     ts = []
     for i in range(reps + warm):
         torch.cuda.synchronize()
@@ -43,13 +47,20 @@ def _sync_time(torch, fn, reps=5, warm=1):
     return float(np.median(ts))
 
 
-def _link_peak(torch, nbytes):
-    nbytes = int(min(nbytes, 4 << 30))
-    host = torch.empty(nbytes, dtype=torch.uint8, pin_memory=True)
-    dev = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0")
-    d2h = nbytes / _sync_time(torch, lambda: host.copy_(dev, non_blocking=True)) / 1e9
-    h2d = nbytes / _sync_time(torch, lambda: dev.copy_(host, non_blocking=True)) / 1e9
-    return d2h, h2d
+def _events(torch, stream, fn, after=None, reps=5, warm=1):
+    """Event-timed fn() on `stream`: (median, best, worst) in ms.  after() retires what fn enqueued."""
+    ts = []
+    for i in range(reps + warm):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        fn()
+        e1.record(stream)
+        if after:
+            after()
+        stream.synchronize()
+        if i >= warm:
+            ts.append(e0.elapsed_time(e1))
+    return float(np.median(ts)), float(min(ts)), float(max(ts))
 
 
 class Ctx:
@@ -65,17 +76,237 @@ class Ctx:
             self.pool.view(torch.int32).random_(0, 2 ** 31 - 1)
             sc = torch.rand(shape.scales_per_block * shape.num_blocks, device="cuda:0") if shape.scales_per_block else None
         self.scales = sc
-        P, pb, S = shape.planes, shape.page_bytes, shape.scales_per_block
-        self.rec = (P * pb + 4 * S + 255) // 256 * 256
+        pb, S = shape.page_bytes, shape.scales_per_block
+        # an upper bound of the record size only sizes the arena; the library says what a record is
         rc, self.ctx = K.tc_create(self.pool, sc, shape.num_layers, shape.num_blocks, pb, shape.block_size, S,
-                                   host_arena_bytes=arena_blocks * self.rec, **opts)
+                                   host_arena_bytes=arena_blocks * (shape.planes * pb + 4 * S + 256), **opts)
         K.check(rc)
-        assert K.tc_record_bytes(self.ctx) == self.rec
+        self.rec = K.tc_record_bytes(self.ctx)
 
     def close(self):
         self.K.check(self.K.tc_destroy(self.ctx))
         self.pool = self.scales = None
         self.torch.cuda.empty_cache()
+
+
+def m_hbm_limits(torch, K, W, emit, reps=12):
+    """512 MiB per launch, every launch on memory that no cache holds: the regions rotate through 3 GiB, the
+    block sets through the whole 32 GiB pool."""
+    shape = W.CONFIGS[1]
+    c = Ctx(torch, K, W, shape, 1, 1, fill=False)
+    n, slots = 256, 6
+    nbytes = n * c.rec
+    src = torch.empty(slots * nbytes, dtype=torch.uint8, device="cuda:0")
+    src.view(torch.int32).random_(0, 2 ** 31 - 1)
+    dst = torch.zeros(slots * nbytes, dtype=torch.uint8, device="cuda:0")
+    perm = W.rng_for(1, salt=60).permutation(shape.num_blocks).astype(np.int32)
+    sets = [np.ascontiguousarray(perm[k * n:(k + 1) * n]) for k in range(shape.num_blocks // n)]
+    stream = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    k = [0]
+
+    def region(t):
+        return t.data_ptr() + (k[0] % slots) * nbytes
+
+    # the same 32 GiB seen as one layer of 32 x as many blocks: every 32 KiB page of a transfer lies at a random
+    # place, instead of 64 pages of one block at the same offset in 64 planes
+    import dataclasses
+    flat_shape = dataclasses.replace(shape, num_layers=1, num_blocks=shape.num_blocks * shape.num_layers)
+    flat = Ctx(torch, K, W, flat_shape, 1, 1, pool=c.pool)
+    n_flat = nbytes // flat.rec
+    perm_flat = W.rng_for(1, salt=63).permutation(flat_shape.num_blocks).astype(np.int32)
+    sets_flat = [np.ascontiguousarray(perm_flat[j * n_flat:(j + 1) * n_flat]) for j in range(16)]
+    kernels = (
+        ("read only (tc_hbm_read)", 1, c, lambda: K.tc_hbm_read(region(src), nbytes, stream)),
+        ("write only, non-temporal (tc_hbm_write)", 1, c, lambda: K.tc_hbm_write(region(dst), nbytes, stream)),
+        ("contiguous copy (tc_copy_contiguous)", 2, c, lambda: K.tc_copy_contiguous(region(dst), region(src), nbytes, stream)),
+        ("gather_pages: scattered pool pages -> device records", 2, c,
+         lambda: K.tc_stage_on_device(c.ctx, 0, sets[k[0] % len(sets)], region(dst), stream)),
+        ("scatter_pages: device records -> scattered pool pages", 2, c,
+         lambda: K.tc_stage_on_device(c.ctx, 1, sets[k[0] % len(sets)], region(src), stream)),
+        ("gather_pages, every page at a random place (one-layer view)", 2, flat,
+         lambda: K.tc_stage_on_device(flat.ctx, 0, sets_flat[k[0] % 16], region(dst), stream)),
+        ("scatter_pages, every page at a random place (one-layer view)", 2, flat,
+         lambda: K.tc_stage_on_device(flat.ctx, 1, sets_flat[k[0] % 16], region(src), stream)),
+    )
+    rows = []
+    for name, ways, owner, fn in kernels:
+        ts = []
+        for i in range(reps + 2):
+            k[0] += 1
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            K.check(fn())
+            e1.record(stream)
+            K.check(K.tc_sync(owner.ctx))
+            stream.synchronize()
+            if i >= 2:
+                ts.append(e0.elapsed_time(e1) * 1e3)
+        avg = float(np.mean(ts))
+        rows.append(dict(kernel=name, launches=reps + 2, bytes_per_launch=ways * nbytes, avg_us=round(avg, 2),
+                         best_us=round(min(ts), 2), worst_us=round(max(ts), 2), TBps=round(ways * nbytes / avg / 1e6, 3),
+                         frac_of_8TBps=round(ways * nbytes / avg / 1e6 / 8, 4)))
+    K.check(K.tc_destroy(flat.ctx))
+    rd, wr = rows[0]["avg_us"], rows[1]["avg_us"]
+    emit(dict(measurement="hbm_limits", MiB_one_way=nbytes / 2 ** 20, reps=reps, rows=rows,
+              read_time_plus_write_time_us=round(rd + wr, 2),
+              note="a copy takes about as long as reading its bytes and then writing them: the two directions "
+                   "share the memory system instead of overlapping"))
+    del src, dst
+    c.close()
+
+
+def m_contention(torch, K, W, emit):
+    """One 256-block agent (512 MiB), three transfers in a row, while an fp32 triad over 3 x 4 GiB keeps HBM busy
+    on another stream.  Against each of them alone."""
+    shape = W.CONFIGS[1]
+    c0 = Ctx(torch, K, W, shape, 1, 1, fill=False)
+    pool = c0.pool
+    K.check(K.tc_destroy(c0.ctx))
+    m = 1 << 30
+    a, b, cc = torch.zeros(m, device="cuda:0"), torch.rand(m, device="cuda:0"), torch.rand(m, device="cuda:0")
+    stream, compute = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+
+    def tri(iters):
+        K.check(K.tc_hbm_stream(a, b, cc, m, 0.5, iters, compute))
+
+    tri(4)
+    compute.synchronize()
+    t_tri = _events(torch, compute, lambda: tri(8), reps=3)[0] / 8
+    n = 256
+    perm = W.rng_for(1, salt=61).permutation(shape.num_blocks).astype(np.int32)
+    ids = np.ascontiguousarray(perm[:n])
+    rows = []
+    cases = [("staged", K.TC_PATH_STAGED, 0)] + [("direct", K.TC_PATH_DIRECT, g) for g in (6, 8, 16, 32)]
+    for name, mode, grid in cases:
+        d = Ctx(torch, K, W, shape, 1, n + 1, pool=pool, direct_offload=mode, direct_upload=mode, host_tail_div=1,
+                direct_grid=grid)
+        K.check(K.tc_alloc_at(d.ctx, ids))
+        rc, buf = K.tc_host_alloc(d.ctx, n)
+        K.check(rc)
+        row = dict(path=name, workgroups=grid or None)
+        for dname, fn in (("offload", lambda: K.check(K.tc_offload(d.ctx, ids, buf, stream))),
+                          ("upload", lambda: K.check(K.tc_upload(d.ctx, buf, ids, None, stream)))):
+            alone = _events(torch, stream, fn, after=lambda: K.check(K.tc_sync(d.ctx)), reps=3)[0]
+            iters = int(4 * alone / t_tri) + 4
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+            torch.cuda.synchronize()
+            ev[0].record(compute)
+            tri(iters)
+            ev[1].record(compute)
+            time.sleep(0.003)                      # the neighbour is running before the first transfer starts
+            ev[2].record(stream)
+            for _ in range(3):
+                fn()
+            ev[3].record(stream)
+            K.check(K.tc_sync(d.ctx))
+            torch.cuda.synchronize()
+            busy = ev[2].elapsed_time(ev[3]) / 3
+            lost = ev[0].elapsed_time(ev[1]) - iters * t_tri      # what the neighbour lost, all of it during the overlap
+            row[dname] = dict(alone_ms=round(alone, 3), next_to_neighbour_ms=round(busy, 3),
+                              transfer_slower_pct=round(100 * (busy / alone - 1), 1),
+                              neighbour_slower_pct_while_overlapped=round(100 * lost / (3 * busy), 1))
+        rows.append(row)
+        K.check(K.tc_free(d.ctx, ids))
+        K.check(K.tc_host_free(d.ctx, buf))
+        K.check(K.tc_destroy(d.ctx))
+    emit(dict(measurement="contention", MiB=n * 2, neighbour="fp32 triad a = b + s c over 3 x 4 GiB",
+              neighbour_alone_GBps=round(12 * m / t_tri / 1e6, 1), rows=rows))
+    del a, b, cc, pool
+    torch.cuda.empty_cache()
+
+
+class _LinkWatch:
+    """Samples what the kernel driver reports about the GPU's PCIe link (sysfs, world-readable) while a transfer
+    runs: the distinct values seen, in order of first appearance."""
+
+    FILES = ("current_link_speed", "current_link_width", "pp_dpm_pcie", "pp_dpm_fclk", "pp_dpm_socclk", "pp_dpm_mclk")
+
+    def __init__(self):
+        import glob
+        import threading
+        self.paths = [p for f in self.FILES for p in sorted(glob.glob("/sys/class/drm/card*/device/" + f))]
+        self.seen, self.stop, self.thread, self._threading = [], False, None, threading
+
+    def _read(self):
+        out = []
+        for p in self.paths:
+            try:
+                with open(p) as f:
+                    txt = f.read()
+                if "pp_dpm_" in p:
+                    txt = " ".join(l.strip() for l in txt.splitlines() if l.rstrip().endswith("*"))
+                out.append(txt.strip())
+            except OSError:
+                out.append("?")
+        return tuple(out)
+
+    def __enter__(self):
+        self.seen, self.stop = [], False
+
+        def loop():
+            while not self.stop:
+                v = self._read()
+                if v not in self.seen:
+                    self.seen.append(v)
+                time.sleep(0.002)
+        self.thread = self._threading.Thread(target=loop, daemon=True)
+        self.thread.start()
+        return self
+
+    def __exit__(self, *a):
+        self.stop = True
+        self.thread.join()
+
+
+def m_dma_spread(torch, K, W, emit, reps=24):
+    """Staged transfers of 1 006 records of 4 MiB (eight chunks each way), one after the other with nothing else
+    on the GPU: the copy engine's rate per transfer, from the event pairs the library puts around each chunk, and
+    what the driver said about the PCIe link meanwhile."""
+    shape = W.CONFIGS[3]
+    n = 1006
+    c = Ctx(torch, K, W, shape, 3, n + 2, fill=False, direct_offload=K.TC_PATH_STAGED, direct_upload=K.TC_PATH_STAGED,
+            host_tail_div=1)
+    ids = W.pick_ids(W.rng_for(3, salt=62), shape.num_blocks, n)
+    K.check(K.tc_alloc_at(c.ctx, ids))
+    rc, buf = K.tc_host_alloc(c.ctx, n)
+    K.check(rc)
+    stream = torch.cuda.Stream()
+    K.check(K.tc_set_profiling(c.ctx, 1))
+    watch = _LinkWatch()
+
+    def host_cpu_ticks():
+        # busy and total jiffies of the whole host (other tenants included), from /proc/stat
+        with open("/proc/stat") as f:
+            v = [int(x) for x in f.readline().split()[1:9]]
+        return sum(v) - v[3] - v[4], sum(v)
+
+    rows, prev = [], K.tc_stats(c.ctx)[1]
+    for r in range(reps):
+        busy0, all0 = host_cpu_ticks()
+        if r % 3 == 2:
+            time.sleep(0.5)                  # an idle gap, as between the agents of a trace
+        with watch:
+            off = _events(torch, stream, lambda: K.check(K.tc_offload(c.ctx, ids, buf, stream)),
+                          after=lambda: K.check(K.tc_sync(c.ctx)), reps=1, warm=0)[0]
+        link_off = list(watch.seen)
+        with watch:
+            up = _events(torch, stream, lambda: K.check(K.tc_upload(c.ctx, buf, ids, None, stream)),
+                         after=lambda: K.check(K.tc_sync(c.ctx)), reps=1, warm=0)[0]
+        st = K.tc_stats(c.ctx)[1]
+        rows.append(dict(rep=r, after_idle_gap=(r % 3 == 2),
+                         offload_GBps=round(n * c.rec / off / 1e6, 2), upload_GBps=round(n * c.rec / up / 1e6, 2),
+                         d2h_dma_GBps=round((st.d2h_bytes - prev.d2h_bytes) / max(st.d2h_ms - prev.d2h_ms, 1e-9) / 1e6, 2),
+                         h2d_dma_GBps=round((st.h2d_bytes - prev.h2d_bytes) / max(st.h2d_ms - prev.h2d_ms, 1e-9) / 1e6, 2),
+                         link_during_offload=link_off, link_during_upload=list(watch.seen),
+                         host_cpus_busy=round((host_cpu_ticks()[0] - busy0) / max(1, host_cpu_ticks()[1] - all0) * (os.cpu_count() or 1), 1)))
+        prev = st
+    emit(dict(measurement="dma_spread", shape=shape.name, blocks=n, GiB=n * c.rec / 2 ** 30, chunks_each_way=8,
+              link_files=watch.paths, rows=rows))
+    K.check(K.tc_free(c.ctx, ids))
+    K.check(K.tc_host_free(c.ctx, buf))
+    c.close()
 
 
 def m_sweep(torch, K, W, emit):
@@ -92,8 +323,9 @@ def m_sweep(torch, K, W, emit):
             K.check(K.tc_alloc_at(c.ctx, ids))
             K.check(K.tc_alloc_at(c.ctx, new))
             table = torch.zeros(n, dtype=torch.int32, device="cuda:0")
-            t_off = _sync_time(torch, lambda: K.check(K.tc_offload(c.ctx, ids, host, stream)), reps=7)
-            t_up = _sync_time(torch, lambda: K.check(K.tc_upload(c.ctx, host, new, table, stream)), reps=7)
+            done = lambda: K.check(K.tc_sync(c.ctx))
+            t_off = _events(torch, stream, lambda: K.check(K.tc_offload(c.ctx, ids, host, stream)), done, reps=7)[0] * 1e-3
+            t_up = _events(torch, stream, lambda: K.check(K.tc_upload(c.ctx, host, new, table, stream)), done, reps=7)[0] * 1e-3
             K.check(K.tc_sync(c.ctx))
             K.check(K.tc_free(c.ctx, ids))
             K.check(K.tc_free(c.ctx, new))
@@ -138,162 +370,6 @@ def m_naive(torch, K, W, emit):
     c.close()
 
 
-def m_config1(torch, K, W, emit):
-    shape = W.CONFIGS[0]
-    out = dict(measurement="config1", note="latency-bound: 256 KiB per direction")
-    for tag, opts in (("", {}), ("direct_", dict(direct_offload=1, direct_upload=1))):
-        c = Ctx(torch, K, W, shape, 0, 16, **opts)
-        rng = W.rng_for(0)
-        ids = W.pick_ids(rng, shape.num_blocks, 8)
-        new = W.pick_ids(rng, shape.num_blocks, 8, exclude=ids)
-        rc, host = K.tc_host_alloc(c.ctx, 8)
-        K.check(rc)
-        K.check(K.tc_alloc_at(c.ctx, ids))
-        K.check(K.tc_alloc_at(c.ctx, new))
-        stream = torch.cuda.Stream()
-        table = torch.zeros(8, dtype=torch.int32, device="cuda:0")
-        t_off = _sync_time(torch, lambda: K.check(K.tc_offload(c.ctx, ids, host, stream)), reps=50, warm=5)
-        t_up = _sync_time(torch, lambda: K.check(K.tc_upload(c.ctx, host, new, table, stream)), reps=50, warm=5)
-        out.update({"payload_KiB": 8 * c.rec / 1024, tag + "offload_us": t_off * 1e6, tag + "upload_us": t_up * 1e6,
-                    tag + "offload_GBps": 8 * c.rec / t_off / 1e9, tag + "upload_GBps": 8 * c.rec / t_up / 1e9})
-        c.close()
-    emit(out)
-
-
-def m_config3(torch, K, W, emit):
-    shape = W.CONFIGS[2]
-    rng = W.rng_for(2)
-    tokens = W.lognormal_contexts(rng, 64)
-    nblk = W.blocks_of(tokens, shape.block_size).astype(int)
-    total = int(nblk.sum())
-    c = Ctx(torch, K, W, shape, 2, total + 8, fill=False)
-
-    class B:
-        def alloc(self, n):
-            rc, ids = K.tc_alloc(c.ctx, n)
-            return ids if rc == 0 else None
-
-        def free(self, ids):
-            K.check(K.tc_free(c.ctx, ids))
-
-        def n_free(self):
-            return K.tc_stats(c.ctx)[1].gpu_blocks_free
-
-    W.fragment_pool(B(), rng, n_ops=50000, need_free=total)
-    src = [B().alloc(int(n)) for n in nblk]
-    dst = src            # 2 x total exceeds the pool: the upload claims the original blocks again
-    bufs = [K.tc_host_alloc(c.ctx, int(n))[1] for n in nblk]
-    tables = torch.full((64, int(nblk.max()) + 1), -1, dtype=torch.int32, device="cuda:0")
-    copy, compute = torch.cuda.Stream(), torch.cuda.Stream()
-    nbytes = total * c.rec
-    d2h, h2d = _link_peak(torch, nbytes)
-
-    # the neighbour: fp32 triad over 3 x 4 GiB
-    m = 1 << 30
-    a = torch.zeros(m, device="cuda:0")
-    b = torch.rand(m, device="cuda:0")
-    cc = torch.rand(m, device="cuda:0")
-    tri_bytes = 3 * 4 * m
-
-    def offload():
-        K.check(K.tc_offload_batch(c.ctx, [(src[i], bufs[i]) for i in range(64)], copy))
-
-    def upload():
-        K.check(K.tc_upload_batch(c.ctx, [(dst[i], bufs[i], tables[i]) for i in range(64)], copy))
-
-    def offload_singles():
-        for i in range(64):
-            K.check(K.tc_offload(c.ctx, src[i], bufs[i], copy))
-
-    t_off = _sync_time(torch, offload, reps=3)
-    t_off1 = _sync_time(torch, offload_singles, reps=3)
-    t_up = _sync_time(torch, upload, reps=3)
-    t_tri = _sync_time(torch, lambda: K.check(K.tc_hbm_stream(a, b, cc, m, 0.5, 4, compute)), reps=3) / 4
-
-    def overlapped(fn, iters):
-        # neighbour runs for the whole copy; its rate is taken from its own events
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        torch.cuda.synchronize()
-        t = time.perf_counter()
-        e0.record(compute)
-        K.check(K.tc_hbm_stream(a, b, cc, m, 0.5, iters, compute))
-        e1.record(compute)
-        fn()
-        copy.synchronize()
-        t_copy = time.perf_counter() - t
-        torch.cuda.synchronize()
-        return t_copy, e0.elapsed_time(e1) * 1e-3 / iters
-
-    iters_off = max(1, int(t_off / t_tri))
-    iters_up = max(1, int(t_up / t_tri))
-    overlapped(offload, iters_off)
-    t_off_ov, tri_off = overlapped(offload, iters_off)
-    t_up_ov, tri_up = overlapped(upload, iters_up)
-    # full duplex: half of the agents go out while the other half comes back, on two streams
-    copy2 = torch.cuda.Stream()
-    half_bytes_out = int(nblk[:32].sum()) * c.rec
-    half_bytes_in = int(nblk[32:].sum()) * c.rec
-
-    def duplex():
-        K.check(K.tc_offload_batch(c.ctx, [(src[i], bufs[i]) for i in range(32)], copy))
-        K.check(K.tc_upload_batch(c.ctx, [(dst[i], bufs[i], tables[i]) for i in range(32, 64)], copy2))
-
-    t_dup = _sync_time(torch, duplex, reps=3)
-    t_out = _sync_time(torch, lambda: K.check(K.tc_offload_batch(c.ctx, [(src[i], bufs[i]) for i in range(32)], copy)), reps=3)
-    t_in = _sync_time(torch, lambda: K.check(K.tc_upload_batch(
-        c.ctx, [(dst[i], bufs[i], tables[i]) for i in range(32, 64)], copy2)), reps=3)
-    # the same with offloads written by the gather kernel straight into pinned memory while uploads are
-    # in flight (direct_offload = 2), and the neighbour's rate next to such direct offloads (= 1)
-    direct = {}
-    for mode in (2, 1):
-        d = Ctx(torch, K, W, shape, 2, total + 8, pool=c.pool, direct_offload=mode)
-        for i in range(64):
-            K.check(K.tc_alloc_at(d.ctx, src[i]))
-        dbufs = [K.tc_host_alloc(d.ctx, int(n))[1] for n in nblk]
-        K.check(K.tc_offload_batch(d.ctx, [(src[i], dbufs[i]) for i in range(64)], copy))
-        K.check(K.tc_sync(d.ctx))
-
-        def dduplex():
-            K.check(K.tc_upload_batch(d.ctx, [(src[i], dbufs[i], tables[i]) for i in range(32, 64)], copy2))
-            K.check(K.tc_offload_batch(d.ctx, [(src[i], dbufs[i]) for i in range(32)], copy))
-
-        if mode == 2:
-            direct["duplex_ms"] = _sync_time(torch, dduplex, reps=3) * 1e3
-        else:
-            t_d = _sync_time(torch, lambda: K.check(K.tc_offload_batch(d.ctx, [(src[i], dbufs[i]) for i in range(64)], copy)), reps=3)
-            direct["offload_batch_GBps"] = nbytes / t_d / 1e9
-
-            def direct_offload():
-                K.check(K.tc_offload_batch(d.ctx, [(src[i], dbufs[i]) for i in range(64)], copy))
-
-            iters = max(1, int(t_d / t_tri))
-            overlapped(direct_offload, iters)
-            t_dov, tri_d = overlapped(direct_offload, iters)
-            direct["overlapped_offload_GBps"] = nbytes / t_dov / 1e9
-            direct["hbm_stream_during_direct_offload_GBps"] = tri_bytes / tri_d / 1e9
-        K.check(K.tc_sync(d.ctx))
-        K.check(K.tc_destroy(d.ctx))
-    emit(dict(measurement="config3", agents=64, blocks=total, GiB=nbytes / 2 ** 30,
-              link_d2h_GBps=d2h, link_h2d_GBps=h2d,
-              offload_batch_GBps=nbytes / t_off / 1e9, offload_64_single_calls_GBps=nbytes / t_off1 / 1e9,
-              upload_batch_GBps=nbytes / t_up / 1e9,
-              offload_pct_link=100 * nbytes / t_off / 1e9 / d2h, upload_pct_link=100 * nbytes / t_up / 1e9 / h2d,
-              overlapped_offload_GBps=nbytes / t_off_ov / 1e9, overlapped_upload_GBps=nbytes / t_up_ov / 1e9,
-              hbm_stream_alone_GBps=tri_bytes / t_tri / 1e9,
-              hbm_stream_during_offload_GBps=tri_bytes / tri_off / 1e9,
-              hbm_stream_during_upload_GBps=tri_bytes / tri_up / 1e9,
-              upload_ms_per_1k_tokens=t_up * 1e3 / (total * shape.block_size / 1024),
-              duplex_half_out_half_in_GBps=(half_bytes_out + half_bytes_in) / t_dup / 1e9,
-              duplex_ms=t_dup * 1e3, half_out_alone_ms=t_out * 1e3, half_in_alone_ms=t_in * 1e3,
-              duplex_direct_ms=direct["duplex_ms"],
-              duplex_direct_GBps=(half_bytes_out + half_bytes_in) / (direct["duplex_ms"] * 1e-3) / 1e9,
-              direct_offload_batch_GBps=direct["offload_batch_GBps"],
-              direct_overlapped_offload_GBps=direct["overlapped_offload_GBps"],
-              hbm_stream_during_direct_offload_GBps=direct["hbm_stream_during_direct_offload_GBps"]))
-    del a, b, cc
-    c.close()
-
-
 def m_config4(torch, K, W, emit):
     shape = W.CONFIGS[3]
     agents, _ = W.dag_trace(W.rng_for(3), block_size=shape.block_size)
@@ -311,9 +387,9 @@ def m_config4(torch, K, W, emit):
         K.check(K.tc_alloc_at(c.ctx, ids))
         K.check(K.tc_alloc_at(c.ctx, new))
         table = torch.zeros(n, dtype=torch.int32, device="cuda:0")
-        t_off = _sync_time(torch, lambda: K.check(K.tc_offload(c.ctx, ids, host, stream)))
-        t_up = _sync_time(torch, lambda: K.check(K.tc_upload(c.ctx, host, new, table, stream)))
-        K.check(K.tc_sync(c.ctx))
+        done = lambda: K.check(K.tc_sync(c.ctx))
+        t_off = _events(torch, stream, lambda: K.check(K.tc_offload(c.ctx, ids, host, stream)), done)[0] * 1e-3
+        t_up = _events(torch, stream, lambda: K.check(K.tc_upload(c.ctx, host, new, table, stream)), done)[0] * 1e-3
         for x in (ids, new):
             K.check(K.tc_free(c.ctx, x))
         K.check(K.tc_host_free(c.ctx, host))
@@ -453,42 +529,6 @@ def m_forecast_noise(torch, K, W, emit, speed=2.0):
     c.close()
 
 
-def m_config5(torch, K, W, emit):
-    shape = W.CONFIGS[4]
-    rng = W.rng_for(4, salt=53)
-    tokens = W.uniform_contexts(rng, 12)
-    private = (W.blocks_of(tokens, shape.block_size) - 32).astype(int)
-    total = int(private.sum())
-    c = Ctx(torch, K, W, shape, 4, total + 8, fill=False)
-    perm = rng.permutation(shape.num_blocks).astype(np.int32)
-    cuts = np.cumsum(private)[:-1]
-    src = np.split(perm[:total], cuts)
-    dst = np.split(perm[total:2 * total], cuts)
-    for x in src + dst:
-        K.check(K.tc_alloc_at(c.ctx, x))
-    bufs = [K.tc_host_alloc(c.ctx, int(n))[1] for n in private]
-    tables = torch.full((12, 1024), -1, dtype=torch.int32, device="cuda:0")
-    stream = torch.cuda.Stream()
-    nbytes = total * c.rec
-    d2h, h2d = _link_peak(torch, nbytes)
-    t_off = _sync_time(torch, lambda: K.check(K.tc_offload_batch(c.ctx, [(src[i], bufs[i]) for i in range(12)], stream)), reps=3)
-    t_up = _sync_time(torch, lambda: K.check(K.tc_upload_batch(
-        c.ctx, [(dst[i], bufs[i], tables[i].data_ptr() + 128) for i in range(12)], stream)), reps=3)
-    K.check(K.tc_set_profiling(c.ctx, 1))
-    K.check(K.tc_offload_batch(c.ctx, [(src[i], bufs[i]) for i in range(12)], stream))
-    K.check(K.tc_upload_batch(c.ctx, [(dst[i], bufs[i], tables[i].data_ptr() + 128) for i in range(12)], stream))
-    K.check(K.tc_sync(c.ctx))
-    st = K.tc_stats(c.ctx)[1]
-    emit(dict(measurement="config5", agents=12, private_blocks=total, GiB=nbytes / 2 ** 30, record_bytes=c.rec,
-              link_d2h_GBps=d2h, link_h2d_GBps=h2d,
-              offload_GBps=nbytes / t_off / 1e9, upload_GBps=nbytes / t_up / 1e9,
-              offload_pct_link=100 * nbytes / t_off / 1e9 / d2h, upload_pct_link=100 * nbytes / t_up / 1e9 / h2d,
-              upload_ms_per_1k_tokens=t_up * 1e3 / (total * shape.block_size / 1024),
-              gather_TBps_overlapping_dma=2 * st.gather_bytes / (st.gather_ms * 1e-3) / 1e12,
-              scatter_TBps_overlapping_dma=2 * st.scatter_bytes / (st.scatter_ms * 1e-3) / 1e12))
-    c.close()
-
-
 def m_lds(torch, K, W, emit):
     n = 512 << 20
     a = torch.empty(n, dtype=torch.uint8, device="cuda:0")
@@ -592,14 +632,15 @@ def m_host(torch, K, W, emit):
     c.close()
 
 
-ALL = dict(sweep=m_sweep, naive=m_naive, config1=m_config1, config3=m_config3, config4=m_config4,
-           config4_replay=m_config4_replay, forecast_noise=m_forecast_noise, config5=m_config5, lds=m_lds, host=m_host)
+ALL = dict(hbm_limits=m_hbm_limits, contention=m_contention, dma_spread=m_dma_spread, sweep=m_sweep, naive=m_naive,
+           config4=m_config4, config4_replay=m_config4_replay, forecast_noise=m_forecast_noise, lds=m_lds, host=m_host)
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--only", default=",".join(ALL))
     ap.add_argument("--out", default=None)
+    ap.add_argument("--reps", type=int, default=0, help="repetitions for hbm_limits / dma_spread (0 = their defaults)")
     args = ap.parse_args()
     import torch
     if not torch.cuda.is_available():
@@ -614,7 +655,10 @@ def main():
         print(json.dumps(obj), flush=True)
 
     for name in args.only.split(","):
-        ALL[name](torch, K, W, emit)
+        if args.reps and name in ("hbm_limits", "dma_spread"):
+            ALL[name](torch, K, W, emit, reps=args.reps)
+        else:
+            ALL[name](torch, K, W, emit)
     if args.out:
         with open(args.out, "w") as f:
             json.dump(results, f, indent=1)

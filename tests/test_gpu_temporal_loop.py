@@ -1,6 +1,8 @@
 """The pieces around the copy path working together on the GPU: forecast (Eq. 1) -> hard rejections
-incl. ShouldOffload (Sec. 4.2, Alg. 1, with a cost model calibrated on this device, Eq. 2) -> offload -> gradual reservation
-(Eq. 4) with piecewise uploads -> lifecycle (Sec. 6.2) deciding resume / immediate upload.
+incl. ShouldOffload (Sec. 4.2, Alg. 1, with a cost model calibrated on this device, Eq. 2) -> offload -> one
+scheduling step of predictive upload at a time (Sec. 4.3: all candidates ranked by P_upload = I + U, the step's
+budget from Eq. 3 with critical demand and a shared pool, Eq. 4 in rank order) with piecewise uploads ->
+lifecycle (Sec. 6.2) deciding resume / immediate upload.
 
 Every decision the library takes is compared with the oracle's on the spot; every agent that went
 through a round trip must find its KV unchanged behind its rewritten block table.
@@ -42,7 +44,11 @@ def test_temporal_loop_on_a_seeded_trace():
         tables = torch.full((len(agents), 260), -1, dtype=torch.int32, device=DEV)
         torch.cuda.synchronize()       # torch wrote this on its own stream; the library's calls run on others
         A = [dict(req=K.tc_req_state(0, 0, 0, 0), model=(L.RUNNING, False, False)) for _ in agents]
-        counts = dict(approved=0, rejected=0, resumed_at_once=0, immediate=0, pieces=0)
+        counts = dict(approved=0, rejected=0, resumed_at_once=0, immediate=0, pieces=0, steps=0, steps_with_several=0,
+                      steps_budget_binds=0, steps_rank_differs_from_listing=0)
+        rng_step = W.rng_for(3, salt=22)                             # draws of the scheduling steps only
+        importance = rng_step.uniform(0.0, 1.0, size=len(agents))   # I: what the spatial scheduler would say
+        step_pending = [False]
 
         heap = [(t * 1e3, k, kind, i) for k, (t, _, kind, i) in enumerate(events) if kind != "upload_due"]
         heapq.heapify(heap)
@@ -69,30 +75,63 @@ def test_temporal_loop_on_a_seeded_trace():
             K.check(K.tc_sync(gp.ctx))
             pool_model.retire_all()
 
-        def upload_piece(i, t, everything):
-            """One scheduling step of the gradual upload of agent i."""
+        def issue_piece(i, t, piece):
+            """`piece` more blocks of agent i come back: a contiguous run of its records."""
             a = A[i]
             if a["req"].state == L.OFFLOADED:
                 assert lifecycle(i, L.UPLOAD_ISSUED) == L.NONE
             n, done = agents[i]["blocks"], a["done"]
-            sync()
-            budget = K.tc_upload_budget(pool_model.n_free(), 0, 0)
-            assert budget == policy.upload_budget(pool_model.n_free(), 0, 0)
-            piece = K.tc_gradual_reserve(budget, n - done, budget)
-            assert piece == policy.gradual_reserve(budget, n - done, budget)
-            if everything:
-                piece = n - done                         # the tool is back: no more waiting
             ids = alloc(piece)
             K.check(K.tc_upload(gp.ctx, a["buf"] + done * rec, ids, tables[i].data_ptr() + 4 * done, stream))
             pool_model.begin_op(ids.tolist())
             a["new"][done:done + piece] = ids
             a["done"] = done + piece
             counts["pieces"] += 1
-            if a["done"] < n:
-                push(t + step_ms, "reserve", i)
-            else:
+            if a["done"] == n:
+                a["due"] = False
                 K.check(K.tc_host_free(gp.ctx, a["buf"]))
                 push(t + 0.001, "upload_done", i)
+
+        def upload_rest(i, t):
+            """The tool is back: no more waiting, everything that is still missing comes at once."""
+            sync()
+            issue_piece(i, t, agents[i]["blocks"] - A[i]["done"])
+
+        def scheduling_step(t):
+            """Sec. 4.3: every candidate whose upload is due, ranked and served within this step's budget."""
+            sync()
+            cand_ids = [j for j, b in enumerate(A) if b.get("due") and not b["req"].finish_seen
+                        and b["req"].state in (L.OFFLOADED, L.PENDING_UPLOAD) and b["done"] < agents[j]["blocks"]]
+            if not cand_ids:
+                return False
+            # urgency: how close the predicted end of the call is, 0 (far) .. 1 (now or past)
+            cands = []
+            for j in cand_ids:
+                b = A[j]
+                urgency = min(1.0, max(0.0, 1.0 - (b["t_call"] + b["t_fc"] - t) / max(b["t_fc"], 1.0)))
+                cands.append((float(importance[j]), urgency, agents[j]["blocks"] - b["done"]))
+            # critical demand: none, nearly everything that is free (Eq. 3 leaves a small budget), or anything
+            gpu_free, shared_free = pool_model.n_free(), int(rng_step.integers(0, 400))
+            kind_of_step = int(rng_step.integers(0, 3))
+            if kind_of_step == 0:
+                d_critical = 0
+            elif kind_of_step == 1:
+                d_critical = max(0, gpu_free + shared_free - int(rng_step.integers(0, 64)))
+            else:
+                d_critical = int(rng_step.integers(0, gpu_free + shared_free + 1))
+            rc, order, reserve = K.tc_upload_plan(cands, gpu_free, d_critical, shared_free)
+            want_order, want_reserve = policy.upload_plan(cands, gpu_free, d_critical, shared_free)
+            assert rc == 0 and order == want_order and reserve == want_reserve
+            budget = K.tc_upload_budget(gpu_free, d_critical, shared_free)
+            assert budget == policy.upload_budget(gpu_free, d_critical, shared_free) and sum(reserve) <= budget
+            counts["steps"] += 1
+            counts["steps_with_several"] += len(cands) > 1
+            counts["steps_budget_binds"] += sum(reserve) < sum(-(-c[2] // 2) for c in cands)
+            counts["steps_rank_differs_from_listing"] += order != sorted(order)
+            for k in order:
+                if reserve[k]:
+                    issue_piece(cand_ids[k], t, reserve[k])
+            return True
 
         def verify_and_resume(i):
             a, n = A[i], agents[i]["blocks"]
@@ -102,7 +141,7 @@ def test_temporal_loop_on_a_seeded_trace():
 
         while heap:
             t, _, kind, i = heapq.heappop(heap)
-            a, n = A[i], agents[i]["blocks"]
+            a, n = (A[i], agents[i]["blocks"]) if i >= 0 else (None, 0)
             ftype = i % 4
             user = 2000.0 if ftype < 2 else None
             if kind == "start":
@@ -126,7 +165,8 @@ def test_temporal_loop_on_a_seeded_trace():
                     counts["rejected"] += 1
                     continue
                 counts["approved"] += 1
-                a.update(sig=gp.block_checksums(a["ids"]), buf=buf, done=0, new=np.full(n, -1, dtype=np.int32))
+                a.update(sig=gp.block_checksums(a["ids"]), buf=buf, done=0, new=np.full(n, -1, dtype=np.int32), t_fc=t_fc,
+                         due=False)
                 K.check(K.tc_offload(gp.ctx, a["ids"], buf, stream))
                 pool_model.begin_op(a["ids"].tolist())
                 K.check(K.tc_free(gp.ctx, a["ids"]))
@@ -138,13 +178,19 @@ def test_temporal_loop_on_a_seeded_trace():
                 sync()
                 if lifecycle(i, L.OFFLOAD_DONE) == L.UPLOAD_NOW:
                     counts["immediate"] += 1
-                    upload_piece(i, t, everything=True)
-            elif kind in ("upload_due", "reserve"):
-                if a["req"].state == L.OFFLOADED and not a["req"].finish_seen or \
-                        (kind == "reserve" and a["req"].state == L.PENDING_UPLOAD and a["done"] < n):
-                    upload_piece(i, t, everything=bool(a["req"].finish_seen))
-                elif a["req"].state == L.PENDING_OFFLOAD and kind == "upload_due":
-                    push(t + step_ms, "upload_due", i)       # the offload itself is not through yet
+                    upload_rest(i, t)
+            elif kind == "upload_due":
+                if a["req"].state in (L.OFFLOADED, L.PENDING_OFFLOAD) and not a["req"].finish_seen:
+                    a["due"] = True                       # a candidate from now on (once its offload is through)
+                    if not step_pending[0]:
+                        step_pending[0] = True
+                        push(t, "step", -1)
+            elif kind == "step":
+                step_pending[0] = False
+                scheduling_step(t)
+                if any(b.get("due") for b in A):
+                    step_pending[0] = True
+                    push(t + step_ms, "step", -1)
             elif kind == "upload_done":
                 sync()
                 a["ids"] = a["new"].copy()
@@ -161,7 +207,11 @@ def test_temporal_loop_on_a_seeded_trace():
                         verify_and_resume(i)
                 elif act == L.UPLOAD_NOW:
                     counts["immediate"] += 1
-                    upload_piece(i, t, everything=True)
+                    a["due"] = False
+                    upload_rest(i, t)
+                elif a["req"].state == L.PENDING_UPLOAD and a.get("done", 0) < n:
+                    a["due"] = False                      # pieces are in flight and the tool is back: the rest, now
+                    upload_rest(i, t)
                 # WAIT: a copy is in flight; its completion event takes it from here
             elif kind == "finish":
                 if a["req"].state != L.RUNNING:            # still coming back: finish once it has resumed
@@ -175,6 +225,10 @@ def test_temporal_loop_on_a_seeded_trace():
         assert counts["approved"] > 5 and counts["rejected"] > 0, counts
         assert counts["resumed_at_once"] > 0 and counts["immediate"] > 0, counts
         assert counts["pieces"] > counts["approved"], counts       # uploads really came in pieces
+        # Eq. 3 with a binding critical demand, and rankings over several candidates that differ from the order
+        # they were listed in, both occurred
+        assert counts["steps_with_several"] > 3 and counts["steps_budget_binds"] > 3, counts
+        assert counts["steps_rank_differs_from_listing"] > 0, counts
         K.tc_forecaster_destroy(fc)
     finally:
         gp.close()
