@@ -72,10 +72,18 @@ class OracleIdRing:
         return out
 
 
-def plan_chunks(total, slot_blocks, upload):
-    """Sizes, in blocks, of the staging chunks a list of `total` records is cut into."""
-    sizes = []
+def plan_chunks(total, slot_blocks, upload, head_blocks=0):
+    """Sizes, in blocks, of the staging chunks a list of `total` records is cut into: full slots, then what is
+    left.  With head_blocks > 0 a list of more than twice that many records starts with a short chunk of
+    head_blocks records (at most a slot): while it crosses the link the copy kernel is already at work on the
+    next one, so only a short kernel runs with the link idle.  An upload takes the same sizes in reverse order:
+    its last kernel, the one nothing hides, is the short one."""
     left = int(total)
+    sizes = []
+    head = min(int(head_blocks), int(slot_blocks))
+    if head > 0 and left > 2 * head:
+        sizes.append(head)
+        left -= head
     while left > 0:
         take = min(int(slot_blocks), left)
         sizes.append(take)
@@ -139,10 +147,18 @@ def upload_path(mode):
     return STAGED if mode == PATH_STAGED else DIRECT
 
 
-def tail_divisor(option, n_chunks, auto_div=64):
-    """option 0 = automatic (a tail only when the transfer has more than one chunk), 1 = never, N >= 2 = 1/N."""
+def kernels_overlap_copies(option, n_chunks):
+    """Whether a staged transfer runs its copy kernels on the engine's own stream, so that the kernel of one chunk
+    overlaps with the link copy of its neighbour: option 0 = automatic (transfers of more than one chunk: a single
+    chunk has nothing to overlap with, and the hop between streams would only delay it), 1 = never."""
+    return option == 0 and n_chunks > 1
+
+
+def tail_divisor(option, n_chunks, overlapped=False, auto_div=64):
+    """option 0 = automatic, 1 = never, N >= 2 = 1/N.  Automatic: a tail where the link would otherwise idle once
+    per chunk, i.e. in transfers of more than one chunk whose kernels run in line with their copies."""
     if option == 0:
-        return auto_div if n_chunks > 1 else 0
+        return auto_div if (n_chunks > 1 and not overlapped) else 0
     return 0 if option == 1 else option
 
 

@@ -106,7 +106,13 @@ CASES = {
         "a large offload goes direct": ("return DIRECT if (upload_in_flight or total_bytes < auto_direct_bytes) else STAGED", "return DIRECT if (upload_in_flight or total_bytes >= auto_direct_bytes) else STAGED"),
         "duplex is ignored": ("return DIRECT if (upload_in_flight or total_bytes < auto_direct_bytes) else STAGED", "return DIRECT if total_bytes < auto_direct_bytes else STAGED"),
         "uploads are staged unless forced": ("return STAGED if mode == PATH_STAGED else DIRECT", "return DIRECT if mode == PATH_DIRECT else STAGED"),
-        "a single chunk gets a tail": ("return auto_div if n_chunks > 1 else 0", "return auto_div"),
+        "a single chunk gets a tail": ("return auto_div if (n_chunks > 1 and not overlapped) else 0", "return auto_div if not overlapped else 0"),
+        "overlapped transfers get a tail too": ("return auto_div if (n_chunks > 1 and not overlapped) else 0", "return auto_div if n_chunks > 1 else 0"),
+        "a single chunk hops between streams": ("return option == 0 and n_chunks > 1", "return option == 0"),
+        "overlap cannot be switched off": ("return option == 0 and n_chunks > 1", "return n_chunks > 1"),
+        "short lists get a head too": ("if head > 0 and left > 2 * head:", "if head > 0 and left > head:"),
+        "a head may be longer than a slot": ("head = min(int(head_blocks), int(slot_blocks))", "head = int(head_blocks)"),
+        "the head is not taken off the list": ("        sizes.append(head)\n        left -= head\n", "        sizes.append(head)\n"),
         "a failed transfer gives its span back": ("        op.update(ticket=self.next_ticket, failed=failed)\n", "        op.update(ticket=self.next_ticket, failed=failed)\n        if failed:\n            self.ring.cancel_newest()\n"),
     },
 }

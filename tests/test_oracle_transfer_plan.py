@@ -74,10 +74,30 @@ def test_chunks_hand_worked():
                 sizes = T.plan_chunks(total, slot, up)
                 assert sum(sizes) == total and all(0 < s <= slot for s in sizes)
                 assert len(sizes) == -(-total // slot)
-    # both directions cut the record list at the same places
+    # the two directions cut the record list at mirrored places
     cuts = lambda sizes: set(np.cumsum(sizes).tolist())
     assert cuts(T.plan_chunks(10, 4, False)) != cuts(T.plan_chunks(10, 4, True))   # 4,8,10 against 2,6,10: mirrored
     assert cuts(T.plan_chunks(10, 4, False)) == {10 - c for c in cuts(T.plan_chunks(10, 4, True)) if c != 10} | {10}
+
+
+def test_chunks_with_a_short_first_chunk():
+    # hand-worked: 2 records ahead of full slots of 4; nothing changes for lists of at most twice the head
+    assert T.plan_chunks(10, 4, False, 2) == [2, 4, 4] and T.plan_chunks(10, 4, True, 2) == [4, 4, 2]
+    assert T.plan_chunks(11, 4, False, 2) == [2, 4, 4, 1] and T.plan_chunks(11, 4, True, 2) == [1, 4, 4, 2]
+    assert T.plan_chunks(4, 4, False, 2) == [4] and T.plan_chunks(5, 4, False, 2) == [2, 3]
+    assert T.plan_chunks(3, 8, False, 1) == [1, 2] and T.plan_chunks(2, 8, False, 1) == [2]
+    assert T.plan_chunks(20, 4, False, 6) == [4, 4, 4, 4, 4]            # a head is never longer than a slot
+    assert T.plan_chunks(9, 4, False, 0) == [4, 4, 1]
+    for total in range(0, 60):
+        for slot in (1, 3, 8):
+            for head in (0, 1, 2, 5, 9):
+                off, up = T.plan_chunks(total, slot, False, head), T.plan_chunks(total, slot, True, head)
+                assert up == off[::-1] and sum(off) == total and all(0 < s <= slot for s in off)
+                h = min(head, slot)
+                if h and total > 2 * h:
+                    assert off[0] == h and off[1:] == T.plan_chunks(total - h, slot, False)
+                else:
+                    assert off == T.plan_chunks(total, slot, False)
 
 
 def test_pieces_carry_every_record_once():
@@ -172,6 +192,11 @@ def test_paths_truth_table():
     assert T.offload_path(T.PATH_AUTO, 1 << 40, True, 128 * MiB) == T.DIRECT
     assert T.tail_divisor(0, 1) == 0 and T.tail_divisor(0, 2) == 64 and T.tail_divisor(0, 9, auto_div=32) == 32
     assert T.tail_divisor(1, 5) == 0 and T.tail_divisor(48, 1) == 48 and T.tail_divisor(2, 3) == 2
+    # kernels on their own stream already keep the link busy: no automatic tail then, an explicit one stays
+    assert T.tail_divisor(0, 2, overlapped=True) == 0 and T.tail_divisor(0, 9, True) == 0
+    assert T.tail_divisor(16, 2, overlapped=True) == 16 and T.tail_divisor(1, 2, True) == 0
+    assert [T.kernels_overlap_copies(0, n) for n in (1, 2, 7)] == [False, True, True]
+    assert [T.kernels_overlap_copies(1, n) for n in (1, 2, 7)] == [False, False, False]
 
 
 # ---------------------------------------------------------------- what a failed enqueue keeps
