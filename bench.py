@@ -648,7 +648,11 @@ def main():
         if not launches:
             return None
         avg_ms = ms / launches
-        traffic = measured.get(name) if measured.get("record_bytes_per_launch") == nbytes // launches else None
+        # measured per transfer of this size (all launches of the transfer together), spread over its launches
+        per_transfer = measured.get("launches_per_transfer", {}).get(name)
+        traffic = None
+        if per_transfer and measured.get("record_bytes_per_transfer") == nbytes // launches * per_transfer:
+            traffic = int(round(measured[name] / per_transfer))
         achieved = 2.0 * nbytes / launches / (avg_ms * 1e-3) / 1e9   # read + write per payload byte
         return {"kernel": name, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
@@ -658,7 +662,8 @@ def main():
 
     # the two-stage path forced in both directions, same agent, same launch configuration, after the timed steps
     staged, st2 = variant(torch, K, pool, shape, pairs, link,
-                          "direct_offload = direct_upload = TC_PATH_STAGED, no host tail: gather_pages -> DMA, DMA -> scatter_pages",
+                          "direct_offload = direct_upload = TC_PATH_STAGED: gather_pages -> DMA, DMA -> scatter_pages; a short first chunk "
+                          "(32 MiB), then the rest, the copy kernels on the context's own stream under the DMA of the neighbouring chunk",
                           steps=12, direct_offload=K.TC_PATH_STAGED, direct_upload=K.TC_PATH_STAGED, host_tail_div=1)
     # `roofline`: the HBM-bound kernel of the timed steps.  With the default paths that is gather_pages; the upload's
     # scatter reads pinned memory and is bound by the host link (it runs at the link rate, see pct_of_pinned_link).
@@ -677,7 +682,8 @@ def main():
                                "(2 MiB/block), 16384-block pool (32 GiB), one agent, "
                                f"{args.tokens} tokens = {n} blocks scattered uniformly",
                    "payload_bytes_each_way": payload, "tokens": n * shape.block_size,
-                   "paths": "library defaults: offload staged (gather_pages + D2H DMA), upload direct (scatter_pages reads pinned memory, 16 workgroups)"},
+                   "paths": "library defaults: offload staged (gather_pages + D2H DMA in two chunks, 32 MiB + the rest, the second "
+                            "gather under the first DMA), upload direct (scatter_pages reads pinned memory, 16 workgroups)"},
         **rates(payload, off_ms, up_ms, link, n * shape.block_size),
         "pinned_link_GBps": {k: round(v, 3) for k, v in link.items()},
         "roofline": dominant, "roofline_other_kernels": [r for r in others if r],
@@ -690,10 +696,14 @@ def main():
     out["direct_paths"] = variant(torch, K, pool, shape, pairs, link,
                                   "direct_offload = direct_upload = TC_PATH_DIRECT (6 / 16 workgroups): no staging, no DMA",
                                   direct_offload=K.TC_PATH_DIRECT, direct_upload=K.TC_PATH_DIRECT)[0]
+    out["staged_in_line"] = variant(torch, K, pool, shape, pairs, link,
+                                    "two-stage path with inline_kernels = 1: one chunk, kernel and DMA in line on the caller's "
+                                    "stream (no short first chunk, no overlap)",
+                                    direct_offload=K.TC_PATH_STAGED, direct_upload=K.TC_PATH_STAGED, host_tail_div=1, inline_kernels=1)[0]
     out["host_tail"] = variant(torch, K, pool, shape, pairs, link,
-                               "staged both ways with host_tail_div = 64: the last 1/64 of the chunk crosses the link inside "
+                               "in line as above, with host_tail_div = 64: the last 1/64 of the chunk crosses the link inside "
                                "the copy launch; the launches get longer, the transfer shorter",
-                               direct_offload=K.TC_PATH_STAGED, direct_upload=K.TC_PATH_STAGED, host_tail_div=64)[0]
+                               direct_offload=K.TC_PATH_STAGED, direct_upload=K.TC_PATH_STAGED, host_tail_div=64, inline_kernels=1)[0]
     if not args.no_configs:
         cfgs = {"1": config1(torch, K, W, link), "3": config3(torch, K, W, link, pool)}
         del pool

@@ -100,11 +100,19 @@ typedef struct {
                                    workgroups of the same copy launch straight to / from the pinned buffer,
                                    using the link while it would otherwise wait for the kernel, and the DMA
                                    carries that much less.  0 = automatic (N = 64 for transfers of more than
-                                   one chunk, none otherwise), 1 = never, N >= 2 = that N.  Applies to chunks
-                                   of at least N blocks whose tail lies in one host buffer.               */
+                                   one chunk whose kernels run in line with their DMAs, see inline_kernels;
+                                   none otherwise), 1 = never, N >= 2 = that N.  Applies to chunks of at
+                                   least N blocks whose tail lies in one host buffer.                      */
     uint64_t auto_direct_bytes; /* TC_PATH_AUTO: offloads below this many record bytes go direct as well (one
                                    kernel instead of kernel + DMA saves ~19 us on an otherwise idle GPU; next to
                                    memory-bound kernels the staged path is the faster one); 0 = no such rule   */
+    uint32_t inline_kernels;    /* staged path: 0 = a transfer of more than one chunk runs its copy kernels on a
+                                   stream of the context's own, ordered with the caller's stream by events both
+                                   ways, so that the kernel of one chunk runs under the DMA of its neighbour; such
+                                   a transfer starts with a short chunk of 32 MiB (ends with it, for an upload).
+                                   Every DMA, the table rewrite and completion stay on the caller's stream.
+                                   1 = everything in line on the caller's stream                               */
+    uint32_t reserved0;         /* must be 0 */
 } tc_opts;
 
 typedef struct {
@@ -131,6 +139,7 @@ typedef struct {
     uint64_t d2h_bytes, h2d_bytes;
     double d2h_ms, h2d_ms;                    /* event pairs on the stream around each chunk's DMAs */
     uint64_t transfers_failed;                /* transfer calls that returned TC_ERR_HIP after validation */
+    uint64_t transfers_overlapped;            /* staged transfers whose kernels ran on the context's own stream */
 } tc_stats_t;
 
 /* ---- life cycle ------------------------------------------------------------------------- */

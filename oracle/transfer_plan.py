@@ -154,6 +154,15 @@ def kernels_overlap_copies(option, n_chunks):
     return option == 0 and n_chunks > 1
 
 
+def plan_staged(total, slot_blocks, upload, head_blocks, overlap_option):
+    """(chunk sizes, whether the kernels overlap with the copies) of a staged transfer: the cut with a short first
+    chunk if that yields something to overlap, else the plain cut with everything in line."""
+    sizes = plan_chunks(total, slot_blocks, upload, head_blocks)
+    if kernels_overlap_copies(overlap_option, len(sizes)):
+        return sizes, True
+    return plan_chunks(total, slot_blocks, upload, 0), False
+
+
 def tail_divisor(option, n_chunks, overlapped=False, auto_div=64):
     """option 0 = automatic, 1 = never, N >= 2 = 1/N.  Automatic: a tail where the link would otherwise idle once
     per chunk, i.e. in transfers of more than one chunk whose kernels run in line with their copies."""

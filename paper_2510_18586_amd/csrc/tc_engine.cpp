@@ -132,8 +132,11 @@ namespace {
 void destroy_unlocked(tc_ctx *c)
 {
     auto &e = c->e;
-    for (auto &s : e.slots)
+    for (auto &s : e.slots) {
         if (s.last) (void)hipEventDestroy(s.last);
+        if (s.ready) (void)hipEventDestroy(s.ready);
+    }
+    if (e.has_kstream) (void)hipStreamDestroy(e.kstream);
     for (hipEvent_t ev : e.sync_events) (void)hipEventDestroy(ev);
     for (hipEvent_t ev : e.time_events) (void)hipEventDestroy(ev);
     if (c->staging) (void)hipFree(c->staging);
@@ -165,7 +168,7 @@ try {
     const uint32_t P = 2 * pool->num_layers;
     const uint32_t S = pool->scales_per_block;
     if (opts && (opts->direct_offload > tc::kPathStaged || opts->direct_upload > tc::kPathStaged ||
-                 opts->direct_upload == tc::kPathDirectIfDuplex))
+                 opts->direct_upload == tc::kPathDirectIfDuplex || opts->inline_kernels > 1 || opts->reserved0 != 0))
         return TC_ERR_INVAL;
     HipDev probe;
     if (!probe.is_device_ptr(pool->kv_base) || (S && !probe.is_device_ptr(pool->scales))) return TC_ERR_NOT_PINNED;
@@ -216,6 +219,12 @@ try {
     for (uint32_t i = 0; i < n_slots; ++i) {
         e.slots[i].buf = c->staging + uint64_t(i) * slot_bytes;
         HIP_OR_FAIL(hipEventCreateWithFlags(&e.slots[i].last, hipEventDisableTiming));
+        HIP_OR_FAIL(hipEventCreateWithFlags(&e.slots[i].ready, hipEventDisableTiming));
+    }
+    // the engine's own stream for the copy kernels of multi-chunk transfers; default priority, like every stream here
+    if (e.opts.inline_kernels == 0) {
+        HIP_OR_FAIL(hipStreamCreateWithFlags(&e.kstream, hipStreamNonBlocking));
+        e.has_kstream = true;
     }
     // Touch what the first transfers will touch, once, here: the runtime maps pinned pages for the
     // copy engines lazily, and a first DMA into fresh arena pages was seen to take up to three times

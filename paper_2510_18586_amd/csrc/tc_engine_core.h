@@ -3,16 +3,22 @@
 // in CPU tests against a recording device.  The library instantiates it with the HIP runtime (tc_engine.cpp).
 //
 // Offload (paper Sec. 4.1 / 6.3: a stalled agent's KV is copied to CPU memory asynchronously on a
-// dedicated stream) runs in two stages per staging chunk, all on the caller's stream:
+// dedicated stream) runs in two stages per staging chunk:
 //     gather_pages  ->  one contiguous D2H DMA per agent segment of the chunk
 // Upload is the mirror image:
 //     H2D DMA  ->  scatter_pages  (... last chunk)  ->  rewrite_table
 // or, on the direct paths, one copy kernel per agent that writes / reads the pinned host buffer itself.
-// The stream is the paper's dedicated copy stream; kernels of other streams overlap freely.  The
-// gather is ~50x faster than the host link, so running it in line with the DMAs costs under 2 %;
-// a second, private DMA stream (gather of chunk c+1 under the DMA of chunk c) was measured and
-// dropped: with two copies queued across streams the runtime at random ran the DMAs at half rate.
-// A slot's `last` event orders its reuse when callers bring different streams.  The block
+// The caller's stream is the paper's dedicated copy stream: it carries every DMA, the table rewrite and the
+// completion event; kernels of other streams overlap freely.  A staged transfer of a single chunk runs its
+// kernel on that stream too.  One of several chunks puts its copy kernels on the engine's own stream, tied to
+// the caller's by events in both directions:
+//     offload   caller: ids, entry event ............ wait ready[c], DMA c, record last[c] ...... done
+//               engine: wait entry; per chunk c: wait last[slot], gather c, record ready[c]
+//     upload    caller: ids; per chunk c: wait last[slot], DMA c, record ready[c] .... wait last[final], tables, done
+//               engine: per chunk c: wait ready[c], scatter c, record last[c]
+// so the kernel of one chunk runs under the link copy of its neighbour, every DMA of a transfer stays on one
+// stream, in order, and the completion event on the caller's stream covers everything.  `last` of a slot is its
+// last consumer's event whoever that was; it orders the slot's reuse across transfers and streams.  The block
 // bookkeeping (tc_blocks.h) is updated under the context's mutex; a transfer holds its blocks "in
 // flight" until poll / sync see its completion event.
 //
@@ -55,7 +61,8 @@ public:
 
     struct Slot {
         char *buf = nullptr;
-        Event last{};  // last consumer finished: the slot may be overwritten
+        Event last{};   // last consumer finished: the slot may be overwritten
+        Event ready{};  // the slot's producer finished (transfers whose kernels run on the engine's stream)
         bool used = false;
     };
     struct Timed {
@@ -65,6 +72,8 @@ public:
     };
     struct OpPayload {
         Event done{};
+        Event entry{};           // ties the engine's stream to the caller's (overlapped transfers only)
+        bool overlapped = false;
         std::vector<Timed> timed;
     };
     using Book = TransferBook<OpPayload>;
@@ -80,6 +89,8 @@ public:
     char *arena_base = nullptr;
     uint64_t arena_bytes = 0;
     uint32_t slot_blocks = 0;
+    Stream kstream{};             // the engine's own stream for copy kernels; valid if has_kstream
+    bool has_kstream = false;
     std::vector<Slot> slots;
     uint32_t next_slot = 0;
     int32_t *ids_host = nullptr;  // pinned ring
@@ -124,6 +135,7 @@ public:
             put_event(true, t.t1);
         }
         put_event(false, op.payload.done);
+        if (op.payload.overlapped) put_event(false, op.payload.entry);
         book->pop_front();
     }
 
@@ -255,15 +267,21 @@ public:
     // Enqueueing failed after begin_op: work already on the stream (the id copy at least, perhaps kernels and
     // DMAs) may still read the id span, the blocks and the host buffers.  If a completion event can still be
     // recorded, the transfer is kept in flight, marked failed, and everything it holds is released when it
-    // retires.  Otherwise the stream is drained here, after which nothing of it can run, and all is rolled back.
+    // retires.  Otherwise the streams are drained here, after which nothing of it can run, and all is rolled back.
+    // Kernels of an overlapped transfer may sit on the engine's stream with nothing on the caller's stream
+    // waiting for them yet: the caller's stream is made to, before its completion event means anything.
     int fail_op(Entry &&op, Stream stream, int rc)
     {
         st.transfers_failed++;
-        if (dev.event_record(op.payload.done, stream) == 0) {
+        bool covered = true;
+        if (op.payload.overlapped)
+            covered = dev.event_record(op.payload.entry, kstream) == 0 && dev.stream_wait(stream, op.payload.entry) == 0;
+        if (covered && dev.event_record(op.payload.done, stream) == 0) {
             op.failed = true;
             book->publish(std::move(op));
             return rc;
         }
+        if (op.payload.overlapped) (void)dev.stream_sync(kstream);
         (void)dev.stream_sync(stream);
         blocks->end_transfer(op.ids.data(), uint32_t(op.ids.size()));
         for (uint64_t s : op.arena_starts) arena->end_transfer(s);
@@ -273,6 +291,7 @@ public:
             put_event(true, t.t1);
         }
         put_event(false, op.payload.done);
+        if (op.payload.overlapped) put_event(false, op.payload.entry);
         return rc;
     }
 
@@ -374,20 +393,34 @@ public:
             return TC_OK;
         };
         auto enqueue = [&]() -> int {
-            const std::vector<uint32_t> chunks = plan_chunks(plan.total, slot_blocks, false);
-            const uint32_t div = tail_divisor(opts.host_tail_div, chunks.size());
+            bool overlapped = false;
+            const std::vector<uint32_t> chunks =
+                plan_staged(plan.total, slot_blocks, false, head_blocks_of(rec), has_kstream ? opts.inline_kernels : 1, &overlapped);
+            const uint32_t div = tail_divisor(opts.host_tail_div, chunks.size(), overlapped);
+            const Stream ks = overlapped ? kstream : stream;
+            if (overlapped) {
+                // the engine's stream starts after the ids are in place and after whatever begin_op waited for
+                TC_RC(get_event(false, &op.payload.entry));
+                op.payload.overlapped = true;
+                TC_DEV(dev.event_record(op.payload.entry, stream));
+                TC_DEV(dev.stream_wait(kstream, op.payload.entry));
+            }
             uint64_t c0 = 0;
             for (uint32_t nblk : chunks) {
                 Slot *slot = &slots[next_slot];
                 next_slot = (next_slot + 1) % uint32_t(slots.size());
-                if (slot->used) TC_DEV(dev.stream_wait(stream, slot->last));
+                if (slot->used) TC_DEV(dev.stream_wait(ks, slot->last));
                 void *host_part = nullptr;
                 const uint32_t split = host_tail(plan, div, c0, nblk, &host_part);
-                TC_RC(time_begin(&op, stream, uint64_t(nblk) * rec, kGather));
+                TC_RC(time_begin(&op, ks, uint64_t(nblk) * rec, kGather));
                 TC_DEV(dev.gather(pool.kv_base, static_cast<const uint32_t *>(pool.scales), slot->buf,
-                                  ids_dev + ring_start + c0, nblk, geom, opts.max_grid, false, stream, host_part, split,
+                                  ids_dev + ring_start + c0, nblk, geom, opts.max_grid, false, ks, host_part, split,
                                   opts.direct_grid ? opts.direct_grid : kDefaultDirectGatherGrid));
-                TC_RC(time_end(&op, stream));
+                TC_RC(time_end(&op, ks));
+                if (overlapped) {
+                    TC_DEV(dev.event_record(slot->ready, kstream));
+                    TC_DEV(dev.stream_wait(stream, slot->ready));
+                }
                 TC_RC(time_begin(&op, stream, uint64_t(split) * rec, kD2H));
                 TC_RC(dma_chunk(plan, c0, c0 + split, slot->buf, true, stream));
                 TC_RC(time_end(&op, stream));
@@ -396,6 +429,7 @@ public:
                 c0 += nblk;
             }
             TC_DEV(dev.event_record(op.payload.done, stream));
+            if (overlapped) st.transfers_overlapped++;
             return TC_OK;
         };
         const uint64_t total = op.ids.size();
@@ -449,8 +483,16 @@ public:
             return rewrite_tables();
         };
         auto enqueue = [&]() -> int {
-            const std::vector<uint32_t> chunks = plan_chunks(plan.total, slot_blocks, true);
-            const uint32_t div = tail_divisor(opts.host_tail_div, chunks.size());
+            bool overlapped = false;
+            const std::vector<uint32_t> chunks =
+                plan_staged(plan.total, slot_blocks, true, head_blocks_of(rec), has_kstream ? opts.inline_kernels : 1, &overlapped);
+            const uint32_t div = tail_divisor(opts.host_tail_div, chunks.size(), overlapped);
+            const Stream ks = overlapped ? kstream : stream;
+            if (overlapped) {
+                TC_RC(get_event(false, &op.payload.entry));   // only a failed enqueue records it (fail_op)
+                op.payload.overlapped = true;
+            }
+            Slot *final_slot = nullptr;
             uint64_t c0 = 0;
             for (uint32_t nblk : chunks) {
                 Slot *slot = &slots[next_slot];
@@ -461,15 +503,24 @@ public:
                 TC_RC(time_begin(&op, stream, uint64_t(split) * rec, kH2D));
                 TC_RC(dma_chunk(plan, c0, c0 + split, slot->buf, false, stream));
                 TC_RC(time_end(&op, stream));
-                TC_RC(time_begin(&op, stream, uint64_t(nblk) * rec, kScatter));
+                if (overlapped) {
+                    // the scatter also needs the ids and whatever begin_op waited for: both precede this event
+                    TC_DEV(dev.event_record(slot->ready, stream));
+                    TC_DEV(dev.stream_wait(kstream, slot->ready));
+                }
+                TC_RC(time_begin(&op, ks, uint64_t(nblk) * rec, kScatter));
                 TC_DEV(dev.scatter(slot->buf, pool.kv_base, static_cast<uint32_t *>(pool.scales),
-                                   ids_dev + ring_start + c0, nblk, geom, opts.max_grid, false, stream, host_part, split,
+                                   ids_dev + ring_start + c0, nblk, geom, opts.max_grid, false, ks, host_part, split,
                                    opts.direct_grid ? opts.direct_grid : kDefaultTailScatterGrid));
-                TC_RC(time_end(&op, stream));
-                TC_DEV(dev.event_record(slot->last, stream));
+                TC_RC(time_end(&op, ks));
+                TC_DEV(dev.event_record(slot->last, ks));
                 slot->used = true;
+                final_slot = slot;
                 c0 += nblk;
             }
+            // the engine's stream runs in order: its last scatter is done when all are
+            if (overlapped && final_slot) TC_DEV(dev.stream_wait(stream, final_slot->last));
+            if (overlapped) st.transfers_overlapped++;
             return rewrite_tables();
         };
         const uint64_t total = op.ids.size();

@@ -73,9 +73,9 @@ uint64_t tcp_book_retire(void *bp)
 }
 uint64_t tcp_book_ring_used(void *bp) { return static_cast<Book *>(bp)->ring().used(); }
 int tcp_book_upload_in_flight(void *bp) { return static_cast<Book *>(bp)->upload_in_flight() ? 1 : 0; }
-uint32_t tcp_plan_chunks(uint64_t total, uint32_t slot_blocks, int upload, uint32_t *out, uint32_t room)
+uint32_t tcp_plan_chunks(uint64_t total, uint32_t slot_blocks, int upload, uint32_t head_blocks, uint32_t *out, uint32_t room)
 {
-    const std::vector<uint32_t> v = tc::plan_chunks(total, slot_blocks, upload != 0);
+    const std::vector<uint32_t> v = tc::plan_chunks(total, slot_blocks, upload != 0, head_blocks);
     for (size_t i = 0; i < v.size() && i < room; ++i) out[i] = v[i];
     return uint32_t(v.size());
 }
@@ -104,7 +104,17 @@ int tcp_offload_direct(uint32_t mode, uint64_t bytes, int upload_in_flight, uint
     return tc::offload_goes_direct(mode, bytes, upload_in_flight != 0, auto_bytes) ? 1 : 0;
 }
 int tcp_upload_direct(uint32_t mode) { return tc::upload_goes_direct(mode) ? 1 : 0; }
-uint32_t tcp_tail_divisor(uint32_t option, uint64_t n_chunks) { return tc::tail_divisor(option, size_t(n_chunks)); }
+uint32_t tcp_tail_divisor(uint32_t option, uint64_t n_chunks, int overlapped) { return tc::tail_divisor(option, size_t(n_chunks), overlapped != 0); }
+uint32_t tcp_plan_staged(uint64_t total, uint32_t slot_blocks, int upload, uint32_t head_blocks, uint32_t option, int *overlapped,
+                         uint32_t *out, uint32_t room)
+{
+    bool ov = false;
+    const std::vector<uint32_t> v = tc::plan_staged(total, slot_blocks, upload != 0, head_blocks, option, &ov);
+    *overlapped = ov ? 1 : 0;
+    for (size_t i = 0; i < v.size() && i < room; ++i) out[i] = v[i];
+    return uint32_t(v.size());
+}
+int tcp_kernels_overlap(uint32_t option, uint64_t n_chunks) { return tc::kernels_overlap_copies(option, size_t(n_chunks)) ? 1 : 0; }
 
 void *tcb_arena_new(uint64_t slots) { return new tc::HostArena(slots); }
 void tcb_arena_del(void *a) { delete static_cast<tc::HostArena *>(a); }

@@ -1,6 +1,10 @@
 // Test-only: the library's transfer engine (tc_engine_core.h) on a CPU stand-in for the device, to be built
-// with AddressSanitizer + UBSan.  The stand-in executes every enqueued operation at once on plain heap
-// buffers of exact size; a copy-kernel launch is walked workgroup by workgroup through the same index
+// with AddressSanitizer + UBSan.  The stand-in keeps a queue per stream and runs nothing when it is enqueued:
+// operations run when somebody waits (event_sync, stream_sync, sometimes event_query), one at a time, from
+// whichever stream a seeded scheduler picks among those whose next operation is not a wait for an event that
+// has not completed yet.  Three policies (random, highest stream first, lowest stream first) make sure that an
+// order the engine relies on without an event to enforce it shows up as wrong data.  Operations work on plain
+// heap buffers of exact size; a copy-kernel launch is walked workgroup by workgroup through the same index
 // arithmetic the kernels use (tc_map.h), so an access outside a pool, a staging slot, an id span or a host
 // buffer is an ASan report here instead of a GPU fault there.  Results are compared with the CPU oracle
 // (oracle/tc_oracle.c, linked in), and every fallible device call of a transfer is made to fail in turn
@@ -9,6 +13,9 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <deque>
+#include <functional>
+#include <map>
 #include <memory>
 #include <random>
 #include <vector>
@@ -27,12 +34,14 @@ int tco_upload(const uint8_t *host, uint32_t L, uint64_t NB, uint64_t pb, uint32
 
 namespace {
 
+int g_policy = 0;   // 0 = random, 1 = the highest-numbered runnable stream first, 2 = the lowest first
+
 struct DevState {
     long calls = 0;           // fallible device calls so far
     long fail_at = -1;        // the call with this number fails (once)
     bool records_fail = false;  // from the failing call on, event_record fails too
     bool failed = false;
-    long launches = 0, copies = 0, waits = 0;
+    long launches = 0, copies = 0, waits = 0, ran_on_engine_stream = 0;
     std::vector<std::pair<const char *, uint64_t>> pinned;   // host buffers that count as pinned
     std::vector<std::pair<const char *, uint64_t>> device;   // device allocations
     bool tick()
@@ -50,6 +59,52 @@ struct DevState {
         for (auto &r : v)
             if (b >= r.first && b + bytes <= r.first + r.second) return true;
         return false;
+    }
+
+    // ---- streams: nothing runs at enqueue
+    struct Op {
+        int kind;   // 0 = work, 1 = record an event, 2 = wait for an event
+        std::function<void()> fn;
+        int ev;
+        long gen;   // which recording of the event (a wait means the latest one at the time of the call)
+    };
+    std::map<uintptr_t, std::deque<Op>> queues;
+    std::map<int, long> recorded, completed;
+    std::mt19937 sched{12345};
+
+    void push_work(uintptr_t stream, std::function<void()> fn) { queues[stream].push_back(Op{0, std::move(fn), 0, 0}); }
+    void push_record(uintptr_t stream, int ev) { queues[stream].push_back(Op{1, nullptr, ev, ++recorded[ev]}); }
+    void push_wait(uintptr_t stream, int ev) { queues[stream].push_back(Op{2, nullptr, ev, recorded[ev]}); }
+    bool step()
+    {
+        std::vector<uintptr_t> runnable;
+        for (auto &kv : queues) {
+            if (kv.second.empty()) continue;
+            const Op &op = kv.second.front();
+            if (op.kind == 2 && completed[op.ev] < op.gen) continue;
+            runnable.push_back(kv.first);
+        }
+        if (runnable.empty()) return false;
+        uintptr_t pick = g_policy == 1 ? runnable.back() : (g_policy == 2 ? runnable.front() : runnable[sched() % runnable.size()]);
+        Op op = std::move(queues[pick].front());
+        queues[pick].pop_front();
+        if (op.kind == 0) op.fn();
+        else if (op.kind == 1) completed[op.ev] = std::max(completed[op.ev], op.gen);
+        return true;
+    }
+    bool idle() const
+    {
+        for (auto &kv : queues)
+            if (!kv.second.empty()) return false;
+        return true;
+    }
+    template <class Pred> void run_until(Pred done)
+    {
+        while (!done())
+            if (!step()) {
+                std::printf("FAILED: the streams are stuck: every queue waits for an event nobody will record\n");
+                std::exit(1);
+            }
     }
 };
 
@@ -89,6 +144,8 @@ void emulate_page_copy(bool gather, uint8_t *pool, uint32_t *scales, uint8_t *st
     for (uint32_t i = 0; i < c.n_items; ++i) REQUIRE(seen[i] == 1);
 }
 
+constexpr uintptr_t kEngineStream = 1000;   // numbered above every caller's stream
+
 struct FakeDev {
     using Stream = uintptr_t;
     using Event = int;
@@ -102,60 +159,92 @@ struct FakeDev {
         return 0;
     }
     void event_destroy(Event) {}
-    int event_record(Event, Stream) { return (s->tick() || (s->failed && s->records_fail)) ? 1 : 0; }
-    int event_query(Event) { return 0; }       // everything has run by the time anybody asks
-    int event_sync(Event) { return 0; }
+    int event_record(Event e, Stream st)
+    {
+        if (s->tick() || (s->failed && s->records_fail)) return 1;
+        s->push_record(st, e);
+        return 0;
+    }
+    int event_query(Event e)
+    {
+        for (unsigned k = s->sched() % 3; k > 0; --k) (void)s->step();   // time passes, a little
+        return s->completed[e] >= s->recorded[e] ? 0 : 1;
+    }
+    int event_sync(Event e)
+    {
+        const long want = s->recorded[e];
+        s->run_until([&] { return s->completed[e] >= want; });
+        return 0;
+    }
     int event_elapsed_ms(float *ms, Event, Event) { *ms = 1.f; return 0; }
-    int stream_wait(Stream, Event) { ++s->waits; return s->tick() ? 1 : 0; }
-    int stream_sync(Stream) { return 0; }
-    int copy_ids(int32_t *dev, const int32_t *host, uint64_t n, Stream)
+    int stream_wait(Stream st, Event e)
     {
+        ++s->waits;
         if (s->tick()) return 1;
-        std::memcpy(dev, host, n * 4);
+        s->push_wait(st, e);
         return 0;
     }
-    int copy_d2h(void *host, const void *dev, uint64_t bytes, Stream)
+    int stream_sync(Stream st)
+    {
+        s->run_until([&] { return s->queues[st].empty(); });
+        return 0;
+    }
+    int copy_ids(int32_t *dev, const int32_t *host, uint64_t n, Stream st)
+    {
+        if (s->tick()) return 1;
+        s->push_work(st, [=] { std::memcpy(dev, host, n * 4); });
+        return 0;
+    }
+    int copy_d2h(void *host, const void *dev, uint64_t bytes, Stream st)
     {
         if (s->tick()) return 1;
         REQUIRE(DevState::inside(s->pinned, host, bytes) && DevState::inside(s->device, dev, bytes));
-        std::memcpy(host, dev, bytes);
         ++s->copies;
+        s->push_work(st, [=] { std::memcpy(host, dev, bytes); });
         return 0;
     }
-    int copy_h2d(void *dev, const void *host, uint64_t bytes, Stream)
+    int copy_h2d(void *dev, const void *host, uint64_t bytes, Stream st)
     {
         if (s->tick()) return 1;
         REQUIRE(DevState::inside(s->pinned, host, bytes) && DevState::inside(s->device, dev, bytes));
-        std::memcpy(dev, host, bytes);
         ++s->copies;
+        s->push_work(st, [=] { std::memcpy(dev, host, bytes); });
         return 0;
     }
     int gather(const void *pool, const uint32_t *scales, void *staging, const int32_t *ids_dev, uint32_t n,
-               const tc::PageGeom &g, uint32_t max_grid, bool direct, Stream, void *host_part, uint32_t split,
+               const tc::PageGeom &g, uint32_t max_grid, bool direct, Stream st, void *host_part, uint32_t split,
                uint32_t host_wgs)
     {
         if (s->tick()) return 1;
         ++s->launches;
-        emulate_page_copy(true, static_cast<uint8_t *>(const_cast<void *>(pool)), const_cast<uint32_t *>(scales),
-                          static_cast<uint8_t *>(staging), ids_dev, n, g, max_grid, direct, static_cast<uint8_t *>(host_part),
-                          split, host_wgs);
+        if (st == kEngineStream) ++s->ran_on_engine_stream;
+        s->push_work(st, [=] {
+            emulate_page_copy(true, static_cast<uint8_t *>(const_cast<void *>(pool)), const_cast<uint32_t *>(scales),
+                              static_cast<uint8_t *>(staging), ids_dev, n, g, max_grid, direct, static_cast<uint8_t *>(host_part),
+                              split, host_wgs);
+        });
         return 0;
     }
     int scatter(const void *staging, void *pool, uint32_t *scales, const int32_t *ids_dev, uint32_t n,
-                const tc::PageGeom &g, uint32_t max_grid, bool direct, Stream, const void *host_part, uint32_t split,
+                const tc::PageGeom &g, uint32_t max_grid, bool direct, Stream st, const void *host_part, uint32_t split,
                 uint32_t host_wgs)
     {
         if (s->tick()) return 1;
         ++s->launches;
-        emulate_page_copy(false, static_cast<uint8_t *>(pool), scales, static_cast<uint8_t *>(const_cast<void *>(staging)),
-                          ids_dev, n, g, max_grid, direct, static_cast<uint8_t *>(const_cast<void *>(host_part)), split,
-                          host_wgs);
+        if (st == kEngineStream) ++s->ran_on_engine_stream;
+        s->push_work(st, [=] {
+            emulate_page_copy(false, static_cast<uint8_t *>(pool), scales, static_cast<uint8_t *>(const_cast<void *>(staging)),
+                              ids_dev, n, g, max_grid, direct, static_cast<uint8_t *>(const_cast<void *>(host_part)), split,
+                              host_wgs);
+        });
         return 0;
     }
-    int rewrite(int32_t *table, const int32_t *ids_dev, uint32_t n, Stream)
+    int rewrite(int32_t *table, const int32_t *ids_dev, uint32_t n, Stream st)
     {
         if (s->tick()) return 1;
-        for (uint32_t i = 0; i < n; ++i) table[i] = ids_dev[i];
+        s->push_work(st, [=] {
+            for (uint32_t i = 0; i < n; ++i) table[i] = ids_dev[i];
+        });
         return 0;
     }
     int device_view(void **out, void *host)
@@ -203,8 +292,11 @@ struct Rig {
         e.slots.resize(n_slots);
         for (uint32_t i = 0; i < n_slots; ++i) {
             e.slots[i].buf = reinterpret_cast<char *>(staging.get()) + uint64_t(i) * slot_blocks * rec;
-            e.slots[i].last = 1000 + int(i);
+            e.slots[i].last = (1 << 30) + 2 * int(i);
+            e.slots[i].ready = (1 << 30) + 1 + 2 * int(i);
         }
+        e.kstream = kEngineStream;
+        e.has_kstream = true;
         ring_cap = std::max<uint64_t>(4ull * s.NB, 64);
         ids_host.reset(new int32_t[ring_cap]);
         ids_dev.reset(new int32_t[ring_cap]);
@@ -281,16 +373,17 @@ void round_trip(Shape sh, tc_opts opts, uint32_t n_slots, uint32_t slot_blocks, 
         std::vector<uint8_t> mirror(r.pool.get(), r.pool.get() + r.pool_bytes);
         std::vector<uint32_t> mirror_scales(sh.S ? r.scales.get() : nullptr, sh.S ? r.scales.get() + uint64_t(sh.S) * sh.NB : nullptr);
         REQUIRE(e.offload(out_descs.data(), agents, FakeDev::Stream(1 + round % 2)) == TC_OK);
+        for (uint32_t a = 0; a < agents; ++a)
+            REQUIRE(e.blocks->free(src[a].data(), uint32_t(src[a].size())) == TC_OK);     // pending-free until retired
+        REQUIRE(e.sync() == TC_OK && e.blocks->n_free() == sh.NB && e.book->ring().used() == 0);
         for (uint32_t a = 0; a < agents; ++a) {
             const uint32_t n = uint32_t(src[a].size());
             std::vector<uint8_t> want(uint64_t(n) * r.rec + 1);
             REQUIRE(tco_offload(mirror.data(), sh.S ? mirror_scales.data() : nullptr, sh.L, sh.NB, sh.pb, sh.S, src[a].data(), n,
                                 want.data()) == 0);
             REQUIRE(std::memcmp(want.data(), host[a], uint64_t(n) * r.rec) == 0);
-            REQUIRE(e.blocks->free(src[a].data(), n) == TC_OK);     // pending-free until retired
         }
         REQUIRE(std::memcmp(mirror.data(), r.pool.get(), r.pool_bytes) == 0);   // an offload writes no block
-        REQUIRE(e.sync() == TC_OK && e.blocks->n_free() == sh.NB && e.book->ring().used() == 0);
         // somebody else uses the freed blocks
         for (uint64_t i = 0; i < r.pool_bytes; i += 1 + rng() % 97) r.pool[i] ^= 0x5a;
         mirror.assign(r.pool.get(), r.pool.get() + r.pool_bytes);
@@ -301,6 +394,7 @@ void round_trip(Shape sh, tc_opts opts, uint32_t n_slots, uint32_t slot_blocks, 
             r.dev.device.push_back({reinterpret_cast<char *>(tables[a].data()), tables[a].size() * 4});
         }
         REQUIRE(e.upload(in_descs.data(), agents, FakeDev::Stream(2)) == TC_OK);
+        REQUIRE(e.sync() == TC_OK);
         for (uint32_t a = 0; a < agents; ++a) {
             const uint32_t n = uint32_t(dst[a].size());
             std::vector<int32_t> want_table(n + 2, -7);
@@ -324,12 +418,13 @@ void round_trip(Shape sh, tc_opts opts, uint32_t n_slots, uint32_t slot_blocks, 
 
 // Every fallible device call of one transfer fails in turn; afterwards nothing the stream may still read has
 // been given away, and the engine works on.
-void failures(bool upload, uint32_t mode, bool records_fail, uint32_t seed)
+void failures(bool upload, uint32_t mode, bool records_fail, uint32_t inline_kernels, uint32_t seed)
 {
     const Shape sh{2, 4096 + 1024, 40, 4};
     tc_opts opts{};
     opts.direct_offload = opts.direct_upload = mode;
     opts.host_tail_div = 2;
+    opts.inline_kernels = inline_kernels;
     const uint32_t n = 7;
     long calls_of_a_good_transfer = 0;
     int held = 0, rolled_back = 0;
@@ -384,6 +479,7 @@ void failures(bool upload, uint32_t mode, bool records_fail, uint32_t seed)
             REQUIRE(e.blocks->alloc(sh.NB - n, std::vector<int32_t>(sh.NB - n).data()) == TC_OK);
             REQUIRE(e.blocks->alloc(1, again.data()) == TC_ERR_NOMEM);        // the held blocks are not handed out
             REQUIRE(e.sync() == TC_OK);
+            REQUIRE(r.dev.idle());   // retired means nothing of it is left on any stream, the engine's own included
             e.fill_stats(&st);
             REQUIRE(st.ops_in_flight == 0 && st.gpu_blocks_pending_free == 0 && st.gpu_blocks_free == n);
             REQUIRE(e.arena->used() == 0 && e.book->ring().used() == 0);
@@ -495,9 +591,93 @@ void hazards_are_waited_for()
     (void)db;
 }
 
+// Several transfers in flight at once on two callers' streams, sharing few small staging slots: slot reuse
+// across transfers and streams, kernels on the engine's stream, and the order of a host buffer's writer and
+// reader on different streams are all left to events.
+void transfers_in_flight_together(uint32_t inline_kernels, uint32_t n_slots, uint32_t seed)
+{
+    std::mt19937 rng(seed);
+    const Shape sh{2, 4096 + 512, 96, 4};
+    tc_opts opts{};
+    opts.direct_offload = opts.direct_upload = tc::kPathStaged;
+    opts.inline_kernels = inline_kernels;
+    opts.host_tail_div = seed % 2 ? 1 : 3;
+    Rig r(sh, opts, n_slots, 3, 64, rng);
+    auto &e = r.e;
+    std::vector<int32_t> free_ids;
+    for (uint32_t b = 0; b < sh.NB; ++b) free_ids.push_back(int32_t(b));
+    const uint32_t agents = 5;
+    std::vector<std::vector<int32_t>> src(agents), dst(agents);
+    std::vector<uint8_t *> host(agents);
+    std::vector<std::unique_ptr<uint8_t[]>> keep;
+    const std::vector<uint8_t> pool0(r.pool.get(), r.pool.get() + r.pool_bytes);
+    const std::vector<uint32_t> scales0(r.scales.get(), r.scales.get() + uint64_t(sh.S) * sh.NB);
+    for (uint32_t a = 0; a < agents; ++a) {
+        const uint32_t n = 1 + rng() % 9;
+        src[a] = pick(rng, free_ids, n);
+        dst[a] = pick(rng, free_ids, n);
+        host[a] = r.host_buffer(n, true, keep);
+        REQUIRE(e.blocks->alloc_at(src[a].data(), n) == TC_OK && e.blocks->alloc_at(dst[a].data(), n) == TC_OK);
+    }
+    // every agent goes out and comes straight back into other blocks, the upload on another stream than the
+    // offload, with nothing waited for in between: the upload has to find the offload's records in the buffer
+    for (uint32_t a = 0; a < agents; ++a) {
+        tc_xfer_desc out{src[a].data(), uint32_t(src[a].size()), host[a], nullptr};
+        tc_xfer_desc in{dst[a].data(), uint32_t(dst[a].size()), host[a], nullptr};
+        REQUIRE(e.offload(&out, 1, FakeDev::Stream(1 + a % 2)) == TC_OK);
+        REQUIRE(e.upload(&in, 1, FakeDev::Stream(2 - a % 2)) == TC_OK);
+    }
+    REQUIRE(e.sync() == TC_OK && r.dev.idle());
+    std::vector<uint8_t> mirror = pool0;
+    std::vector<uint32_t> mirror_scales = scales0;
+    for (uint32_t a = 0; a < agents; ++a) {
+        const uint32_t n = uint32_t(src[a].size());
+        std::vector<uint8_t> want(uint64_t(n) * r.rec);
+        REQUIRE(tco_offload(pool0.data(), scales0.data(), sh.L, sh.NB, sh.pb, sh.S, src[a].data(), n, want.data()) == 0);
+        REQUIRE(std::memcmp(want.data(), host[a], want.size()) == 0);
+        REQUIRE(tco_upload(want.data(), sh.L, sh.NB, sh.pb, sh.S, dst[a].data(), n, mirror.data(), mirror_scales.data(), nullptr) == 0);
+    }
+    REQUIRE(std::memcmp(mirror.data(), r.pool.get(), r.pool_bytes) == 0);
+    REQUIRE(std::memcmp(mirror_scales.data(), r.scales.get(), mirror_scales.size() * 4) == 0);
+    tc_stats_t st;
+    e.fill_stats(&st);
+    if (inline_kernels == 0) REQUIRE(st.transfers_overlapped > 0 && r.dev.ran_on_engine_stream > 0);
+    else REQUIRE(st.transfers_overlapped == 0 && r.dev.ran_on_engine_stream == 0);
+}
+
+// The plan the engine follows: a single chunk stays in line, several chunks overlap and start with a short one.
+void which_transfers_overlap()
+{
+    std::mt19937 rng(8);
+    const Shape sh{1, 1 << 20, 80, 0};                 // 2 MiB records: the short chunk is 16 blocks
+    tc_opts opts{};
+    opts.direct_offload = opts.direct_upload = tc::kPathStaged;
+    Rig r(sh, opts, 2, 40, 80, rng);
+    auto &e = r.e;
+    std::vector<int32_t> ids(80);
+    for (int i = 0; i < 80; ++i) ids[size_t(i)] = i;
+    REQUIRE(e.blocks->alloc_at(ids.data(), 80) == TC_OK && e.arena->alloc(80) == 0);
+    tc_stats_t st;
+    auto launches_of = [&](uint32_t n, bool upload) {
+        const long before = r.dev.launches;
+        tc_xfer_desc d{ids.data(), n, r.arena.get(), nullptr};
+        REQUIRE((upload ? e.upload(&d, 1, 1) : e.offload(&d, 1, 1)) == TC_OK && e.sync() == TC_OK);
+        return r.dev.launches - before;
+    };
+    REQUIRE(launches_of(32, false) == 1);              // at most twice the short chunk: one chunk, in line
+    e.fill_stats(&st);
+    REQUIRE(st.transfers_overlapped == 0 && r.dev.ran_on_engine_stream == 0);
+    REQUIRE(launches_of(33, false) == 2);              // 16 + 17
+    e.fill_stats(&st);
+    REQUIRE(st.transfers_overlapped == 1 && r.dev.ran_on_engine_stream == 2);
+    REQUIRE(launches_of(80, true) == 3);               // 24 + 40 + 16 in upload order
+    e.fill_stats(&st);
+    REQUIRE(st.transfers_overlapped == 2 && r.dev.ran_on_engine_stream == 5);
+}
+
 }  // namespace
 
-int main()
+void all_tests()
 {
     const Shape shapes[] = {
         {2, 8192, 64, 0},        // the tiny configuration's pages
@@ -525,9 +705,19 @@ int main()
     }
     for (bool upload : {false, true})
         for (uint32_t mode : {tc::kPathStaged, tc::kPathDirect})
-            for (bool records_fail : {false, true}) failures(upload, mode, records_fail, 9);
+            for (bool records_fail : {false, true})
+                for (uint32_t inline_kernels : {0u, 1u}) failures(upload, mode, records_fail, inline_kernels, 9);
     validation();
     hazards_are_waited_for();
+    which_transfers_overlap();
+    for (uint32_t inline_kernels : {0u, 1u})
+        for (uint32_t n_slots : {1u, 2u, 3u})
+            for (uint32_t seed = 0; seed < 6; ++seed) transfers_in_flight_together(inline_kernels, n_slots, 40 + seed);
+}
+
+int main()
+{
+    for (g_policy = 0; g_policy < 3; ++g_policy) all_tests();
     std::puts("ok");
     return 0;
 }

@@ -50,11 +50,11 @@ def test_error_strings_and_struct_layout():
     assert "unknown" in K.tc_strerror(-99)
     # the ctypes mirrors must match the C layout (checked against sizes the compiler would give)
     assert ctypes.sizeof(K.tc_pool_desc) == 40
-    assert ctypes.sizeof(K.tc_opts) == 48
+    assert ctypes.sizeof(K.tc_opts) == 56
     assert ctypes.sizeof(K.tc_xfer_desc) == 32
     assert ctypes.sizeof(K.tc_gate_input) == 40 and ctypes.sizeof(K.tc_upload_cand) == 24
     assert ctypes.sizeof(K.tc_index_hit) == 24
-    assert ctypes.sizeof(K.tc_stats_t) == 24 + 16 + 48 + 32 + 16 + 24 + 48 + 8
+    assert ctypes.sizeof(K.tc_stats_t) == 24 + 16 + 48 + 32 + 16 + 24 + 48 + 8 + 8
 
 
 def test_null_arguments_are_rejected_without_a_gpu():
@@ -66,6 +66,7 @@ def test_null_arguments_are_rejected_without_a_gpu():
     assert K.tc_create(0x1000, None, 1 << 19, 4096, 16, 1)[0] == K.TC_ERR_INVAL
     assert K.tc_create(0x1000, None, 2, 16, 4096, 16, direct_offload=4)[0] == K.TC_ERR_INVAL
     assert K.tc_create(0x1000, None, 2, 16, 4096, 16, direct_upload=2)[0] == K.TC_ERR_INVAL
+    assert K.tc_create(0x1000, None, 2, 16, 4096, 16, inline_kernels=2)[0] == K.TC_ERR_INVAL
     assert K.tc_create(0x1010, None, 2, 16, 4096, 16)[0] == K.TC_ERR_INVAL          # base not 256-B aligned
     assert K.tc_create(0x1000, None, 2, 16, 4100, 16)[0] == K.TC_ERR_INVAL          # page not a multiple of 16
     assert K.tc_destroy(None) == K.TC_OK

@@ -316,12 +316,14 @@ def _plan_sigs(lib):
     lib.tcp_book_retire.restype, lib.tcp_book_retire.argtypes = u64, [vp]
     lib.tcp_book_ring_used.restype, lib.tcp_book_ring_used.argtypes = u64, [vp]
     lib.tcp_book_upload_in_flight.argtypes = [vp]
-    lib.tcp_plan_chunks.restype, lib.tcp_plan_chunks.argtypes = u32, [u64, u32, ci, vp, u32]
+    lib.tcp_plan_chunks.restype, lib.tcp_plan_chunks.argtypes = u32, [u64, u32, ci, u32, vp, u32]
     lib.tcp_chunk_pieces.restype, lib.tcp_chunk_pieces.argtypes = u32, [vp, vp, u32, u64, u64, vp, u32]
     lib.tcp_host_tail.argtypes = [u32, u64, u32, vp, vp, u32, vp]
     lib.tcp_offload_direct.argtypes = [u32, u64, ci, u64]
     lib.tcp_upload_direct.argtypes = [u32]
-    lib.tcp_tail_divisor.restype, lib.tcp_tail_divisor.argtypes = u32, [u32, u64]
+    lib.tcp_tail_divisor.restype, lib.tcp_tail_divisor.argtypes = u32, [u32, u64, ci]
+    lib.tcp_kernels_overlap.argtypes = [u32, u64]
+    lib.tcp_plan_staged.restype, lib.tcp_plan_staged.argtypes = u32, [u64, u32, ci, u32, u32, ctypes.POINTER(ci), vp, u32]
     return lib
 
 
@@ -376,9 +378,13 @@ def test_chunks_pieces_tail_and_paths_match_the_model(shim):
         segs = [(int(f), int(n)) for f, n in zip(firsts, lens)]
         total, slot, up = int(lens.sum()), int(rng.integers(1, 400)), int(rng.integers(0, 2))
         out = np.zeros(2048, dtype=np.uint32)
-        k = lib.tcp_plan_chunks(total, slot, up, out.ctypes.data, out.size)
-        sizes = T.plan_chunks(total, slot, bool(up))
+        head = int(rng.choice([0, 0, 1, 7, 64, 500]))
+        k = lib.tcp_plan_chunks(total, slot, up, head, out.ctypes.data, out.size)
+        sizes = T.plan_chunks(total, slot, bool(up), head)
         assert out[:k].tolist() == sizes
+        ov = ctypes.c_int(0)
+        k2 = lib.tcp_plan_staged(total, slot, up, head, opt01 := int(rng.integers(0, 2)), ctypes.byref(ov), out.ctypes.data, out.size)
+        assert (out[:k2].tolist(), bool(ov.value)) == T.plan_staged(total, slot, bool(up), head, opt01)
         c0 = 0
         for size in sizes[:6]:
             buf = np.zeros(4 * 16, dtype=np.uint64)
@@ -394,14 +400,16 @@ def test_chunks_pieces_tail_and_paths_match_the_model(shim):
         assert bool(lib.tcp_offload_direct(mode, nbytes, dup, auto)) == (T.offload_path(mode, nbytes, bool(dup), auto) == T.DIRECT)
         assert bool(lib.tcp_upload_direct(mode)) == (T.upload_path(mode) == T.DIRECT)
         opt, nch = int(rng.choice([0, 1, 2, 48])), int(rng.integers(1, 5))
-        assert lib.tcp_tail_divisor(opt, nch) == T.tail_divisor(opt, nch)
+        ov = int(rng.integers(0, 2))
+        assert lib.tcp_tail_divisor(opt, nch, ov) == T.tail_divisor(opt, nch, bool(ov))
+        assert bool(lib.tcp_kernels_overlap(opt if opt < 2 else 0, nch)) == T.kernels_overlap_copies(opt if opt < 2 else 0, nch)
 
 
 def test_engine_on_a_cpu_stand_in_under_sanitizers(tmp_path):
     """tests/csrc/engine_emul.cpp: the whole transfer engine (csrc/tc_engine_core.h) with a stand-in device that
-    runs every copy and every kernel launch at once on exact-size heap buffers, walking a launch through the
-    kernels' own index arithmetic.  Built with AddressSanitizer + UBSan, compared byte for byte with the oracle's
-    C file, with every fallible device call failing in turn."""
+    queues work per stream and runs it in adversarial orders on exact-size heap buffers, walking a launch through
+    the kernels' own index arithmetic.  Built with AddressSanitizer + UBSan, compared byte for byte with the
+    oracle's C file, with every fallible device call failing in turn."""
     import oracle
     csrc = os.path.join(ROOT, "paper_2510_18586_amd", "csrc")
     exe, obj = str(tmp_path / "engine_emul"), str(tmp_path / "tc_oracle.o")
@@ -413,3 +421,54 @@ def test_engine_on_a_cpu_stand_in_under_sanitizers(tmp_path):
                     "-o", exe], check=True)
     out = subprocess.run([exe], capture_output=True, text=True, timeout=600)
     assert out.returncode == 0 and out.stdout.strip().endswith("ok"), (out.returncode, out.stdout[-2000:], out.stderr[-4000:])
+
+
+ORDERING_MISTAKES = {
+    "an offload's DMA does not wait for its gather": (
+        "                    TC_DEV(dev.stream_wait(stream, slot->ready));\n                }\n                TC_RC(time_begin(&op, stream, uint64_t(split) * rec, kD2H));",
+        "                }\n                TC_RC(time_begin(&op, stream, uint64_t(split) * rec, kD2H));"),
+    "a gather overwrites a slot whose DMA is still to come": ("if (slot->used) TC_DEV(dev.stream_wait(ks, slot->last));", ";"),
+    "a scatter does not wait for its DMA": ("                    TC_DEV(dev.stream_wait(kstream, slot->ready));", ""),
+    "the table is rewritten before the last scatter": (
+        "            if (overlapped && final_slot) TC_DEV(dev.stream_wait(stream, final_slot->last));", ""),
+    "the engine's stream starts before the ids are in place": ("                TC_DEV(dev.stream_wait(kstream, op.payload.entry));", ""),
+    "a transfer on another stream is not waited for": (
+        "            if (dev.stream_wait(stream, book->entries()[at].payload.done)) return TC_ERR_HIP;", ";"),
+    "an upload's DMA overwrites a slot whose scatter is still to come": ("if (slot->used) TC_DEV(dev.stream_wait(stream, slot->last));", ";"),
+    "a failed transfer's completion does not cover the engine's stream": (
+        "covered = dev.event_record(op.payload.entry, kstream) == 0 && dev.stream_wait(stream, op.payload.entry) == 0;", "covered = true;"),
+}
+
+
+def test_ordering_mistakes_planted_in_the_engine_are_caught(tmp_path):
+    """The stand-in device of tests/csrc/engine_emul.cpp runs queued work in adversarial orders.  That this finds a
+    missing event wait is itself checked: each wait the engine relies on is taken out of a copy of
+    csrc/tc_engine_core.h in turn, and every such build must fail the stand-in's tests (CPU only, memory-safe:
+    the stand-in works on heap buffers)."""
+    import shutil
+    from concurrent.futures import ThreadPoolExecutor
+    import oracle
+    csrc = os.path.join(ROOT, "paper_2510_18586_amd", "csrc")
+    obj = str(tmp_path / "tc_oracle.o")
+    subprocess.run(["gcc", "-std=c11", "-O1", "-c", os.path.join(os.path.dirname(oracle.__file__), "tc_oracle.c"), "-o", obj], check=True)
+    text = open(os.path.join(csrc, "tc_engine_core.h")).read()
+
+    def build_and_run(item):
+        k, (name, (old, new)) = item
+        d = tmp_path / f"m{k}"
+        d.mkdir()
+        for h in os.listdir(csrc):
+            if h.endswith(".h"):
+                shutil.copy(os.path.join(csrc, h), d / h)
+        assert text.count(old) >= 1, name
+        (d / "tc_engine_core.h").write_text(text.replace(old, new, 1))
+        exe = str(d / "emul")
+        subprocess.run(["g++", "-std=c++17", "-O1", "-I", os.path.join(ROOT, "include"), "-I", str(d),
+                        os.path.join(HERE, "csrc", "engine_emul.cpp"), obj, "-o", exe], check=True)
+        out = subprocess.run([exe], capture_output=True, text=True, timeout=300)
+        return name, out.returncode, out.stdout[-300:]
+
+    with ThreadPoolExecutor(4) as pool:
+        results = list(pool.map(build_and_run, enumerate(ORDERING_MISTAKES.items())))
+    for name, rc, tail in results:
+        assert rc != 0 and "FAILED" in tail, f"not caught: {name}: {tail}"

@@ -100,6 +100,15 @@ def test_chunks_with_a_short_first_chunk():
                     assert off == T.plan_chunks(total, slot, False)
 
 
+def test_a_staged_transfer_overlaps_only_if_there_is_something_to_overlap():
+    assert T.plan_staged(4, 8, False, 2, 0) == ([4], False)              # at most twice the head: one chunk, in line
+    assert T.plan_staged(5, 8, False, 2, 0) == ([2, 3], True) and T.plan_staged(5, 8, True, 2, 0) == ([3, 2], True)
+    assert T.plan_staged(5, 8, False, 2, 1) == ([5], False)              # switched off: the plain cut
+    assert T.plan_staged(20, 8, False, 2, 1) == ([8, 8, 4], False) and T.plan_staged(20, 8, True, 2, 0) == ([2, 8, 8, 2], True)
+    assert T.plan_staged(20, 8, False, 0, 0) == ([8, 8, 4], True) and T.plan_staged(8, 8, False, 0, 0) == ([8], False)
+    assert T.plan_staged(0, 8, False, 2, 0) == ([], False)
+
+
 def test_pieces_carry_every_record_once():
     rng = np.random.default_rng(6)
     assert T.chunk_pieces([(0, 5), (5, 3)], 3, 7) == [(0, 3, 0, 2), (1, 0, 2, 2)]
