@@ -222,7 +222,7 @@ class TwoContexts:
     forced, so that the HBM-bound kernels can be timed on the same agents.  Host buffers come from the first
     context's pinned arena; the second takes them as the caller's pinned memory."""
 
-    def __init__(self, torch, K, shape, pool, scales, arena_blocks):
+    def __init__(self, torch, K, shape, pool, scales, arena_blocks, overlapped=False):
         self.K, self.shape = K, shape
         a = (shape.num_layers, shape.num_blocks, shape.page_bytes, shape.block_size, shape.scales_per_block)
         # the arena is sized by an upper bound of the record size; what a record is, the library says
@@ -234,8 +234,15 @@ class TwoContexts:
                                       host_tail_div=1)
         K.check(rc)
         K.check(K.tc_set_profiling(self.staged, 1))
+        self.overlapped = None
+        if overlapped:   # a third binding: the two-stage path with its kernels on the context's own stream
+            rc, self.overlapped = K.tc_create(pool, scales, *a, direct_offload=K.TC_PATH_STAGED, direct_upload=K.TC_PATH_STAGED,
+                                              host_tail_div=1, overlap_kernels=1)
+            K.check(rc)
 
     def close(self):
+        if self.overlapped:
+            self.K.check(self.K.tc_destroy(self.overlapped))
         self.K.check(self.K.tc_destroy(self.staged))
         self.K.check(self.K.tc_destroy(self.auto))
 
@@ -253,7 +260,9 @@ def batch_both_ways(torch, K, two, link, src, dst, tables, stream, tokens):
     link = plain_copy_on(torch, K.tc_arena_base(two.auto), min(payload, 512 << 20), stream)
     out["pinned_link_GBps_on_this_arena"] = {k: round(v, 3) for k, v in link.items()}
     before = K.tc_stats(two.staged)[1]
-    for ctx, key in ((two.auto, "default_paths"), (two.staged, "staged_path")):
+    for ctx, key in ((two.auto, "default_paths"), (two.staged, "staged_path"), (two.overlapped, "staged_overlapped")):
+        if ctx is None:
+            continue
         for s in src:
             K.check(K.tc_alloc_at(ctx, s))
         if dst is not src:
@@ -311,7 +320,7 @@ def config3(torch, K, W, link, pool):
     tokens = W.lognormal_contexts(rng, 64)
     nblk = W.blocks_of(tokens, shape.block_size).astype(int)
     total = int(nblk.sum())
-    two = TwoContexts(torch, K, shape, pool, None, total + 8)
+    two = TwoContexts(torch, K, shape, pool, None, total + 8, overlapped=True)
 
     class B:
         def alloc(self, n):
@@ -357,7 +366,7 @@ def config3(torch, K, W, link, pool):
     tri_alone()
     t_tri = tri_alone()
 
-    def overlapped(fn, alone_ms):
+    def overlapped(fn, alone_ms, ctx=two.auto):
         iters = max(1, int(alone_ms / t_tri) + 2)
         e = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
         torch.cuda.synchronize()
@@ -384,6 +393,20 @@ def config3(torch, K, W, link, pool):
         "neighbour_alone_GBps": round(tri_bytes / t_tri / 1e6, 1),
         "neighbour_during_offload_GBps": round(tri_bytes / tri_off / 1e6, 1),
         "neighbour_during_upload_GBps": round(tri_bytes / tri_up / 1e6, 1)}
+
+    # the same next to the neighbour with the copy kernels on the context's own stream (overlap_kernels = 1): what
+    # happens depends on which hardware queue the runtime gives that stream
+    for s in src:
+        K.check(K.tc_free(two.auto, s))
+        K.check(K.tc_alloc_at(two.overlapped, s))
+    so = out["staged_overlapped"]
+    off_ov2, tri_off2 = overlapped(lambda: K.check(K.tc_offload_batch(two.overlapped, items_out, copy)), so["offload_ms"], two.overlapped)
+    out["next_to_a_memory_bound_kernel"]["staged_overlapped"] = {
+        "offload_GBps": round(payload / off_ov2 / 1e6, 3), "offload_change_pct": round(100 * (so["offload_ms"] / off_ov2 - 1), 2),
+        "neighbour_during_offload_GBps": round(tri_bytes / tri_off2 / 1e6, 1)}
+    for s in src:
+        K.check(K.tc_free(two.overlapped, s))
+        K.check(K.tc_alloc_at(two.auto, s))
 
     # half of the agents go out while the other half comes back, on two streams
     dup = {}
@@ -455,7 +478,7 @@ def config5(torch, K, W, link):
     private = (W.blocks_of(tokens, shape.block_size) - 32).astype(int)
     bound = shape.planes * shape.page_bytes + 4 * shape.scales_per_block + 256      # what a record can take at most
     arena_blocks = budget // bound
-    two = TwoContexts(torch, K, shape, pool, scales.view(torch.int32), arena_blocks)
+    two = TwoContexts(torch, K, shape, pool, scales.view(torch.int32), arena_blocks, overlapped=True)
     wave = []
     for n in private:                 # agents in index order while the arena has room
         if sum(wave) + n + 8 > arena_blocks:
@@ -662,8 +685,7 @@ def main():
 
     # the two-stage path forced in both directions, same agent, same launch configuration, after the timed steps
     staged, st2 = variant(torch, K, pool, shape, pairs, link,
-                          "direct_offload = direct_upload = TC_PATH_STAGED: gather_pages -> DMA, DMA -> scatter_pages; a short first chunk "
-                          "(32 MiB), then the rest, the copy kernels on the context's own stream under the DMA of the neighbouring chunk",
+                          "direct_offload = direct_upload = TC_PATH_STAGED, no host tail: gather_pages -> DMA, DMA -> scatter_pages",
                           steps=12, direct_offload=K.TC_PATH_STAGED, direct_upload=K.TC_PATH_STAGED, host_tail_div=1)
     # `roofline`: the HBM-bound kernel of the timed steps.  With the default paths that is gather_pages; the upload's
     # scatter reads pinned memory and is bound by the host link (it runs at the link rate, see pct_of_pinned_link).
@@ -682,8 +704,7 @@ def main():
                                "(2 MiB/block), 16384-block pool (32 GiB), one agent, "
                                f"{args.tokens} tokens = {n} blocks scattered uniformly",
                    "payload_bytes_each_way": payload, "tokens": n * shape.block_size,
-                   "paths": "library defaults: offload staged (gather_pages + D2H DMA in two chunks, 32 MiB + the rest, the second "
-                            "gather under the first DMA), upload direct (scatter_pages reads pinned memory, 16 workgroups)"},
+                   "paths": "library defaults: offload staged (gather_pages + D2H DMA), upload direct (scatter_pages reads pinned memory, 16 workgroups)"},
         **rates(payload, off_ms, up_ms, link, n * shape.block_size),
         "pinned_link_GBps": {k: round(v, 3) for k, v in link.items()},
         "roofline": dominant, "roofline_other_kernels": [r for r in others if r],
@@ -696,14 +717,14 @@ def main():
     out["direct_paths"] = variant(torch, K, pool, shape, pairs, link,
                                   "direct_offload = direct_upload = TC_PATH_DIRECT (6 / 16 workgroups): no staging, no DMA",
                                   direct_offload=K.TC_PATH_DIRECT, direct_upload=K.TC_PATH_DIRECT)[0]
-    out["staged_in_line"] = variant(torch, K, pool, shape, pairs, link,
-                                    "two-stage path with inline_kernels = 1: one chunk, kernel and DMA in line on the caller's "
-                                    "stream (no short first chunk, no overlap)",
-                                    direct_offload=K.TC_PATH_STAGED, direct_upload=K.TC_PATH_STAGED, host_tail_div=1, inline_kernels=1)[0]
+    out["staged_overlapped"] = variant(torch, K, pool, shape, pairs, link,
+                                       "two-stage path with overlap_kernels = 1: a short first chunk (32 MiB), then the rest, the copy "
+                                       "kernels on the context's own stream under the DMA of the neighbouring chunk",
+                                       direct_offload=K.TC_PATH_STAGED, direct_upload=K.TC_PATH_STAGED, host_tail_div=1, overlap_kernels=1)[0]
     out["host_tail"] = variant(torch, K, pool, shape, pairs, link,
-                               "in line as above, with host_tail_div = 64: the last 1/64 of the chunk crosses the link inside "
+                               "staged both ways with host_tail_div = 64: the last 1/64 of the chunk crosses the link inside "
                                "the copy launch; the launches get longer, the transfer shorter",
-                               direct_offload=K.TC_PATH_STAGED, direct_upload=K.TC_PATH_STAGED, host_tail_div=64, inline_kernels=1)[0]
+                               direct_offload=K.TC_PATH_STAGED, direct_upload=K.TC_PATH_STAGED, host_tail_div=64)[0]
     if not args.no_configs:
         cfgs = {"1": config1(torch, K, W, link), "3": config3(torch, K, W, link, pool)}
         del pool

@@ -100,18 +100,20 @@ typedef struct {
                                    workgroups of the same copy launch straight to / from the pinned buffer,
                                    using the link while it would otherwise wait for the kernel, and the DMA
                                    carries that much less.  0 = automatic (N = 64 for transfers of more than
-                                   one chunk whose kernels run in line with their DMAs, see inline_kernels;
+                                   one chunk whose kernels run in line with their DMAs, see overlap_kernels;
                                    none otherwise), 1 = never, N >= 2 = that N.  Applies to chunks of at
                                    least N blocks whose tail lies in one host buffer.                      */
     uint64_t auto_direct_bytes; /* TC_PATH_AUTO: offloads below this many record bytes go direct as well (one
                                    kernel instead of kernel + DMA saves ~19 us on an otherwise idle GPU; next to
                                    memory-bound kernels the staged path is the faster one); 0 = no such rule   */
-    uint32_t inline_kernels;    /* staged path: 0 = a transfer of more than one chunk runs its copy kernels on a
-                                   stream of the context's own, ordered with the caller's stream by events both
-                                   ways, so that the kernel of one chunk runs under the DMA of its neighbour; such
-                                   a transfer starts with a short chunk of 32 MiB (ends with it, for an upload).
-                                   Every DMA, the table rewrite and completion stay on the caller's stream.
-                                   1 = everything in line on the caller's stream                               */
+    uint32_t overlap_kernels;   /* staged path: 0 (the default) = kernels and DMAs of a transfer in line on the
+                                   caller's stream.  1 = a transfer of more than one chunk runs its copy kernels
+                                   on a stream of the context's own, ordered with the caller's stream by events
+                                   both ways, so that the kernel of one chunk runs under the DMA of its neighbour;
+                                   such a transfer starts with a short chunk of 32 MiB (an upload ends with it).
+                                   Every DMA, the table rewrite and completion stay on the caller's stream.  Up to
+                                   2 % faster on an otherwise idle GPU; if the runtime places that stream behind
+                                   a stream of long kernels on the same hardware queue, much slower               */
     uint32_t reserved0;         /* must be 0 */
 } tc_opts;
 

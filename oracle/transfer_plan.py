@@ -149,9 +149,10 @@ def upload_path(mode):
 
 def kernels_overlap_copies(option, n_chunks):
     """Whether a staged transfer runs its copy kernels on the engine's own stream, so that the kernel of one chunk
-    overlaps with the link copy of its neighbour: option 0 = automatic (transfers of more than one chunk: a single
-    chunk has nothing to overlap with, and the hop between streams would only delay it), 1 = never."""
-    return option == 0 and n_chunks > 1
+    overlaps with the link copy of its neighbour: option 1 asks for it, and it happens for transfers of more than
+    one chunk (a single chunk has nothing to overlap with, and the hop between streams would only delay it);
+    option 0 (the default) keeps everything in line on the caller's stream."""
+    return option == 1 and n_chunks > 1
 
 
 def plan_staged(total, slot_blocks, upload, head_blocks, overlap_option):

@@ -59,7 +59,7 @@ class tc_opts(ctypes.Structure):
         ("staging_slots", ctypes.c_uint32), ("max_grid", ctypes.c_uint32),
         ("direct_offload", ctypes.c_uint32), ("direct_upload", ctypes.c_uint32), ("direct_grid", ctypes.c_uint32),
         ("host_tail_div", ctypes.c_uint32), ("auto_direct_bytes", ctypes.c_uint64),
-        ("inline_kernels", ctypes.c_uint32), ("reserved0", ctypes.c_uint32),
+        ("overlap_kernels", ctypes.c_uint32), ("reserved0", ctypes.c_uint32),
     ]
 
 
@@ -263,12 +263,12 @@ def _stream(s):
 # ------------------------------------------------------------------ the calls
 def tc_create(kv_base, scales, num_layers, num_blocks, page_bytes, block_size_tokens, scales_per_block=0,
               host_arena_bytes=0, staging_bytes=0, staging_slots=0, max_grid=0, direct_offload=0, direct_upload=0, direct_grid=0,
-              host_tail_div=0, auto_direct_bytes=0, inline_kernels=0):
+              host_tail_div=0, auto_direct_bytes=0, overlap_kernels=0):
     """Returns (rc, ctx); ctx is an opaque handle (int) or None."""
     desc = tc_pool_desc(_ptr(kv_base), _ptr(scales), num_layers, num_blocks, page_bytes, block_size_tokens,
                         scales_per_block)
     opts = tc_opts(host_arena_bytes, staging_bytes, staging_slots, max_grid, direct_offload, direct_upload,
-                   direct_grid, host_tail_div, auto_direct_bytes, inline_kernels, 0)
+                   direct_grid, host_tail_div, auto_direct_bytes, overlap_kernels, 0)
     out = ctypes.c_void_p()
     rc = _load().tc_create(ctypes.byref(desc), ctypes.byref(opts), ctypes.byref(out))
     return rc, out.value

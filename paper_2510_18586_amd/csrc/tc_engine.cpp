@@ -168,7 +168,7 @@ try {
     const uint32_t P = 2 * pool->num_layers;
     const uint32_t S = pool->scales_per_block;
     if (opts && (opts->direct_offload > tc::kPathStaged || opts->direct_upload > tc::kPathStaged ||
-                 opts->direct_upload == tc::kPathDirectIfDuplex || opts->inline_kernels > 1 || opts->reserved0 != 0))
+                 opts->direct_upload == tc::kPathDirectIfDuplex || opts->overlap_kernels > 1 || opts->reserved0 != 0))
         return TC_ERR_INVAL;
     HipDev probe;
     if (!probe.is_device_ptr(pool->kv_base) || (S && !probe.is_device_ptr(pool->scales))) return TC_ERR_NOT_PINNED;
@@ -222,7 +222,7 @@ try {
         HIP_OR_FAIL(hipEventCreateWithFlags(&e.slots[i].ready, hipEventDisableTiming));
     }
     // the engine's own stream for the copy kernels of multi-chunk transfers; default priority, like every stream here
-    if (e.opts.inline_kernels == 0) {
+    if (e.opts.overlap_kernels == 1) {
         HIP_OR_FAIL(hipStreamCreateWithFlags(&e.kstream, hipStreamNonBlocking));
         e.has_kstream = true;
     }

@@ -9,9 +9,9 @@
 //     H2D DMA  ->  scatter_pages  (... last chunk)  ->  rewrite_table
 // or, on the direct paths, one copy kernel per agent that writes / reads the pinned host buffer itself.
 // The caller's stream is the paper's dedicated copy stream: it carries every DMA, the table rewrite and the
-// completion event; kernels of other streams overlap freely.  A staged transfer of a single chunk runs its
-// kernel on that stream too.  One of several chunks puts its copy kernels on the engine's own stream, tied to
-// the caller's by events in both directions:
+// completion event; kernels of other streams overlap freely.  By default the copy kernels run on that stream
+// too, in line with the DMAs.  With tc_opts.overlap_kernels a transfer of several chunks puts its copy kernels
+// on the engine's own stream, tied to the caller's by events in both directions:
 //     offload   caller: ids, entry event ............ wait ready[c], DMA c, record last[c] ...... done
 //               engine: wait entry; per chunk c: wait last[slot], gather c, record ready[c]
 //     upload    caller: ids; per chunk c: wait last[slot], DMA c, record ready[c] .... wait last[final], tables, done
@@ -395,7 +395,7 @@ public:
         auto enqueue = [&]() -> int {
             bool overlapped = false;
             const std::vector<uint32_t> chunks =
-                plan_staged(plan.total, slot_blocks, false, head_blocks_of(rec), has_kstream ? opts.inline_kernels : 1, &overlapped);
+                plan_staged(plan.total, slot_blocks, false, head_blocks_of(rec), has_kstream ? opts.overlap_kernels : 0, &overlapped);
             const uint32_t div = tail_divisor(opts.host_tail_div, chunks.size(), overlapped);
             const Stream ks = overlapped ? kstream : stream;
             if (overlapped) {
@@ -485,7 +485,7 @@ public:
         auto enqueue = [&]() -> int {
             bool overlapped = false;
             const std::vector<uint32_t> chunks =
-                plan_staged(plan.total, slot_blocks, true, head_blocks_of(rec), has_kstream ? opts.inline_kernels : 1, &overlapped);
+                plan_staged(plan.total, slot_blocks, true, head_blocks_of(rec), has_kstream ? opts.overlap_kernels : 0, &overlapped);
             const uint32_t div = tail_divisor(opts.host_tail_div, chunks.size(), overlapped);
             const Stream ks = overlapped ? kstream : stream;
             if (overlapped) {

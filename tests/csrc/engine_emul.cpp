@@ -418,13 +418,13 @@ void round_trip(Shape sh, tc_opts opts, uint32_t n_slots, uint32_t slot_blocks, 
 
 // Every fallible device call of one transfer fails in turn; afterwards nothing the stream may still read has
 // been given away, and the engine works on.
-void failures(bool upload, uint32_t mode, bool records_fail, uint32_t inline_kernels, uint32_t seed)
+void failures(bool upload, uint32_t mode, bool records_fail, uint32_t overlap_kernels, uint32_t seed)
 {
     const Shape sh{2, 4096 + 1024, 40, 4};
     tc_opts opts{};
     opts.direct_offload = opts.direct_upload = mode;
     opts.host_tail_div = 2;
-    opts.inline_kernels = inline_kernels;
+    opts.overlap_kernels = overlap_kernels;
     const uint32_t n = 7;
     long calls_of_a_good_transfer = 0;
     int held = 0, rolled_back = 0;
@@ -594,13 +594,13 @@ void hazards_are_waited_for()
 // Several transfers in flight at once on two callers' streams, sharing few small staging slots: slot reuse
 // across transfers and streams, kernels on the engine's stream, and the order of a host buffer's writer and
 // reader on different streams are all left to events.
-void transfers_in_flight_together(uint32_t inline_kernels, uint32_t n_slots, uint32_t seed)
+void transfers_in_flight_together(uint32_t overlap_kernels, uint32_t n_slots, uint32_t seed)
 {
     std::mt19937 rng(seed);
     const Shape sh{2, 4096 + 512, 96, 4};
     tc_opts opts{};
     opts.direct_offload = opts.direct_upload = tc::kPathStaged;
-    opts.inline_kernels = inline_kernels;
+    opts.overlap_kernels = overlap_kernels;
     opts.host_tail_div = seed % 2 ? 1 : 3;
     Rig r(sh, opts, n_slots, 3, 64, rng);
     auto &e = r.e;
@@ -641,7 +641,7 @@ void transfers_in_flight_together(uint32_t inline_kernels, uint32_t n_slots, uin
     REQUIRE(std::memcmp(mirror_scales.data(), r.scales.get(), mirror_scales.size() * 4) == 0);
     tc_stats_t st;
     e.fill_stats(&st);
-    if (inline_kernels == 0) REQUIRE(st.transfers_overlapped > 0 && r.dev.ran_on_engine_stream > 0);
+    if (overlap_kernels == 1) REQUIRE(st.transfers_overlapped > 0 && r.dev.ran_on_engine_stream > 0);
     else REQUIRE(st.transfers_overlapped == 0 && r.dev.ran_on_engine_stream == 0);
 }
 
@@ -652,6 +652,7 @@ void which_transfers_overlap()
     const Shape sh{1, 1 << 20, 80, 0};                 // 2 MiB records: the short chunk is 16 blocks
     tc_opts opts{};
     opts.direct_offload = opts.direct_upload = tc::kPathStaged;
+    opts.overlap_kernels = 1;
     Rig r(sh, opts, 2, 40, 80, rng);
     auto &e = r.e;
     std::vector<int32_t> ids(80);
@@ -698,6 +699,7 @@ void all_tests()
                 opts.host_tail_div = variant == 3 ? 2 : (variant == 2 ? 1 : 0);
                 opts.direct_grid = variant == 2 ? 3 : 0;
                 opts.auto_direct_bytes = variant == 1 ? (1ull << 40) : 0;         // automatic, and everything is "small"
+                opts.overlap_kernels = (variant + mode) % 2;                        // copy kernels on the engine's stream, or in line
                 const uint32_t slot_blocks = variant == 0 ? 64 : 3 + variant;     // one chunk, or several
                 round_trip(sh, opts, 1 + variant % 3, std::min(slot_blocks, sh.NB), ++seed);
             }
@@ -706,13 +708,13 @@ void all_tests()
     for (bool upload : {false, true})
         for (uint32_t mode : {tc::kPathStaged, tc::kPathDirect})
             for (bool records_fail : {false, true})
-                for (uint32_t inline_kernels : {0u, 1u}) failures(upload, mode, records_fail, inline_kernels, 9);
+                for (uint32_t overlap_kernels : {0u, 1u}) failures(upload, mode, records_fail, overlap_kernels, 9);
     validation();
     hazards_are_waited_for();
     which_transfers_overlap();
-    for (uint32_t inline_kernels : {0u, 1u})
+    for (uint32_t overlap_kernels : {0u, 1u})
         for (uint32_t n_slots : {1u, 2u, 3u})
-            for (uint32_t seed = 0; seed < 6; ++seed) transfers_in_flight_together(inline_kernels, n_slots, 40 + seed);
+            for (uint32_t seed = 0; seed < 6; ++seed) transfers_in_flight_together(overlap_kernels, n_slots, 40 + seed);
 }
 
 int main()

@@ -66,7 +66,7 @@ def test_null_arguments_are_rejected_without_a_gpu():
     assert K.tc_create(0x1000, None, 1 << 19, 4096, 16, 1)[0] == K.TC_ERR_INVAL
     assert K.tc_create(0x1000, None, 2, 16, 4096, 16, direct_offload=4)[0] == K.TC_ERR_INVAL
     assert K.tc_create(0x1000, None, 2, 16, 4096, 16, direct_upload=2)[0] == K.TC_ERR_INVAL
-    assert K.tc_create(0x1000, None, 2, 16, 4096, 16, inline_kernels=2)[0] == K.TC_ERR_INVAL
+    assert K.tc_create(0x1000, None, 2, 16, 4096, 16, overlap_kernels=2)[0] == K.TC_ERR_INVAL
     assert K.tc_create(0x1010, None, 2, 16, 4096, 16)[0] == K.TC_ERR_INVAL          # base not 256-B aligned
     assert K.tc_create(0x1000, None, 2, 16, 4100, 16)[0] == K.TC_ERR_INVAL          # page not a multiple of 16
     assert K.tc_destroy(None) == K.TC_OK

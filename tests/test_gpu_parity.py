@@ -88,15 +88,15 @@ def test_config1_tiny_same_ids():
     _round_trip_case(W.CONFIGS[0], 0, 8, salt=1, same_ids=True)
 
 
-@pytest.mark.parametrize("inline_kernels", [0, 1], ids=["kernels-on-the-engines-stream", "in-line"])
+@pytest.mark.parametrize("overlap_kernels", [0, 1], ids=["in-line", "kernels-on-the-engines-stream"])
 @pytest.mark.parametrize("slots", [1, 3])
-def test_8b_pages_many_chunks_ragged_tail(slots, inline_kernels):
-    # 8B-shaped pages (32 KiB, 64 planes); staging slots of 5 records -> 8 chunks, the last one ragged; the copy
-    # kernels on the context's own stream under the DMAs of their neighbours (one slot: strictly taking turns), or
-    # everything in line on the caller's stream
+def test_8b_pages_many_chunks_ragged_tail(slots, overlap_kernels):
+    # 8B-shaped pages (32 KiB, 64 planes); staging slots of 5 records -> 8 chunks, the last one ragged; everything
+    # in line on the caller's stream, or the copy kernels on the context's own stream under the DMAs of their
+    # neighbours (with one slot: strictly taking turns)
     shape = W.CONFIGS[1].with_blocks(96)
     _round_trip_case(shape, 1, 37, salt=slots, staging_bytes=slots * 5 * 2 * 1024 * 1024, staging_slots=slots,
-                     inline_kernels=inline_kernels)
+                     overlap_kernels=overlap_kernels)
 
 
 @pytest.mark.parametrize("div,slots", [(2, 1), (4, 2), (5, 3)])
@@ -169,7 +169,7 @@ def _random_case(k):
     if rng.random() < 0.5:
         opts["host_tail_div"] = int(rng.choice([2, 3, 4, 8]))
     if rng.random() < 0.4:
-        opts["inline_kernels"] = 1
+        opts["overlap_kernels"] = 1
     return shape, n, opts
 
 
@@ -200,7 +200,7 @@ def test_zero_blocks_is_a_no_op():
     _round_trip_case(W.CONFIGS[0], 0, 0, salt=3)
 
 
-@pytest.mark.parametrize("host_tail_div,paths", [(1, "staged"), (64, "staged"), (0, "auto"), (1, "staged-in-line")])
+@pytest.mark.parametrize("host_tail_div,paths", [(1, "staged"), (64, "staged"), (0, "auto"), (1, "staged-overlapped")])
 def test_config2_full_size_llama3_8b(host_tail_div, paths):
     """32 layers x 8 heads x 128 x 16 tokens bf16 (2 MiB per block), 16 384 blocks (32 GiB), one agent
     with a 4 096-token context = 256 blocks scattered uniformly; default launch configuration, and the
@@ -212,8 +212,8 @@ def test_config2_full_size_llama3_8b(host_tail_div, paths):
     ids = W.pick_ids(rng, NB, n)
     new_ids = W.pick_ids(rng, NB, n, exclude=ids)
     path = {} if paths == "auto" else dict(direct_offload=K.TC_PATH_STAGED, direct_upload=K.TC_PATH_STAGED)
-    if paths == "staged-in-line":
-        path["inline_kernels"] = 1
+    if paths == "staged-overlapped":
+        path["overlap_kernels"] = 1
     gp = GpuPool(shape, seed=W.seed_for(1), host_tail_div=host_tail_div, **path)
     try:
         rec = gp.rec

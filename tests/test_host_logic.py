@@ -402,7 +402,7 @@ def test_chunks_pieces_tail_and_paths_match_the_model(shim):
         opt, nch = int(rng.choice([0, 1, 2, 48])), int(rng.integers(1, 5))
         ov = int(rng.integers(0, 2))
         assert lib.tcp_tail_divisor(opt, nch, ov) == T.tail_divisor(opt, nch, bool(ov))
-        assert bool(lib.tcp_kernels_overlap(opt if opt < 2 else 0, nch)) == T.kernels_overlap_copies(opt if opt < 2 else 0, nch)
+        assert bool(lib.tcp_kernels_overlap(opt if opt < 2 else 1, nch)) == T.kernels_overlap_copies(opt if opt < 2 else 1, nch)
 
 
 def test_engine_on_a_cpu_stand_in_under_sanitizers(tmp_path):

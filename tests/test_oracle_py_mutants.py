@@ -108,8 +108,8 @@ CASES = {
         "uploads are staged unless forced": ("return STAGED if mode == PATH_STAGED else DIRECT", "return DIRECT if mode == PATH_DIRECT else STAGED"),
         "a single chunk gets a tail": ("return auto_div if (n_chunks > 1 and not overlapped) else 0", "return auto_div if not overlapped else 0"),
         "overlapped transfers get a tail too": ("return auto_div if (n_chunks > 1 and not overlapped) else 0", "return auto_div if n_chunks > 1 else 0"),
-        "a single chunk hops between streams": ("return option == 0 and n_chunks > 1", "return option == 0"),
-        "overlap cannot be switched off": ("return option == 0 and n_chunks > 1", "return n_chunks > 1"),
+        "a single chunk hops between streams": ("return option == 1 and n_chunks > 1", "return option == 1"),
+        "overlap without being asked for": ("return option == 1 and n_chunks > 1", "return n_chunks > 1"),
         "a transfer in line keeps its head": ("    return plan_chunks(total, slot_blocks, upload, 0), False", "    return sizes, False"),
         "short lists get a head too": ("if head > 0 and left > 2 * head:", "if head > 0 and left > head:"),
         "a head may be longer than a slot": ("head = min(int(head_blocks), int(slot_blocks))", "head = int(head_blocks)"),

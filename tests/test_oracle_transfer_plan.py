@@ -101,12 +101,12 @@ def test_chunks_with_a_short_first_chunk():
 
 
 def test_a_staged_transfer_overlaps_only_if_there_is_something_to_overlap():
-    assert T.plan_staged(4, 8, False, 2, 0) == ([4], False)              # at most twice the head: one chunk, in line
-    assert T.plan_staged(5, 8, False, 2, 0) == ([2, 3], True) and T.plan_staged(5, 8, True, 2, 0) == ([3, 2], True)
-    assert T.plan_staged(5, 8, False, 2, 1) == ([5], False)              # switched off: the plain cut
-    assert T.plan_staged(20, 8, False, 2, 1) == ([8, 8, 4], False) and T.plan_staged(20, 8, True, 2, 0) == ([2, 8, 8, 2], True)
-    assert T.plan_staged(20, 8, False, 0, 0) == ([8, 8, 4], True) and T.plan_staged(8, 8, False, 0, 0) == ([8], False)
-    assert T.plan_staged(0, 8, False, 2, 0) == ([], False)
+    assert T.plan_staged(4, 8, False, 2, 1) == ([4], False)              # at most twice the head: one chunk, in line
+    assert T.plan_staged(5, 8, False, 2, 1) == ([2, 3], True) and T.plan_staged(5, 8, True, 2, 1) == ([3, 2], True)
+    assert T.plan_staged(5, 8, False, 2, 0) == ([5], False)              # not asked for: the plain cut
+    assert T.plan_staged(20, 8, False, 2, 0) == ([8, 8, 4], False) and T.plan_staged(20, 8, True, 2, 1) == ([2, 8, 8, 2], True)
+    assert T.plan_staged(20, 8, False, 0, 1) == ([8, 8, 4], True) and T.plan_staged(8, 8, False, 0, 1) == ([8], False)
+    assert T.plan_staged(0, 8, False, 2, 1) == ([], False)
 
 
 def test_pieces_carry_every_record_once():
@@ -204,8 +204,8 @@ def test_paths_truth_table():
     # kernels on their own stream already keep the link busy: no automatic tail then, an explicit one stays
     assert T.tail_divisor(0, 2, overlapped=True) == 0 and T.tail_divisor(0, 9, True) == 0
     assert T.tail_divisor(16, 2, overlapped=True) == 16 and T.tail_divisor(1, 2, True) == 0
-    assert [T.kernels_overlap_copies(0, n) for n in (1, 2, 7)] == [False, True, True]
-    assert [T.kernels_overlap_copies(1, n) for n in (1, 2, 7)] == [False, False, False]
+    assert [T.kernels_overlap_copies(1, n) for n in (1, 2, 7)] == [False, True, True]
+    assert [T.kernels_overlap_copies(0, n) for n in (1, 2, 7)] == [False, False, False]
 
 
 # ---------------------------------------------------------------- what a failed enqueue keeps
