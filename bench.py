@@ -36,6 +36,9 @@ def parse():
     ap.add_argument("--tokens", type=int, default=4096, help="context length of the agent")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-configs", action="store_true", help="skip the other four configurations")
+    ap.add_argument("--no-overlapped", action="store_true",
+                    help="leave the overlap_kernels extras out (under rocprofv3 their kernels run next to the profiler's blit "
+                         "copies, which says nothing about them and blurs the per-kernel statistics)")
     ap.add_argument("--config", type=int, default=0, choices=[0, 1, 3, 4, 5],
                     help="run only this one of the other configurations and print its object (for profiler runs)")
     return ap.parse_args()
@@ -312,6 +315,9 @@ def config1(torch, K, W, link):
     return out
 
 
+WITH_OVERLAPPED = True      # cleared by --no-overlapped
+
+
 def config3(torch, K, W, link, pool):
     """64 agents of the 8B shape in a fragmented pool, as one batch; alone, next to a memory-bound neighbour on
     another stream, and half of them going out while the other half comes back."""
@@ -320,7 +326,7 @@ def config3(torch, K, W, link, pool):
     tokens = W.lognormal_contexts(rng, 64)
     nblk = W.blocks_of(tokens, shape.block_size).astype(int)
     total = int(nblk.sum())
-    two = TwoContexts(torch, K, shape, pool, None, total + 8, overlapped=True)
+    two = TwoContexts(torch, K, shape, pool, None, total + 8, overlapped=WITH_OVERLAPPED)
 
     class B:
         def alloc(self, n):
@@ -396,17 +402,18 @@ def config3(torch, K, W, link, pool):
 
     # the same next to the neighbour with the copy kernels on the context's own stream (overlap_kernels = 1): what
     # happens depends on which hardware queue the runtime gives that stream
-    for s in src:
-        K.check(K.tc_free(two.auto, s))
-        K.check(K.tc_alloc_at(two.overlapped, s))
-    so = out["staged_overlapped"]
-    off_ov2, tri_off2 = overlapped(lambda: K.check(K.tc_offload_batch(two.overlapped, items_out, copy)), so["offload_ms"], two.overlapped)
-    out["next_to_a_memory_bound_kernel"]["staged_overlapped"] = {
-        "offload_GBps": round(payload / off_ov2 / 1e6, 3), "offload_change_pct": round(100 * (so["offload_ms"] / off_ov2 - 1), 2),
-        "neighbour_during_offload_GBps": round(tri_bytes / tri_off2 / 1e6, 1)}
-    for s in src:
-        K.check(K.tc_free(two.overlapped, s))
-        K.check(K.tc_alloc_at(two.auto, s))
+    if two.overlapped:
+        for s in src:
+            K.check(K.tc_free(two.auto, s))
+            K.check(K.tc_alloc_at(two.overlapped, s))
+        so = out["staged_overlapped"]
+        off_ov2, tri_off2 = overlapped(lambda: K.check(K.tc_offload_batch(two.overlapped, items_out, copy)), so["offload_ms"], two.overlapped)
+        out["next_to_a_memory_bound_kernel"]["staged_overlapped"] = {
+            "offload_GBps": round(payload / off_ov2 / 1e6, 3), "offload_change_pct": round(100 * (so["offload_ms"] / off_ov2 - 1), 2),
+            "neighbour_during_offload_GBps": round(tri_bytes / tri_off2 / 1e6, 1)}
+        for s in src:
+            K.check(K.tc_free(two.overlapped, s))
+            K.check(K.tc_alloc_at(two.auto, s))
 
     # half of the agents go out while the other half comes back, on two streams
     dup = {}
@@ -478,7 +485,7 @@ def config5(torch, K, W, link):
     private = (W.blocks_of(tokens, shape.block_size) - 32).astype(int)
     bound = shape.planes * shape.page_bytes + 4 * shape.scales_per_block + 256      # what a record can take at most
     arena_blocks = budget // bound
-    two = TwoContexts(torch, K, shape, pool, scales.view(torch.int32), arena_blocks, overlapped=True)
+    two = TwoContexts(torch, K, shape, pool, scales.view(torch.int32), arena_blocks, overlapped=WITH_OVERLAPPED)
     wave = []
     for n in private:                 # agents in index order while the arena has room
         if sum(wave) + n + 8 > arena_blocks:
@@ -586,6 +593,8 @@ def main():
     import paper_2510_18586_amd as K
     import tc_workloads as W
 
+    global WITH_OVERLAPPED
+    WITH_OVERLAPPED = not args.no_overlapped
     if args.config:
         stream = torch.cuda.Stream()
         link = pinned_link_peak(torch, 512 << 20, stream)
@@ -717,10 +726,12 @@ def main():
     out["direct_paths"] = variant(torch, K, pool, shape, pairs, link,
                                   "direct_offload = direct_upload = TC_PATH_DIRECT (6 / 16 workgroups): no staging, no DMA",
                                   direct_offload=K.TC_PATH_DIRECT, direct_upload=K.TC_PATH_DIRECT)[0]
-    out["staged_overlapped"] = variant(torch, K, pool, shape, pairs, link,
-                                       "two-stage path with overlap_kernels = 1: a short first chunk (32 MiB), then the rest, the copy "
-                                       "kernels on the context's own stream under the DMA of the neighbouring chunk",
-                                       direct_offload=K.TC_PATH_STAGED, direct_upload=K.TC_PATH_STAGED, host_tail_div=1, overlap_kernels=1)[0]
+    if WITH_OVERLAPPED:
+        out["staged_overlapped"] = variant(torch, K, pool, shape, pairs, link,
+                                           "two-stage path with overlap_kernels = 1: a short first chunk (32 MiB), then the rest, the "
+                                           "copy kernels on the context's own stream under the DMA of the neighbouring chunk",
+                                           direct_offload=K.TC_PATH_STAGED, direct_upload=K.TC_PATH_STAGED, host_tail_div=1,
+                                           overlap_kernels=1)[0]
     out["host_tail"] = variant(torch, K, pool, shape, pairs, link,
                                "staged both ways with host_tail_div = 64: the last 1/64 of the chunk crosses the link inside "
                                "the copy launch; the launches get longer, the transfer shorter",
