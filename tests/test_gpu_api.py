@@ -117,9 +117,9 @@ def test_pending_free_blocks_are_not_handed_out_while_the_copy_runs():
         gp.close()
 
 
-@pytest.mark.parametrize("direct,tail", [(3, 1), (1, 0), (3, 2), (3, 4), (0, 0)],
-                         ids=["staged", "direct", "staged-tail2", "staged-tail4", "auto"])
-def test_batch_of_agents_shares_chunks(direct, tail):
+@pytest.mark.parametrize("direct,tail,overlap_kernels", [(3, 1, 0), (1, 0, 0), (3, 2, 0), (3, 4, 0), (0, 0, 0), (3, 1, 1), (3, 4, 1)],
+                         ids=["staged", "direct", "staged-tail2", "staged-tail4", "auto", "staged-overlapped", "staged-tail4-overlapped"])
+def test_batch_of_agents_shares_chunks(direct, tail, overlap_kernels):
     rng = W.rng_for(2, salt=3)
     shape = W.CONFIGS[1].with_blocks(128)
     L, NB, pb, P = shape.num_layers, shape.num_blocks, shape.page_bytes, shape.planes
@@ -131,7 +131,8 @@ def test_batch_of_agents_shares_chunks(direct, tail):
     # staging: 3 slots of 4 records, so chunks straddle agents
     gp = GpuPool(shape, pool_h, None, staging_bytes=3 * 4 * 2 * 1024 * 1024, staging_slots=3,
                  host_arena_bytes=40 * 2 * 1024 * 1024, direct_offload=direct, direct_upload=direct,
-                 host_tail_div=tail)      # chunk tails inside one agent's buffer skip staging, the others do not
+                 host_tail_div=tail,      # chunk tails inside one agent's buffer skip staging, the others do not
+                 overlap_kernels=overlap_kernels)
     try:
         rec = gp.rec
         bufs = []
@@ -304,7 +305,8 @@ def test_calibrated_cost_model_predicts_a_transfer_and_leaves_the_pool_alone():
         gp.close()
 
 
-def test_whole_pool_moves_in_one_call_over_many_chunks():
+@pytest.mark.parametrize("overlap_kernels", [0, 1], ids=["in-line", "kernels-on-the-engines-stream"])
+def test_whole_pool_moves_in_one_call_over_many_chunks(overlap_kernels):
     """Maximum size: every block of the pool is a source, then a destination (reversed order)."""
     rng = W.rng_for(1, salt=31)
     shape = W.CONFIGS[1].with_blocks(160)                       # 320 MiB pool
@@ -312,7 +314,7 @@ def test_whole_pool_moves_in_one_call_over_many_chunks():
     pool_h = W.make_pool_host(shape, rng)
     ids = rng.permutation(NB).astype(np.int32)
     gp = GpuPool(shape, pool_h, None, staging_bytes=2 * 7 * 2 * 1024 * 1024, staging_slots=2,   # 7 records per chunk
-                 direct_offload=K.TC_PATH_STAGED, direct_upload=K.TC_PATH_STAGED)
+                 direct_offload=K.TC_PATH_STAGED, direct_upload=K.TC_PATH_STAGED, overlap_kernels=overlap_kernels)
     try:
         host = pinned_bytes(NB * gp.rec)
         rc, got = K.tc_alloc(gp.ctx, NB)
@@ -337,7 +339,8 @@ def test_whole_pool_moves_in_one_call_over_many_chunks():
         gp.close()
 
 
-def test_two_streams_share_one_staging_slot():
+@pytest.mark.parametrize("overlap_kernels", [0, 1], ids=["in-line", "kernels-on-the-engines-stream"])
+def test_two_streams_share_one_staging_slot(overlap_kernels):
     """An offload and an upload of different agents issued back to back on different streams must not
     trample each other's chunk in the single staging slot."""
     rng = W.rng_for(1, salt=32)
@@ -347,7 +350,7 @@ def test_two_streams_share_one_staging_slot():
     perm = W.pick_ids(rng, NB, 90)
     a_src, b_src, b_dst = perm[:30], perm[30:60], perm[60:90]
     gp = GpuPool(shape, pool_h, None, staging_bytes=4 * 2 * 1024 * 1024, staging_slots=1,       # 4 records per chunk
-                 direct_offload=K.TC_PATH_STAGED, direct_upload=K.TC_PATH_STAGED)
+                 direct_offload=K.TC_PATH_STAGED, direct_upload=K.TC_PATH_STAGED, overlap_kernels=overlap_kernels)
     try:
         rec = gp.rec
         s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
@@ -372,7 +375,8 @@ def test_two_streams_share_one_staging_slot():
         gp.close()
 
 
-def test_calls_from_several_host_threads():
+@pytest.mark.parametrize("overlap_kernels", [0, 1], ids=["in-line", "kernels-on-the-engines-stream"])
+def test_calls_from_several_host_threads(overlap_kernels):
     """The context serialises callers: four threads, each with its own stream and agent."""
     import threading
     rng = W.rng_for(1, salt=33)
@@ -381,7 +385,8 @@ def test_calls_from_several_host_threads():
     pool_h = W.make_pool_host(shape, rng)
     perm = W.pick_ids(rng, NB, 4 * 2 * 24)
     gp = GpuPool(shape, pool_h, None, staging_bytes=2 * 8 * 2 * 1024 * 1024, staging_slots=2,
-                 host_arena_bytes=100 * 2 * 1024 * 1024, direct_offload=K.TC_PATH_STAGED, direct_upload=K.TC_PATH_STAGED)
+                 host_arena_bytes=100 * 2 * 1024 * 1024, direct_offload=K.TC_PATH_STAGED, direct_upload=K.TC_PATH_STAGED,
+                 overlap_kernels=overlap_kernels)
     try:
         rec = gp.rec
         K.check(K.tc_alloc_at(gp.ctx, perm))
