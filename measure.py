@@ -280,52 +280,57 @@ class _LinkWatch:
 
 
 def m_dma_spread(torch, K, W, emit, reps=24):
-    """Staged transfers of 1 006 records of 4 MiB (eight chunks each way), one after the other with nothing else
-    on the GPU: the copy engine's rate per transfer, from the event pairs the library puts around each chunk, and
-    what the driver said about the PCIe link meanwhile."""
+    """Staged transfers of 1 006 records of 4 MiB, one after the other with nothing else on the GPU, through a
+    context with 512 MiB staging slots (eight chunks, eight DMAs each way) and through one with the default 4 GiB
+    slots (one chunk, one DMA): the copy engine's rate per transfer, from the event pairs the library puts around
+    each chunk, and what the driver said about the PCIe link meanwhile.  A DMA enqueued while the previous one of
+    the stream is still running is now and then carried out at about half rate; a single DMA never was."""
     shape = W.CONFIGS[3]
     n = 1006
-    c = Ctx(torch, K, W, shape, 3, n + 2, fill=False, direct_offload=K.TC_PATH_STAGED, direct_upload=K.TC_PATH_STAGED,
-            host_tail_div=1)
+    staged = dict(direct_offload=K.TC_PATH_STAGED, direct_upload=K.TC_PATH_STAGED, host_tail_div=1)
+    one = Ctx(torch, K, W, shape, 3, n + 2, fill=False, **staged)                          # default slots: one chunk
+    rec = one.rec
+    eight = Ctx(torch, K, W, shape, 3, 0, pool=one.pool, staging_bytes=2 * 128 * rec, staging_slots=2, **staged)
     ids = W.pick_ids(W.rng_for(3, salt=62), shape.num_blocks, n)
-    K.check(K.tc_alloc_at(c.ctx, ids))
-    rc, buf = K.tc_host_alloc(c.ctx, n)
+    rc, buf = K.tc_host_alloc(one.ctx, n)
     K.check(rc)
     stream = torch.cuda.Stream()
-    K.check(K.tc_set_profiling(c.ctx, 1))
     watch = _LinkWatch()
-
-    def host_cpu_ticks():
-        # busy and total jiffies of the whole host (other tenants included), from /proc/stat
-        with open("/proc/stat") as f:
-            v = [int(x) for x in f.readline().split()[1:9]]
-        return sum(v) - v[3] - v[4], sum(v)
-
-    rows, prev = [], K.tc_stats(c.ctx)[1]
+    out = {}
+    for name, c in (("eight_chunks", eight), ("one_chunk", one)):
+        K.check(K.tc_alloc_at(c.ctx, ids))
+        K.check(K.tc_set_profiling(c.ctx, 1))
+    prev = {id(c): K.tc_stats(c.ctx)[1] for c in (eight, one)}
+    rows = {"eight_chunks": [], "one_chunk": []}
     for r in range(reps):
-        busy0, all0 = host_cpu_ticks()
         if r % 3 == 2:
             time.sleep(0.5)                  # an idle gap, as between the agents of a trace
-        with watch:
-            off = _events(torch, stream, lambda: K.check(K.tc_offload(c.ctx, ids, buf, stream)),
-                          after=lambda: K.check(K.tc_sync(c.ctx)), reps=1, warm=0)[0]
-        link_off = list(watch.seen)
-        with watch:
-            up = _events(torch, stream, lambda: K.check(K.tc_upload(c.ctx, buf, ids, None, stream)),
-                         after=lambda: K.check(K.tc_sync(c.ctx)), reps=1, warm=0)[0]
-        st = K.tc_stats(c.ctx)[1]
-        rows.append(dict(rep=r, after_idle_gap=(r % 3 == 2),
-                         offload_GBps=round(n * c.rec / off / 1e6, 2), upload_GBps=round(n * c.rec / up / 1e6, 2),
-                         d2h_dma_GBps=round((st.d2h_bytes - prev.d2h_bytes) / max(st.d2h_ms - prev.d2h_ms, 1e-9) / 1e6, 2),
-                         h2d_dma_GBps=round((st.h2d_bytes - prev.h2d_bytes) / max(st.h2d_ms - prev.h2d_ms, 1e-9) / 1e6, 2),
-                         link_during_offload=link_off, link_during_upload=list(watch.seen),
-                         host_cpus_busy=round((host_cpu_ticks()[0] - busy0) / max(1, host_cpu_ticks()[1] - all0) * (os.cpu_count() or 1), 1)))
-        prev = st
-    emit(dict(measurement="dma_spread", shape=shape.name, blocks=n, GiB=n * c.rec / 2 ** 30, chunks_each_way=8,
-              link_files=watch.paths, rows=rows))
-    K.check(K.tc_free(c.ctx, ids))
-    K.check(K.tc_host_free(c.ctx, buf))
-    c.close()
+        for name, c in (("eight_chunks", eight), ("one_chunk", one)):      # in turn, so that both see the same moments
+            with watch:
+                off = _events(torch, stream, lambda: K.check(K.tc_offload(c.ctx, ids, buf, stream)),
+                              after=lambda: K.check(K.tc_sync(c.ctx)), reps=1, warm=0)[0]
+            link_off = list(watch.seen)
+            with watch:
+                up = _events(torch, stream, lambda: K.check(K.tc_upload(c.ctx, buf, ids, None, stream)),
+                             after=lambda: K.check(K.tc_sync(c.ctx)), reps=1, warm=0)[0]
+            st, p = K.tc_stats(c.ctx)[1], prev[id(c)]
+            rows[name].append(dict(rep=r, after_idle_gap=(r % 3 == 2),
+                                   offload_GBps=round(n * rec / off / 1e6, 2), upload_GBps=round(n * rec / up / 1e6, 2),
+                                   d2h_dma_GBps=round((st.d2h_bytes - p.d2h_bytes) / max(st.d2h_ms - p.d2h_ms, 1e-9) / 1e6, 2),
+                                   h2d_dma_GBps=round((st.h2d_bytes - p.h2d_bytes) / max(st.h2d_ms - p.h2d_ms, 1e-9) / 1e6, 2),
+                                   dmas_each_way=int(st.d2h_copies - p.d2h_copies),
+                                   link_during_offload=link_off, link_during_upload=list(watch.seen)))
+            prev[id(c)] = st
+    for name, v in rows.items():
+        rates = [x for r_ in v for x in (r_["offload_GBps"], r_["upload_GBps"])]
+        out[name] = dict(transfers=len(rates), below_50_GBps=sum(x < 50 for x in rates), slowest_GBps=min(rates),
+                         median_GBps=float(np.median(rates)), rows=v)
+    emit(dict(measurement="dma_spread", shape=shape.name, blocks=n, GiB=n * rec / 2 ** 30, link_files=watch.paths, **out))
+    for c in (eight, one):
+        K.check(K.tc_free(c.ctx, ids))
+    K.check(K.tc_host_free(one.ctx, buf))
+    K.check(K.tc_destroy(eight.ctx))
+    one.close()
 
 
 def m_sweep(torch, K, W, emit):

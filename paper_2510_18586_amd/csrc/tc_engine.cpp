@@ -16,7 +16,15 @@
 
 namespace {
 
-constexpr uint64_t kDefaultSlotBytes = 512ull << 20;
+// A staging slot holds what one DMA carries.  4 GiB (8 GiB of staging out of 288 GB) makes one agent one chunk
+// and one DMA in every shape this was measured on (a 32k-token context of an 8B model, 16k tokens of a 32B one).
+// That matters beyond launch counts: a hipMemcpyAsync that is enqueued while the previous copy of the stream is
+// still running, with a kernel in between, now and then runs at about half the link's rate (31-46 GB/s instead of 57;
+// 3.9 GiB transfers in eight chunks: roughly every second repetition on some machines).  With the host waiting for
+// the previous chunk's DMA before enqueueing the next, 72 of 72 such transfers ran at full rate, and so did every
+// single-chunk transfer ever measured; the runtime picks its copy engine at enqueue time by what is busy then.
+// An asynchronous call cannot wait, so the library keeps the number of DMAs per transfer small instead.
+constexpr uint64_t kDefaultSlotBytes = 4096ull << 20;
 constexpr uint32_t kDefaultSlots = 2;
 
 bool report(hipError_t e, const char *what)

@@ -22,10 +22,10 @@ def _stats(gp):
 
 
 def _staged_launches(n, rec, num_blocks, overlap_kernels=0):
-    """How many copy launches a staged transfer of n records takes (512 MiB slots; with overlap_kernels a short
+    """How many copy launches a staged transfer of n records takes (4 GiB slots; with overlap_kernels a short
     first chunk of 32 MiB for transfers that have something to overlap), from the planning model."""
     from oracle import transfer_plan as T
-    return len(T.plan_staged(n, min((512 << 20) // rec, num_blocks), False, max(1, (32 << 20) // rec), overlap_kernels)[0])
+    return len(T.plan_staged(n, min((4096 << 20) // rec, num_blocks), False, max(1, (32 << 20) // rec), overlap_kernels)[0])
 
 
 def test_validation_errors_have_no_effect():
