@@ -599,3 +599,36 @@ def test_the_librarys_own_choice_of_path():
                 mirror.close()
                 mirror = None
             gp.close()
+
+
+def test_an_agent_of_4_GiB_is_one_launch_and_one_dma_by_default():
+    """The default staging slot holds 4 GiB of records: the largest agent of the config-4 trace (1 006 blocks of
+    4 MiB) goes out and comes back as one chunk (a DMA enqueued behind a running one is what the runtime sometimes
+    carries out at half rate; a single DMA never was)."""
+    shape = W.CONFIGS[3].with_blocks(1100)
+    gp = GpuPool(shape, seed=41, direct_offload=K.TC_PATH_STAGED, direct_upload=K.TC_PATH_STAGED)
+    try:
+        n, rec = 1006, gp.rec
+        rng = W.rng_for(3, salt=41)
+        ids = W.pick_ids(rng, shape.num_blocks, n)
+        K.check(K.tc_alloc_at(gp.ctx, ids))
+        K.check(K.tc_set_profiling(gp.ctx, 1))
+        host = pinned_bytes(n * rec)
+        stream = torch.cuda.Stream()
+        sig = gp.block_checksums(ids)
+        K.check(K.tc_offload(gp.ctx, ids, host, stream))
+        K.check(K.tc_sync(gp.ctx))
+        # a few records against the oracle's definition, page by page (the whole agent is compared in the config-4 test)
+        P, pb = shape.planes, shape.page_bytes
+        pool_v = gp.pool.view(P, shape.num_blocks, pb)
+        for j in (0, 1, 517, n - 1):
+            want = pool_v[:, int(ids[j]), :].reshape(-1).cpu()
+            assert torch.equal(host[j * rec: j * rec + P * pb], want)
+        K.check(K.tc_upload(gp.ctx, host, ids, None, stream))
+        K.check(K.tc_sync(gp.ctx))
+        assert torch.equal(gp.block_checksums(ids), sig)
+        st = _stats(gp)
+        assert (st.gather_launches, st.d2h_copies, st.h2d_copies, st.scatter_launches) == (1, 1, 1, 1)
+        assert st.d2h_bytes == n * rec and st.transfers_overlapped == 0
+    finally:
+        gp.close()
