@@ -78,8 +78,9 @@ enum { TC_PATH_AUTO = 0, TC_PATH_DIRECT = 1, TC_PATH_DIRECT_IF_DUPLEX = 2, TC_PA
 typedef struct {
     uint64_t host_arena_bytes;  /* pinned arena, allocated once; 0 = none (caller brings buffers)  */
     uint64_t staging_bytes;     /* device staging ring in total; 0 = default (2 slots of 4 GiB, or of the
-                                   whole pool's records if that is less): a transfer that fits a slot is one
-                                   copy launch and one DMA                                          */
+                                   whole pool's records if that is less; halved until it fits, down to
+                                   64 MiB, where device memory is short): a transfer that fits a slot is
+                                   one copy launch and one DMA                                      */
     uint32_t staging_slots;     /* ring depth, >= 1; 0 = default                                   */
     uint32_t max_grid;          /* cap on workgroups per gather/scatter launch; 0 = one per tile   */
     uint32_t direct_offload;    /* which path an offload takes: TC_PATH_AUTO (0, the default) = through device

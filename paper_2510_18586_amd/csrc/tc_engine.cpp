@@ -218,7 +218,23 @@ try {
             return e_ == hipErrorOutOfMemory && std::strstr(#expr, "Host") ? TC_ERR_HOST_NOMEM : TC_ERR_HIP; \
         }                                                                                     \
     } while (0)
-    HIP_OR_FAIL(hipMalloc(reinterpret_cast<void **>(&c->staging), slot_bytes * n_slots));
+    // The default ring is generous (see kDefaultSlotBytes).  Where the pool leaves less room than that, a default
+    // ring shrinks by halves (down to 64 MiB per slot) rather than failing; a size the caller asked for is taken
+    // literally.
+    for (;;) {
+        const hipError_t err = hipMalloc(reinterpret_cast<void **>(&c->staging), slot_bytes * n_slots);
+        if (err == hipSuccess) break;
+        c->staging = nullptr;
+        (void)hipGetLastError();
+        if (err != hipErrorOutOfMemory || e.opts.staging_bytes != 0 || slot_blocks < 2 || slot_bytes <= (64ull << 20)) {
+            std::fprintf(stderr, "tokencake_kv: hipMalloc of %llu B of staging failed: %s\n",
+                         static_cast<unsigned long long>(slot_bytes * n_slots), hipGetErrorString(err));
+            return TC_ERR_HIP;
+        }
+        slot_blocks = (slot_blocks + 1) / 2;
+        e.slot_blocks = uint32_t(slot_blocks);
+        slot_bytes = slot_blocks * e.rec;
+    }
     HIP_OR_FAIL(hipMalloc(reinterpret_cast<void **>(&e.ids_dev), ring_cap * sizeof(int32_t)));
     HIP_OR_FAIL(hipHostMalloc(reinterpret_cast<void **>(&e.ids_host), ring_cap * sizeof(int32_t), hipHostMallocDefault));
     if (e.arena_bytes)

@@ -632,3 +632,43 @@ def test_an_agent_of_4_GiB_is_one_launch_and_one_dma_by_default():
         assert st.d2h_bytes == n * rec and st.transfers_overlapped == 0
     finally:
         gp.close()
+
+
+def test_default_staging_shrinks_where_device_memory_is_short():
+    """With less device memory free than the default ring of 2 x 4 GiB, tc_create takes a smaller ring instead of
+    failing, and transfers are cut into more chunks; a ring size the caller asked for is taken literally."""
+    shape = W.CONFIGS[3].with_blocks(1100)                 # 4 MiB records, 4.3 GiB pool
+    gp = GpuPool(shape, seed=42, direct_offload=K.TC_PATH_STAGED, direct_upload=K.TC_PATH_STAGED)
+    gp.close()                                             # (the pool's memory is known to fit; now take the rest away)
+    torch.cuda.empty_cache()
+    free, _ = torch.cuda.mem_get_info()
+    leave = shape.pool_bytes + (3 << 30)                   # room for the pool and about 3 GiB more: not for 8 GiB of staging
+    hog = torch.empty(free - leave, dtype=torch.uint8, device=DEV)
+    gp = None
+    try:
+        pool = W.make_pool_device(shape, 42, DEV)
+        a = (shape.num_layers, shape.num_blocks, shape.page_bytes, shape.block_size, 0)
+        rc, ctx = K.tc_create(pool, None, *a, staging_bytes=8 << 30, staging_slots=2)
+        assert rc == K.TC_ERR_HIP and ctx is None          # asked for: not there
+        rc, ctx = K.tc_create(pool, None, *a, direct_offload=K.TC_PATH_STAGED, direct_upload=K.TC_PATH_STAGED, host_tail_div=1)
+        assert rc == K.TC_OK
+        try:
+            n, rec = 600, K.tc_record_bytes(ctx)
+            ids = W.pick_ids(W.rng_for(3, salt=42), shape.num_blocks, n)
+            K.check(K.tc_alloc_at(ctx, ids))
+            K.check(K.tc_set_profiling(ctx, 1))
+            host = pinned_bytes(n * rec)
+            stream = torch.cuda.Stream()
+            K.check(K.tc_offload(ctx, ids, host, stream))
+            K.check(K.tc_sync(ctx))
+            st = K.tc_stats(ctx)[1]
+            assert st.gather_launches >= 2 and st.d2h_bytes == n * rec      # a smaller ring: several chunks
+            P, pb = shape.planes, shape.page_bytes
+            pool_v = pool.view(P, shape.num_blocks, pb)
+            for j in (0, 299, 300, n - 1):
+                assert torch.equal(host[j * rec: j * rec + P * pb], pool_v[:, int(ids[j]), :].reshape(-1).cpu())
+        finally:
+            K.check(K.tc_destroy(ctx))
+    finally:
+        del hog
+        torch.cuda.empty_cache()
