@@ -647,6 +647,7 @@ def test_default_staging_shrinks_where_device_memory_is_short():
     gp = None
     try:
         pool = W.make_pool_device(shape, 42, DEV)
+        torch.cuda.synchronize()       # torch filled the pool on its own stream; the library's calls run on others
         a = (shape.num_layers, shape.num_blocks, shape.page_bytes, shape.block_size, 0)
         rc, ctx = K.tc_create(pool, None, *a, staging_bytes=8 << 30, staging_slots=2)
         assert rc == K.TC_ERR_HIP and ctx is None          # asked for: not there
