@@ -175,19 +175,24 @@ def variant(torch, K, pool, shape, pairs, link, note, steps=10, **opts):
         K.check(K.tc_alloc_at(ctx, dst))
         if k == 2:
             K.check(K.tc_set_profiling(ctx, 1))
-        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        # each transfer is retired before the next is enqueued: a DMA enqueued behind a running one is sometimes
+        # carried out at half rate by the runtime, which would be measured here as the path's own rate
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
         ev[0].record(stream)
         K.check(K.tc_offload(ctx, src, host, stream))
         ev[1].record(stream)
-        K.check(K.tc_upload(ctx, host, dst, None, stream))
-        ev[2].record(stream)
         K.check(K.tc_sync(ctx))
-        stream.synchronize()          # ev[2] is recorded after the transfer's own completion event
+        stream.synchronize()          # ev[1] is recorded after the transfer's own completion event
+        ev[2].record(stream)
+        K.check(K.tc_upload(ctx, host, dst, None, stream))
+        ev[3].record(stream)
+        K.check(K.tc_sync(ctx))
+        stream.synchronize()
         K.check(K.tc_free(ctx, src))
         K.check(K.tc_free(ctx, dst))
         if k >= 2:
             off.append(ev[0].elapsed_time(ev[1]))
-            up.append(ev[1].elapsed_time(ev[2]))
+            up.append(ev[2].elapsed_time(ev[3]))
     st = K.tc_stats(ctx)[1]
     K.check(K.tc_host_free(ctx, host))
     K.check(K.tc_destroy(ctx))
